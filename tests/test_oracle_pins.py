@@ -1,0 +1,281 @@
+"""Pins for the CPU oracle: things the mathematics fixes, independent of oracle/ itself."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import paging, sampling
+from oracle import transformer as otf
+from paper_2601_05475_amd import synth
+
+import bruteforce
+from golden_io import paper_values
+from helpers import oracle_config, small_shape
+
+
+# ---------------------------------------------------------------- whole forward pass
+@pytest.mark.parametrize("shape_kw", [
+    dict(L=1, d=8, Hq=2, Hkv=1, hd=4, F=12, V=16),
+    dict(L=2, d=16, Hq=4, Hkv=2, hd=4, F=12, V=32),
+    dict(L=2, d=12, Hq=6, Hkv=2, hd=2, F=10, V=20, base=500.0),
+])
+def test_forward_matches_bruteforce(shape_kw):
+    s = small_shape(**shape_kw)
+    w = synth.make_weights(s, seed=7)
+    # larger-than-init weights so that softmax and SiLU are far from their linear regime
+    for lw in w["layers"]:
+        for k in lw:
+            if not k.endswith("norm"):
+                lw[k] = lw[k] * 25.0
+    w["embed"] = w["embed"] * 50.0
+    toks = synth.tokens(11, 1, (11,), s.vocab)
+    got = otf.forward(oracle_config(s), w, toks)[0]
+    cfgd = dict(n_layers=s.n_layers, d_model=s.d_model, n_q_heads=s.n_q_heads,
+                n_kv_heads=s.n_kv_heads, head_dim=s.head_dim, rms_eps=s.rms_eps,
+                rope_base=s.rope_base)
+    want = np.array(bruteforce.forward(cfgd, w, list(toks)))
+    assert got.shape == want.shape
+    # non-trivial attention: some softmax row must be far from uniform
+    assert np.abs(want).max() > 1e-2
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-9 * max(1.0, np.abs(want).max()))
+
+
+def test_shared_prefix_equals_unshared():
+    s = small_shape(L=2, d=32, Hq=4, Hkv=2, hd=8, F=40, V=64)
+    cfg = oracle_config(s)
+    w = synth.make_weights(s, seed=3)
+    prefix = synth.tokens(5, 1, (9,), s.vocab)
+    suf = synth.tokens(5, 2, (3, 5), s.vocab)
+    plast, shared = otf.forward_shared(cfg, w, prefix, suf)
+    for b in range(3):
+        full = otf.forward_unshared(cfg, w, prefix, suf[b])
+        np.testing.assert_allclose(shared[b], full[len(prefix):], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(plast, full[len(prefix) - 1], rtol=0, atol=1e-12)
+
+
+def test_decode_equals_prefill_and_causality():
+    s = small_shape(L=2, d=32, Hq=4, Hkv=2, hd=8, F=40, V=64)
+    cfg = oracle_config(s)
+    w = synth.make_weights(s, seed=4)
+    toks = synth.tokens(6, 1, (10,), s.vocab)
+    full = otf.forward(cfg, w, toks)[0]
+    cache = None
+    for t in range(10):                       # token by token
+        lg, cache = otf.forward(cfg, w, toks[t:t + 1], cache)
+        np.testing.assert_allclose(lg[0], full[t], rtol=0, atol=1e-12)
+    toks2 = toks.copy()
+    toks2[7:] = (toks2[7:] + 1) % s.vocab     # later tokens do not influence earlier logits
+    full2 = otf.forward(cfg, w, toks2)[0]
+    np.testing.assert_array_equal(full[:7], full2[:7])
+    assert np.abs(full[7:] - full2[7:]).max() > 0
+
+
+def test_identical_candidates_give_identical_rows():
+    s = small_shape()
+    cfg = oracle_config(s)
+    w = synth.make_weights(s, seed=5)
+    prefix = synth.tokens(1, 1, (6,), s.vocab)
+    suf = np.tile(synth.tokens(1, 2, (1, 4), s.vocab), (3, 1))
+    _, out = otf.forward_shared(cfg, w, prefix, suf)
+    np.testing.assert_array_equal(out[0], out[1])
+    np.testing.assert_array_equal(out[0], out[2])
+
+
+# ---------------------------------------------------------------- RMSNorm closed forms
+def test_rmsnorm_closed_forms():
+    d, eps = 16, 1e-6
+    g = np.linspace(0.5, 1.5, d)
+    c = 3.0
+    np.testing.assert_allclose(otf.rmsnorm(np.full((1, d), c), g, eps)[0],
+                               g * c / math.sqrt(c * c + eps), rtol=1e-15)
+    a, j = -2.0, 5
+    x = np.zeros((1, d)); x[0, j] = a
+    y = otf.rmsnorm(x, g, eps)[0]
+    assert y[j] == pytest.approx(g[j] * a / math.sqrt(a * a / d + eps), rel=1e-15)
+    assert np.all(np.delete(y, j) == 0)
+    x = np.random.default_rng(0).normal(size=(3, d))
+    np.testing.assert_allclose(otf.rmsnorm(7.0 * x, g, 0.0), otf.rmsnorm(x, g, 0.0), rtol=1e-14)
+    # eps matters where it should: zero input stays zero, finite
+    assert np.all(otf.rmsnorm(np.zeros((1, d)), g, eps) == 0)
+
+
+# ---------------------------------------------------------------- RoPE closed forms
+def test_rope_closed_forms():
+    rng = np.random.default_rng(1)
+    hd, base = 8, 10000.0
+    z = rng.normal(size=(5, 3, hd))
+    np.testing.assert_array_equal(otf.rope(z, np.zeros(5, int), base), z)       # pos 0 identity
+    pos = np.array([0, 1, 7, 100, 4095])
+    r = otf.rope(z, pos, base)
+    np.testing.assert_allclose(np.linalg.norm(r, axis=-1), np.linalg.norm(z, axis=-1), rtol=1e-13)
+    # hd = 2: (1, 0) -> (cos pos, sin pos)
+    e = otf.rope(np.array([[[1.0, 0.0]]]).repeat(3, 0), np.array([1, 2, 3]), base)
+    np.testing.assert_allclose(e[:, 0, 0], np.cos([1, 2, 3]), atol=1e-15)
+    np.testing.assert_allclose(e[:, 0, 1], np.sin([1, 2, 3]), atol=1e-15)
+    # relative-position property
+    q, k = rng.normal(size=(1, 1, hd)), rng.normal(size=(1, 1, hd))
+    def dot(m, n):
+        return float(np.sum(otf.rope(q, [m], base) * otf.rope(k, [n], base)))
+    assert dot(9, 4) == pytest.approx(dot(105, 100), rel=1e-11)
+    assert abs(dot(9, 4) - dot(9, 5)) > 1e-3
+    # pairing: perturbing coordinate i changes only outputs i and i + hd/2
+    z1 = rng.normal(size=(1, 1, hd)); z2 = z1.copy(); z2[0, 0, 1] += 1.0
+    diff = np.abs(otf.rope(z1, [3], base) - otf.rope(z2, [3], base))[0, 0]
+    assert set(np.flatnonzero(diff > 0)) == {1, 1 + hd // 2}
+    # frequency of pair i is base^(-2i/hd): pair 1 of hd=8 at pos 1 rotates by base^-0.25
+    one = np.zeros((1, 1, hd)); one[0, 0, 1] = 1.0
+    out = otf.rope(one, [1], base)[0, 0]
+    assert out[1] == pytest.approx(math.cos(base ** -0.25), rel=1e-14)
+    assert out[1 + hd // 2] == pytest.approx(math.sin(base ** -0.25), rel=1e-14)
+
+
+# ---------------------------------------------------------------- attention invariants
+def test_attention_invariants():
+    rng = np.random.default_rng(2)
+    T, S, Hq, Hkv, hd = 3, 7, 4, 2, 8
+    q = rng.normal(size=(T, Hq, hd)); k = rng.normal(size=(S, Hkv, hd)); v = rng.normal(size=(S, Hkv, hd))
+    qpos = np.array([6, 6, 6]); kpos = np.arange(S)
+    p = otf.softmax_rows(rng.normal(size=(5, 9)) * 10)
+    assert np.abs(p.sum(-1) - 1).max() < 1e-12
+    # one visible key -> that value exactly
+    o = otf.attention(q, k, v, np.array([0, 0, 0]), kpos)
+    for a in range(Hq):
+        np.testing.assert_allclose(o[:, a], np.tile(v[0, a // 2], (T, 1)), rtol=1e-15)
+    # zero queries -> equal scores -> mean of the visible values
+    o = otf.attention(np.zeros_like(q), k, v, qpos, kpos)
+    np.testing.assert_allclose(o[0, 3], v[:, 1].mean(0), rtol=1e-13)
+    # GQA mapping: head a reads kv head a // G
+    v2 = v.copy(); v2[:, 1] += 1.0
+    d = otf.attention(q, k, v2, qpos, kpos) - otf.attention(q, k, v, qpos, kpos)
+    assert np.abs(d[:, :2]).max() == 0 and np.allclose(d[:, 2:], 1.0)
+    # scale 1/sqrt(hd): one query, two keys, closed form
+    q1 = np.zeros((1, 1, 4)); q1[0, 0, 0] = 2.0
+    k2 = np.zeros((2, 1, 4)); k2[0, 0, 0] = 1.0
+    v2 = np.array([[[1.0, 0, 0, 0]], [[0, 1.0, 0, 0]]])
+    o = otf.attention(q1, k2, v2, [1], [0, 1])[0, 0]
+    w0 = 1.0 / (1.0 + math.exp(-(2.0 * 1.0) / math.sqrt(4)))
+    np.testing.assert_allclose(o[:2], [w0, 1 - w0], rtol=1e-14)
+    # attention_one equals the batched routine
+    one = otf.attention_one(q[0, 1], k[:, 0], v[:, 0])
+    np.testing.assert_allclose(one, otf.attention(q, k, v, qpos, kpos)[0, 1], rtol=1e-13)
+
+
+def test_split_softmax_merge_identity():
+    """Any partition of the keys, merged by (max, sum, weighted value), is the full softmax."""
+    rng = np.random.default_rng(3)
+    S, hd = 37, 8
+    q = rng.normal(size=hd) * 3; k = rng.normal(size=(S, hd)); v = rng.normal(size=(S, hd))
+    want = otf.attention_one(q, k, v)
+    parts = [(0, 5), (5, 6), (6, 30), (30, 37)]
+    ms, ls, os_ = [], [], []
+    for a, b in parts:
+        s = k[a:b] @ q / math.sqrt(hd)
+        m = s.max(); e = np.exp(s - m)
+        ms.append(m); ls.append(e.sum()); os_.append(e @ v[a:b])
+    M = max(ms)
+    num = sum(np.exp(m - M) * o for m, o in zip(ms, os_))
+    den = sum(np.exp(m - M) * l for m, l in zip(ms, ls))
+    np.testing.assert_allclose(num / den, want, rtol=1e-13)
+
+
+def test_silu_and_linear():
+    assert otf.silu(np.array([0.0]))[0] == 0
+    assert otf.silu(np.array([40.0]))[0] == pytest.approx(40.0, rel=1e-15)
+    assert abs(otf.silu(np.array([-40.0]))[0]) < 1e-15
+    assert otf.silu(np.array([1.0]))[0] == pytest.approx(1 / (1 + math.exp(-1)), rel=1e-15)
+    x = np.array([[1.0, 2.0, 3.0]]); w = np.array([[1.0, 0, 0], [0, 0, 2.0]])   # [out][in]
+    np.testing.assert_array_equal(otf.linear(x, w), [[1.0, 6.0]])
+
+
+# ---------------------------------------------------------------- sampler
+def test_sampler_special_cases():
+    rng = np.random.default_rng(4)
+    lg = rng.normal(size=200).astype(np.float32)
+    top = int(np.argmax(lg))
+    assert sampling.sample(lg, 0.0, 50, 0.3)[0] == top
+    assert sampling.sample(lg, 0.8, 1, 0.9)[0] == top
+    assert sampling.sample(lg, 0.8, 50, 0.0)[0] == top                       # u = 0 -> top token
+    tok, ids, _ = sampling.sample(lg, 0.8, 50, np.float32(1 - 2 ** -24))
+    assert tok == ids[-1] and len(ids) == 50                                 # u -> 1: k-th token
+    assert list(ids) == sorted(range(200), key=lambda i: (-lg[i], i))[:50]
+    # ties: all equal -> floor(u k)-th lowest id
+    eq = np.zeros(64, np.float32)
+    for u in (0.0, 0.26, 0.5, 0.99):
+        assert sampling.sample(eq, 0.7, 10, u)[0] == int(u * 10)
+    assert sampling.sample(eq, 0.0, 10, 0.5)[0] == 0                          # argmax tie: lowest id
+    # full vocabulary when k <= 0 or k >= V
+    assert len(sampling.sample(lg, 1.0, 0, 0.5)[1]) == 200
+    assert len(sampling.sample(lg, 1.0, 500, 0.5)[1]) == 200
+    # determinism
+    assert sampling.sample(lg, 0.7, 50, 0.4321)[0] == sampling.sample(lg, 0.7, 50, 0.4321)[0]
+
+
+def test_sampler_two_logit_closed_form_and_frequencies():
+    pv = paper_values()
+    T = pv["temperature_reward_model"]
+    a, b = 1.3, 0.2
+    lg = np.array([b, a], np.float32)
+    p_top = 1.0 / (1.0 + math.exp(-(a - b) / T))
+    us = synth.uniforms(99, 1, (100000,))
+    picks = np.array([sampling.sample(lg, T, 2, u)[0] for u in us[:20000]])
+    frac = np.mean(picks == 1)
+    assert abs(frac - p_top) < 4 * math.sqrt(p_top * (1 - p_top) / 20000)
+    # threshold sits at the closed-form probability
+    assert sampling.sample(lg, T, 2, np.float32(p_top - 1e-4))[0] == 1
+    assert sampling.sample(lg, T, 2, np.float32(p_top + 1e-4))[0] == 0
+    # temperature really divides: at the generation temperature the top token is likelier
+    Tg = pv["temperature_generation"]
+    assert sampling.sample(lg, Tg, 2, np.float32(p_top + 1e-3))[0] == 1
+
+
+def test_sampler_top_k_restricts_support():
+    lg = np.arange(100, dtype=np.float32) * 0.01
+    us = synth.uniforms(5, 1, (2000,))
+    picks = {sampling.sample(lg, 1.0, 7, u)[0] for u in us}
+    assert picks == set(range(93, 100))
+
+
+# ---------------------------------------------------------------- scoring
+def test_reward_logprobs_and_score():
+    pv = paper_values()
+    labels = np.array(pv["reward_labels"])
+    rng = np.random.default_rng(5)
+    lg = rng.normal(size=50) * 3
+    lp_all = sampling.reward_logprobs(lg, np.arange(50))
+    assert abs(np.exp(lp_all).sum() - 1) < 1e-12
+    ids = np.array([3, 17, 4, 40, 9])
+    lp = sampling.reward_logprobs(lg, ids)
+    np.testing.assert_allclose(lp, lp_all[ids], rtol=0, atol=0)
+    # shifting all logits changes nothing
+    np.testing.assert_allclose(sampling.reward_logprobs(lg + 11.0, ids), lp, atol=1e-12)
+    # equal reward logits -> expectation of labels 0..4 is 2
+    lg2 = lg.copy(); lg2[ids] = 0.7
+    assert sampling.expected_value(sampling.reward_logprobs(lg2, ids), labels, 1.0) == pytest.approx(2.0, abs=1e-14)
+    # one dominant label -> its value
+    lg3 = lg.copy(); lg3[ids[3]] = 60.0
+    assert sampling.expected_value(sampling.reward_logprobs(lg3, ids), labels, 1.0) == pytest.approx(3.0, abs=1e-12)
+    # two labels, closed form with temperature
+    Ts = pv["temperature_reward_model"]
+    got = sampling.expected_value(np.array([math.log(0.2), math.log(0.1)]), np.array([1.0, 4.0]), Ts)
+    p1 = 0.2 ** (1 / Ts) / (0.2 ** (1 / Ts) + 0.1 ** (1 / Ts))
+    assert got == pytest.approx(p1 * 1 + (1 - p1) * 4, rel=1e-13)
+
+
+def test_rank_with_ties():
+    assert list(sampling.rank(np.array([0.5, 2.0, 0.5, 3.0, 2.0]))) == [3, 1, 4, 0, 2]
+    assert list(sampling.rank(np.array([1.0]))) == [0]
+
+
+# ---------------------------------------------------------------- paging
+def test_page_table_reference_small_example():
+    # 3 candidates, page of 2 tokens, 5 steps: pages handed out in candidate order per boundary
+    t = paging.page_tables(3, 5, 2, range(100))
+    assert t.tolist() == [[0, 3, 6], [1, 4, 7], [2, 5, 8]]
+    perm = [9, 8, 7, 6, 5, 4, 3, 2, 1, 0]
+    t = paging.page_tables(2, 3, 2, perm)
+    assert t.tolist() == [[9, 7], [8, 6]]
+    assert paging.slot_of(t, 1, 2, 2) == (6, 0)
+    assert paging.page_tables(2, 0, 4, range(4)).shape == (2, 0)
+    # exactly one page when n_steps == page size; two when one more
+    assert paging.page_tables(1, 4, 4, range(4)).tolist() == [[0]]
+    assert paging.page_tables(1, 5, 4, range(4)).tolist() == [[0, 1]]
