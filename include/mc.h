@@ -1,0 +1,247 @@
+/*
+ * mc.h - C ABI of the MI355X shared-prefix candidate decoding / scoring library.
+ *
+ * The computation is the LLM step inside the MaxCode search loop: a frozen
+ * autoregressive policy proposes several candidates from ONE search state (Sec. 3,
+ * "The Markov Decision Process": stochastic token sampling yields M distinct
+ * candidates for the same state; Sec. 3.2, CUDA-LLM reformulation: k candidates per
+ * state), and a generative value model reranks candidate states by the expected
+ * value of a categorical reward-to-go (Sec. 3.3, "Generative Value Function Guided
+ * Search").  All candidates share the prompt (problem, trajectory, critiques, best
+ * result so far), so its keys/values are computed once and read once per step.
+ *
+ * Conventions
+ *  - Every function returns an mc_status (0 = ok, negative = error) unless noted.
+ *    mc_last_error() gives a message for the last failure on the calling thread.
+ *  - "host" pointers are ordinary CPU memory, read or written during the call only.
+ *    "device" pointers are HIP device memory on the session's / call's device.
+ *  - The library never calls hipMalloc for device memory: models and sessions live
+ *    inside arenas supplied by the caller (mc_arena), sized by mc_model_bytes /
+ *    mc_session_bytes.  The caller keeps ownership and frees them after destroy.
+ *  - All work is enqueued on the arena's HIP stream.  Calls with host outputs return
+ *    after the outputs are valid; calls without host outputs are asynchronous.
+ *  - On error no output is valid and the session keeps its pre-call state
+ *    (MC_ERR_DEVICE excepted).  Handles are not thread-safe.
+ *  - Matrices are row-major [out_features][in_features]; element type is the
+ *    model's dtype (MC_F32: float, MC_BF16: 16-bit bfloat16 bit patterns).
+ */
+#ifndef MC_H_
+#define MC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mc_model mc_model;     /* immutable weights + shape, on device      */
+typedef struct mc_session mc_session; /* shared prefix KV + candidates' KV pages   */
+
+typedef enum { MC_F32 = 0, MC_BF16 = 1 } mc_dtype;
+
+typedef enum {
+  MC_OK = 0,
+  MC_ERR_INVALID = -1,     /* bad argument (null, out of range, non-finite)       */
+  MC_ERR_STATE = -2,       /* call out of order (decode before prefill, ...)      */
+  MC_ERR_OOM = -3,         /* arena or page pool too small                        */
+  MC_ERR_DEVICE = -4,      /* a HIP call failed                                   */
+  MC_ERR_UNSUPPORTED = -5  /* shape or option the kernels do not cover            */
+} mc_status;
+
+/* Decoder shape: pre-norm blocks of grouped-query attention with rotary position
+ * embedding (pairs (i, i + head_dim/2), angle pos * rope_base^(-2i/head_dim)) and a
+ * SwiGLU feed-forward, RMSNorm (x * g / sqrt(mean(x^2) + rms_eps)), no biases,
+ * untied LM head.  Query head a reads KV head a / (n_q_heads / n_kv_heads). */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype; /* mc_dtype of weights, activations and KV */
+} mc_config;
+
+/* Weight pointers (host or device memory; copied during mc_model_create and free
+ * to release afterwards).  Per-layer members are arrays of n_layers pointers. */
+typedef struct {
+  const void *embed;              /* [vocab][d_model]                              */
+  const void *const *attn_norm;   /* [d_model]                                     */
+  const void *const *wq;          /* [n_q_heads*head_dim][d_model]                 */
+  const void *const *wk;          /* [n_kv_heads*head_dim][d_model]                */
+  const void *const *wv;          /* [n_kv_heads*head_dim][d_model]                */
+  const void *const *wo;          /* [d_model][n_q_heads*head_dim]                 */
+  const void *const *ffn_norm;    /* [d_model]                                     */
+  const void *const *w_gate;      /* [d_ffn][d_model]                              */
+  const void *const *w_up;        /* [d_ffn][d_model]                              */
+  const void *const *w_down;      /* [d_model][d_ffn]                              */
+  const void *final_norm;         /* [d_model]                                     */
+  const void *lm_head;            /* [vocab][d_model]                              */
+} mc_weights;
+
+/* Device memory owned by the caller (e.g. a torch tensor) plus the stream to use. */
+typedef struct {
+  void *dev_base;     /* device pointer, 256-byte aligned                         */
+  size_t dev_bytes;
+  void *hip_stream;   /* hipStream_t; NULL = the default stream                   */
+  int32_t device;     /* HIP device ordinal                                       */
+} mc_arena;
+
+typedef struct {
+  int32_t max_prefix;   /* longest shared prefix, tokens                          */
+  int32_t max_cands;    /* most candidates B                                      */
+  int32_t max_suffix;   /* longest per-candidate suffix (decode steps / scoring)  */
+  int32_t page_tokens;  /* KV page size in tokens: power of two, 4..128           */
+  int32_t chunk_rows;   /* rows processed at once by prefill/scoring (0 = default)*/
+} mc_session_params;
+
+/* ---- lifecycle ------------------------------------------------------------------ */
+size_t mc_model_bytes(const mc_config *cfg);                   /* 0 if cfg is invalid */
+int mc_model_create(const mc_config *cfg, const mc_weights *w, const mc_arena *arena,
+                    mc_model **out);
+void mc_model_destroy(mc_model *m);
+
+size_t mc_session_bytes(const mc_config *cfg, const mc_session_params *p);
+int mc_session_create(const mc_model *m, const mc_arena *arena, const mc_session_params *p,
+                      mc_session **out);
+void mc_session_destroy(mc_session *s);
+/* Drop all candidates (their pages return to the free list in its initial order) and
+ * keep the prefix; the next mc_sample draws again from the prefix's last position. */
+int mc_session_reset_candidates(mc_session *s);
+/* Wait for everything enqueued by this session. */
+int mc_session_sync(mc_session *s);
+
+/* ---- the four calls -------------------------------------------------------------- */
+
+/* 1. One context -> shared KV (policy paragraph of Sec. 3: all candidates of a step
+ *    are conditioned on the same state).  tokens: host, n_tokens in [1, max_prefix].
+ *    Replaces any earlier prefix and drops all candidates.  Leaves the logits of the
+ *    last prefix position on the device for mc_sample.  Asynchronous. */
+int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens);
+
+/* 2. One new token per candidate: appends its K/V to the candidate's current page
+ *    and leaves logits [n_cands][vocab] on the device.  tokens: host [n_cands], or
+ *    NULL to consume the tokens drawn by the latest mc_sample without leaving the
+ *    device.  n_cands is fixed by the first call after a prefill/reset.
+ *    Asynchronous. */
+int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_cands);
+
+/* 3. Draw the next token of every candidate from the logits left by call 1 (one row,
+ *    shared by all candidates) or call 2 (one row each).  With z = logit / T, keep
+ *    the top_k entries under the order (z descending, id ascending), softmax over
+ *    them (sums taken left to right in that order, fp32) and pick the first entry
+ *    whose cumulative probability exceeds uniforms[b]; the last entry if none does.
+ *    temperature <= 0 or top_k == 1: argmax (lowest id on ties).  top_k <= 0 or
+ *    >= vocab: whole vocabulary (supported up to MC_MAX_TOP_K entries).
+ *    uniforms: host [n_cands], each in [0, 1).  out_tokens: host [n_cands] or NULL
+ *    (NULL keeps the call asynchronous).  out_topk_ids: host [n_cands][k] sorted by
+ *    that order, or NULL. */
+int mc_sample(mc_session *s, int32_t n_cands, float temperature, int32_t top_k,
+              const float *uniforms, int32_t *out_tokens, int32_t *out_topk_ids);
+
+/* 4. Rerank candidates by the generative reward-to-go score (Sec. 3.3): run each
+ *    candidate's suffix against the shared prefix, take the log-probabilities of the
+ *    reward tokens (log-softmax over the whole vocabulary) at its last position,
+ *    score = sum_r reward_values[r] * softmax_r(logprob_r / score_temperature), and
+ *    rank by (score descending, candidate index ascending).  Does not touch the
+ *    candidates' decode state.  suffix_tokens: host [n_cands][max_len] (entries past
+ *    suffix_lens[b] ignored); suffix_lens[b] in [1, max_len]; reward_ids distinct.
+ *    Outputs: host out_logprobs [n_cands][n_reward], out_scores [n_cands],
+ *    out_rank [n_cands] (best first); any may be NULL. */
+int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
+                        const int32_t *suffix_lens, int32_t n_cands, int32_t max_len,
+                        const int32_t *reward_ids, const float *reward_values,
+                        int32_t n_reward, float score_temperature, float *out_logprobs,
+                        float *out_scores, int32_t *out_rank);
+
+#define MC_MAX_TOP_K 4096
+#define MC_MAX_REWARD 64
+
+/* ---- inspection hooks (tests and tools; not on the fast path) -------------------- */
+/* Copy the pending logits to host as fp32: n_rows rows of vocab floats (1 row after
+ * a prefill, n_cands after a decode step, n_cands after scoring). */
+int mc_debug_copy_logits(mc_session *s, float *out, int32_t n_rows);
+/* Page ids of every candidate's allocated suffix pages.  out: host
+ * [max_cands][max_pages] (unused entries -1), n_pages: host [max_cands]. */
+int mc_debug_page_table(mc_session *s, int32_t *out, int32_t *n_pages, int32_t max_pages);
+/* Replace the free list's order (a permutation of 0..n-1, n = pool size); only
+ * allowed while no candidate holds a page.  mc_debug_pool_pages gives n. */
+int mc_debug_set_free_list(mc_session *s, const int32_t *perm, int32_t n);
+int32_t mc_debug_pool_pages(const mc_session *s);
+/* Override the number of key-axis splits used for the shared prefix (0 = automatic). */
+int mc_debug_set_prefix_splits(mc_session *s, int32_t n_splits);
+const char *mc_last_error(void);
+
+/* ---- timing of one kernel class inside a session --------------------------------- */
+typedef enum {
+  MC_K_NONE = 0, MC_K_EMBED, MC_K_ADD_RMSNORM, MC_K_LINEAR_QKV, MC_K_ROPE_KV,
+  MC_K_ATTN_DECODE, MC_K_ATTN_MERGE, MC_K_ATTN_PREFILL, MC_K_LINEAR_O,
+  MC_K_LINEAR_GATE_UP, MC_K_LINEAR_DOWN, MC_K_LINEAR_LM_HEAD, MC_K_SAMPLE,
+  MC_K_REWARD, MC_K_COUNT
+} mc_kernel_class;
+/* Bracket every `stride`-th launch of one kernel class with HIP events on the session
+ * stream (kernel_class = MC_K_NONE switches it off; at most 8192 launches recorded). */
+int mc_profile_begin(mc_session *s, int32_t kernel_class, int32_t stride);
+/* Synchronise, then report how many launches were timed and their total duration. */
+int mc_profile_end(mc_session *s, int32_t *n_timed, double *total_ms);
+
+/* ---- single operations on device buffers (kernel-level tests and measurement) ---- */
+/* All pointers below are DEVICE pointers unless marked host; `stream` is a hipStream_t
+ * (NULL = default).  `dtype` selects float or bf16 for buffers marked (T). */
+
+/* Residual update + RMSNorm: x[r][:] += sum_s partials[s][r][:] (n_partials may be 0),
+ * then h[r][:] = (T)(x * gain / sqrt(mean(x^2) + eps)).  x: fp32 [rows][d], in/out. */
+int mc_op_add_rmsnorm(void *stream, int32_t dtype, int32_t rows, int32_t d, float *x,
+                      const float *partials, int32_t n_partials, const void *gain /*(T)[d]*/,
+                      float eps, void *h_out /*(T)[rows][d]*/);
+
+/* out[s][m][n] = sum over the s-th K range of a[m][k] * w[n][k]; n_splits partial sums
+ * (fp32) that add up to a * w^T.  a: (T)[M][K], w: (T)[N][K], out: fp32 [n_splits][M][N]. */
+int mc_op_linear(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void *a,
+                 const void *w, float *out, int32_t n_splits);
+
+/* out[m][n] = (T)( silu(a . w_gate[n]) * (a . w_up[n]) ).  out: (T)[M][N]. */
+int mc_op_linear_swiglu(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K,
+                        const void *a, const void *w_gate, const void *w_up, void *out);
+
+/* Sum the n_splits partial QKV rows, rotate q and k of row r by position row_pos[r],
+ * store q as (T)[rows][Hq][hd] and write k, v of row r into KV page row_page[r] at
+ * offset row_off[r].  K pages are (T)[Hkv][page_tokens][hd]; V pages are stored
+ * transposed, (T)[Hkv][hd][page_tokens].  qkv: fp32 [n_splits][rows][(Hq+2Hkv)*hd]. */
+int mc_op_rope_kv_write(void *stream, int32_t dtype, int32_t rows, int32_t n_q_heads,
+                        int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens,
+                        float rope_base, const float *qkv, int32_t n_splits,
+                        const int32_t *row_pos, const int32_t *row_page,
+                        const int32_t *row_off, void *q_out, void *k_pages, void *v_pages);
+
+/* Decode attention for n_cands candidates in lock-step: candidate b attends to the
+ * prefix_len keys of the shared prefix (pages 0.. of k_prefix/v_prefix, in order) and
+ * to its own suffix_len keys (pages page_table[b][0..] of k_suffix/v_suffix).
+ * q, out: (T)[n_cands][Hq][hd].  workspace: fp32 scratch of mc_op_attention_decode_ws
+ * bytes.  prefix_splits: key-axis splits of the prefix (0 = automatic). */
+size_t mc_op_attention_decode_ws(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
+                                 int32_t head_dim, int32_t prefix_len, int32_t suffix_len,
+                                 int32_t page_tokens);
+int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t n_q_heads,
+                           int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens,
+                           int32_t prefix_len, int32_t suffix_len, const void *q,
+                           const void *k_prefix, const void *v_prefix, const void *k_suffix,
+                           const void *v_suffix, const int32_t *page_table,
+                           int32_t table_stride, int32_t prefix_splits, void *workspace,
+                           size_t workspace_bytes, void *out);
+
+/* Sampling from fp32 logits [rows][vocab] (row_stride 0 = every candidate reads row 0).
+ * uniforms: device [n_cands].  out_tokens: device [n_cands]; out_topk: device
+ * [n_cands][k] or NULL.  Same rule as mc_sample. */
+int mc_op_sample(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
+                 size_t row_stride, float temperature, int32_t top_k, const float *uniforms,
+                 int32_t *out_tokens, int32_t *out_topk);
+
+/* Reward log-probs, expected-value scores and ranking from fp32 logits [n_cands][vocab].
+ * reward_ids, reward_values: device [n_reward].  Outputs: device. */
+int mc_op_reward_score(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
+                       const int32_t *reward_ids, const float *reward_values,
+                       int32_t n_reward, float score_temperature, float *out_logprobs,
+                       float *out_scores, int32_t *out_rank);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MC_H_ */

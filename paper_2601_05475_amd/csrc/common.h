@@ -1,0 +1,122 @@
+// Shared declarations of the library's translation units (HIP, gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mc.h"
+
+namespace mc {
+
+typedef unsigned short bf16_t;   // bfloat16 bit pattern
+
+__host__ __device__ inline float bf16_to_f32(bf16_t b) {
+  union { uint32_t u; float f; } v;
+  v.u = (uint32_t)b << 16;
+  return v.f;
+}
+
+// round to nearest, ties to even; NaN stays NaN
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } v;
+  v.f = f;
+  if ((v.u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((v.u >> 16) | 0x40u);
+  uint32_t lsb = (v.u >> 16) & 1u;
+  return (bf16_t)((v.u + 0x7FFFu + lsb) >> 16);
+}
+
+template <typename T> struct Cvt;
+template <> struct Cvt<float> {
+  __host__ __device__ static float to_f32(float v) { return v; }
+  __host__ __device__ static float from_f32(float v) { return v; }
+};
+template <> struct Cvt<bf16_t> {
+  __host__ __device__ static float to_f32(bf16_t v) { return bf16_to_f32(v); }
+  __host__ __device__ static bf16_t from_f32(float v) { return f32_to_bf16(v); }
+};
+
+// ---- error plumbing -----------------------------------------------------------------
+void set_error(const char *fmt, ...);
+#define MC_FAIL(code, ...)            \
+  do {                                \
+    ::mc::set_error(__VA_ARGS__);     \
+    return (code);                    \
+  } while (0)
+#define MC_HIP(expr)                                                              \
+  do {                                                                            \
+    hipError_t e__ = (expr);                                                      \
+    if (e__ != hipSuccess)                                                        \
+      MC_FAIL(MC_ERR_DEVICE, "%s failed: %s", #expr, hipGetErrorString(e__));     \
+  } while (0)
+#define MC_TRY(expr)                  \
+  do {                                \
+    int s__ = (expr);                 \
+    if (s__ != MC_OK) return s__;     \
+  } while (0)
+
+// ---- geometry of one KV page ---------------------------------------------------------
+// K page: [Hkv][page_tokens][hd]; V page: [Hkv][hd][page_tokens] (transposed so that the
+// probability-times-value contraction reads keys contiguously).  Both have this many elements.
+inline size_t page_elems(int n_kv_heads, int head_dim, int page_tokens) {
+  return (size_t)n_kv_heads * head_dim * page_tokens;
+}
+
+// ---- kernel launchers (defined in kernels_*.hip) -----------------------------------
+// Every launcher validates nothing: callers (runtime.cpp, ops.cpp) check shapes first.
+
+struct AttnArgs {
+  const void *q;                 // (T)[rows][Hq][hd]
+  const void *k_prefix, *v_prefix, *k_suffix, *v_suffix;   // page pools of this layer
+  const int32_t *row_pos;        // [rows] absolute position of each query row
+  const int32_t *row_tab;        // [rows] page-table row of the query's sequence (unused if no suffix)
+  const int32_t *page_table;     // [*][table_stride] suffix page ids
+  int32_t table_stride;
+  int32_t rows, n_q_heads, n_kv_heads, head_dim, page_tokens;
+  int32_t prefix_len;            // keys at positions < prefix_len live in prefix pages pos / page_tokens
+  void *out;                     // (T)[rows][Hq][hd]
+};
+
+struct DecodeAttnArgs {
+  const void *q;                 // (T)[B][Hq][hd]
+  const void *k_prefix, *v_prefix, *k_suffix, *v_suffix;
+  const int32_t *page_table;
+  int32_t table_stride;
+  int32_t n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens;
+  int32_t prefix_len, suffix_len;
+  int32_t prefix_splits;         // 0 = automatic
+  void *workspace;
+  size_t workspace_bytes;
+  void *out;
+};
+
+int launch_embed(hipStream_t st, int dtype, int rows, int d, const int32_t *tokens,
+                 const void *table, float *x);
+int launch_add_rmsnorm(hipStream_t st, int dtype, int rows, int d, float *x, const float *partials,
+                       int n_partials, const void *gain, float eps, void *h_out);
+int launch_gather_rows(hipStream_t st, int rows, int d, const float *x, const int32_t *idx,
+                       float *out);
+int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a, const void *w,
+                  float *out, int n_splits);
+int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
+                         const void *wg, const void *wu, void *out);
+int launch_rope_kv(hipStream_t st, int dtype, int rows, int Hq, int Hkv, int hd, int page_tokens,
+                   double rope_base, const float *qkv, int n_splits, const int32_t *row_pos,
+                   const int32_t *row_page, const int32_t *row_off, void *q_out, void *k_pages,
+                   void *v_pages);
+int launch_attention_generic(hipStream_t st, int dtype, const AttnArgs &a);
+size_t decode_attention_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int prefix_len,
+                                 int suffix_len, int page_tokens);
+int launch_attention_decode(hipStream_t st, int dtype, const DecodeAttnArgs &a);
+int launch_sample(hipStream_t st, int n_cands, int vocab, const float *logits, size_t row_stride,
+                  float temperature, int top_k, const float *uniforms, int32_t *out_tokens,
+                  int32_t *out_topk);
+int launch_reward_score(hipStream_t st, int n_cands, int vocab, const float *logits,
+                        const int32_t *reward_ids, const float *reward_values, int n_reward,
+                        float score_temperature, float *out_logprobs, float *out_scores,
+                        int32_t *out_rank);
+
+// number of K-axis splits the linear kernels use for an [M x N x K] product
+int linear_auto_splits(int dtype, int M, int N, int K);
+
+}  // namespace mc

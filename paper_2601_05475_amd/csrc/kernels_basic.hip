@@ -1,0 +1,600 @@
+// Plain-ALU kernels: embedding, residual + RMSNorm, RoPE + KV page write, a generic
+// tiled linear layer, a generic attention kernel, sampling, reward scoring.
+// They serve every dtype and shape; the bf16 MFMA kernels in kernels_mfma.hip take over
+// the large contractions when the shape allows.
+#include "common.h"
+
+namespace mc {
+
+// ------------------------------------------------------------------ block reductions
+__device__ inline float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ inline double wave_sum_d(double v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// sum over a block of up to 1024 threads; every thread gets the result; fixed order
+template <typename F>
+__device__ inline F block_sum(F v, F *scratch /* >= 16 */) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  F t = 0;
+  for (int w = 0; w < nw; ++w) t += scratch[w];
+  return t;
+}
+__device__ inline float block_max(float v, float *scratch) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_max(v);
+  __syncthreads();
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  float t = scratch[0];
+  for (int w = 1; w < nw; ++w) t = fmaxf(t, scratch[w]);
+  return t;
+}
+
+// ------------------------------------------------------------------ embedding gather
+template <typename T>
+__global__ void embed_kernel(int d, const int32_t *__restrict__ tok, const T *__restrict__ table,
+                             float *__restrict__ x) {
+  const int r = blockIdx.x;
+  const T *src = table + (size_t)tok[r] * d;
+  float *dst = x + (size_t)r * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = Cvt<T>::to_f32(src[i]);
+}
+
+int launch_embed(hipStream_t st, int dtype, int rows, int d, const int32_t *tokens,
+                 const void *table, float *x) {
+  if (rows <= 0) return MC_OK;
+  if (dtype == MC_F32)
+    embed_kernel<float><<<rows, 256, 0, st>>>(d, tokens, (const float *)table, x);
+  else
+    embed_kernel<bf16_t><<<rows, 256, 0, st>>>(d, tokens, (const bf16_t *)table, x);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+// ------------------------------------------------------------------ residual + RMSNorm
+// x[r] += sum_s partials[s][r];  h[r] = x[r] * gain / sqrt(mean(x[r]^2) + eps)
+template <typename T>
+__global__ __launch_bounds__(256) void add_rmsnorm_kernel(
+    int d, float *__restrict__ x, const float *__restrict__ partials, int n_partials,
+    size_t pstride, const T *__restrict__ gain, float eps, T *__restrict__ h) {
+  __shared__ float scratch[16];
+  const size_t row = (size_t)blockIdx.x * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = x[row + i];
+    for (int s = 0; s < n_partials; ++s) v += partials[s * pstride + row + i];
+    if (n_partials) x[row + i] = v;
+    ss += v * v;
+  }
+  ss = block_sum<float>(ss, scratch);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256)
+    h[row + i] = Cvt<T>::from_f32(x[row + i] * inv * Cvt<T>::to_f32(gain[i]));
+}
+
+int launch_add_rmsnorm(hipStream_t st, int dtype, int rows, int d, float *x, const float *partials,
+                       int n_partials, const void *gain, float eps, void *h_out) {
+  if (rows <= 0) return MC_OK;
+  const size_t ps = (size_t)rows * d;
+  if (dtype == MC_F32)
+    add_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps,
+                                                    (const float *)gain, eps, (float *)h_out);
+  else
+    add_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps,
+                                                     (const bf16_t *)gain, eps, (bf16_t *)h_out);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+__global__ void gather_rows_kernel(int d, const float *__restrict__ x,
+                                   const int32_t *__restrict__ idx, float *__restrict__ out) {
+  const float *src = x + (size_t)idx[blockIdx.x] * d;
+  float *dst = out + (size_t)blockIdx.x * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = src[i];
+}
+
+int launch_gather_rows(hipStream_t st, int rows, int d, const float *x, const int32_t *idx,
+                       float *out) {
+  if (rows <= 0) return MC_OK;
+  gather_rows_kernel<<<rows, 256, 0, st>>>(d, x, idx, out);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+// ------------------------------------------------------------------ generic linear layer
+// out[s][m][n] = sum_{k in split s} a[m][k] * w[n][k]; 64x64 tile, 16-deep slabs, 4x4 per thread.
+// SWIGLU: two weight matrices, out[m][n] = silu(a.wg[n]) * (a.wu[n]) in the model dtype.
+template <typename T, bool SWIGLU>
+__global__ __launch_bounds__(256) void linear_generic_kernel(
+    int M, int N, int K, int k_per_split, const T *__restrict__ a, const T *__restrict__ w,
+    const T *__restrict__ w2, float *__restrict__ out, T *__restrict__ out_t) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Ws[BK][BN + 4];
+  __shared__ float Us[SWIGLU ? BK : 1][BN + 4];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN, split = blockIdx.z;
+  const int k_begin = split * k_per_split;
+  const int k_end = min(K, k_begin + k_per_split);
+  float acc[4][4] = {}, acc2[4][4] = {};
+  const int lr = tid >> 2, lk = (tid & 3) * 4;   // each thread stages 4 consecutive k of one row
+  for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = k0 + lk + j;
+      const bool kin = k < k_end;
+      As[lk + j][lr] = (kin && m0 + lr < M) ? Cvt<T>::to_f32(a[(size_t)(m0 + lr) * K + k]) : 0.f;
+      Ws[lk + j][lr] = (kin && n0 + lr < N) ? Cvt<T>::to_f32(w[(size_t)(n0 + lr) * K + k]) : 0.f;
+      if (SWIGLU)
+        Us[lk + j][lr] = (kin && n0 + lr < N) ? Cvt<T>::to_f32(w2[(size_t)(n0 + lr) * K + k]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float av[4], wv[4], uv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        av[i] = As[kk][ty * 4 + i];
+        wv[i] = Ws[kk][tx * 4 + i];
+        if (SWIGLU) uv[i] = Us[kk][tx * 4 + i];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[i][j] += av[i] * wv[j];
+          if (SWIGLU) acc2[i][j] += av[i] * uv[j];
+        }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      if (SWIGLU) {
+        const float g = acc[i][j];
+        out_t[(size_t)m * N + n] = Cvt<T>::from_f32(g / (1.0f + expf(-g)) * acc2[i][j]);
+      } else {
+        out[((size_t)split * M + m) * N + n] = acc[i][j];
+      }
+    }
+  }
+}
+
+int launch_linear_generic(hipStream_t st, int dtype, int M, int N, int K, const void *a,
+                          const void *w, float *out, int n_splits) {
+  if (M <= 0 || N <= 0) return MC_OK;
+  int kps = (K + n_splits - 1) / n_splits;
+  kps = (kps + 15) / 16 * 16;
+  dim3 grid((N + 63) / 64, (M + 63) / 64, n_splits);
+  if (dtype == MC_F32)
+    linear_generic_kernel<float, false><<<grid, 256, 0, st>>>(
+        M, N, K, kps, (const float *)a, (const float *)w, nullptr, out, nullptr);
+  else
+    linear_generic_kernel<bf16_t, false><<<grid, 256, 0, st>>>(
+        M, N, K, kps, (const bf16_t *)a, (const bf16_t *)w, nullptr, out, nullptr);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+int launch_linear_swiglu_generic(hipStream_t st, int dtype, int M, int N, int K, const void *a,
+                                 const void *wg, const void *wu, void *out) {
+  if (M <= 0 || N <= 0) return MC_OK;
+  dim3 grid((N + 63) / 64, (M + 63) / 64, 1);
+  if (dtype == MC_F32)
+    linear_generic_kernel<float, true><<<grid, 256, 0, st>>>(
+        M, N, K, (K + 15) / 16 * 16, (const float *)a, (const float *)wg, (const float *)wu,
+        nullptr, (float *)out);
+  else
+    linear_generic_kernel<bf16_t, true><<<grid, 256, 0, st>>>(
+        M, N, K, (K + 15) / 16 * 16, (const bf16_t *)a, (const bf16_t *)wg, (const bf16_t *)wu,
+        nullptr, (bf16_t *)out);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+// ------------------------------------------------------------------ RoPE + KV page write
+// One block per (row, head).  Heads 0..Hq-1 are queries, then Hkv key heads, then Hkv value
+// heads.  The angle pos * base^(-2i/hd) and its sine/cosine are taken in double.
+template <typename T>
+__global__ __launch_bounds__(64) void rope_kv_kernel(
+    int rows, int Hq, int Hkv, int hd, int pg, double rope_base,
+    const float *__restrict__ qkv, int n_splits, const int32_t *__restrict__ row_pos,
+    const int32_t *__restrict__ row_page, const int32_t *__restrict__ row_off,
+    T *__restrict__ q_out, T *__restrict__ k_pages, T *__restrict__ v_pages) {
+  const int r = blockIdx.x, h = blockIdx.y;
+  const int nqkv = (Hq + 2 * Hkv) * hd, half = hd >> 1;
+  const size_t sstride = (size_t)rows * nqkv;
+  const float *src = qkv + (size_t)r * nqkv + (size_t)h * hd;
+  const size_t pelems = (size_t)Hkv * hd * pg;
+  if (h < Hq + Hkv) {
+    const double pos = (double)row_pos[r];
+    T *dst;
+    if (h < Hq) {
+      dst = q_out + ((size_t)r * Hq + h) * hd;
+    } else {
+      dst = k_pages + (size_t)row_page[r] * pelems + ((size_t)(h - Hq) * pg + row_off[r]) * hd;
+    }
+    for (int i = threadIdx.x; i < half; i += 64) {
+      float lo = 0.f, hi = 0.f;
+      for (int s = 0; s < n_splits; ++s) {
+        lo += src[s * sstride + i];
+        hi += src[s * sstride + i + half];
+      }
+      double sn, cs;
+      sincos(pos * pow(rope_base, -2.0 * (double)i / (double)hd), &sn, &cs);
+      dst[i] = Cvt<T>::from_f32((float)((double)lo * cs - (double)hi * sn));
+      dst[i + half] = Cvt<T>::from_f32((float)((double)hi * cs + (double)lo * sn));
+    }
+  } else {
+    const int kvh = h - Hq - Hkv;
+    T *dst = v_pages + (size_t)row_page[r] * pelems + (size_t)kvh * hd * pg + row_off[r];
+    for (int i = threadIdx.x; i < hd; i += 64) {
+      float v = 0.f;
+      for (int s = 0; s < n_splits; ++s) v += src[s * sstride + i];
+      dst[(size_t)i * pg] = Cvt<T>::from_f32(v);
+    }
+  }
+}
+
+int launch_rope_kv(hipStream_t st, int dtype, int rows, int Hq, int Hkv, int hd, int page_tokens,
+                   double rope_base, const float *qkv, int n_splits, const int32_t *row_pos,
+                   const int32_t *row_page, const int32_t *row_off, void *q_out, void *k_pages,
+                   void *v_pages) {
+  if (rows <= 0) return MC_OK;
+  dim3 grid(rows, Hq + 2 * Hkv);
+  if (dtype == MC_F32)
+    rope_kv_kernel<float><<<grid, 64, 0, st>>>(rows, Hq, Hkv, hd, page_tokens, rope_base, qkv,
+                                               n_splits, row_pos, row_page, row_off,
+                                               (float *)q_out, (float *)k_pages, (float *)v_pages);
+  else
+    rope_kv_kernel<bf16_t><<<grid, 64, 0, st>>>(rows, Hq, Hkv, hd, page_tokens, rope_base, qkv,
+                                                n_splits, row_pos, row_page, row_off,
+                                                (bf16_t *)q_out, (bf16_t *)k_pages,
+                                                (bf16_t *)v_pages);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+// ------------------------------------------------------------------ generic attention
+// One wave per (query row, query head).  Keys 0..pos of the row's sequence are walked 64 at a
+// time with a running (max, sum, weighted value) state.  Lane j scores key j of the block; then
+// lane d accumulates coordinates d, d+64, ... of the value sum.
+template <typename T>
+__global__ __launch_bounds__(64) void attention_generic_kernel(AttnArgs a) {
+  constexpr int MAXD = 4;   // head_dim <= 256
+  __shared__ float qs[256];
+  __shared__ float ps[64];
+  __shared__ long long kbase[64];   // element offset of the key's page+head base, -1 if masked
+  __shared__ int koff[64];
+  const int r = blockIdx.x, qh = blockIdx.y, lane = threadIdx.x;
+  const int hd = a.head_dim, pg = a.page_tokens, Hkv = a.n_kv_heads;
+  const int kvh = qh / (a.n_q_heads / Hkv);
+  const int pos = a.row_pos[r];
+  const int n_keys = pos + 1;
+  const int n_pre = min(n_keys, a.prefix_len);
+  const size_t pelems = (size_t)Hkv * hd * pg;
+  const T *q = (const T *)a.q + ((size_t)r * a.n_q_heads + qh) * hd;
+  for (int i = lane; i < hd; i += 64) qs[i] = Cvt<T>::to_f32(q[i]);
+  const int32_t *tab = a.page_table ? a.page_table + (size_t)a.row_tab[r] * a.table_stride : nullptr;
+  const float scale = 1.0f / sqrtf((float)hd);
+  float m = -INFINITY, l = 0.f, o[MAXD] = {0.f, 0.f, 0.f, 0.f};
+  __syncthreads();
+  for (int j0 = 0; j0 < n_keys; j0 += 64) {
+    const int j = j0 + lane;
+    float s = -INFINITY;
+    long long base = -1;
+    int off = 0;
+    bool in_prefix = true;
+    if (j < n_keys) {
+      int page;
+      if (j < n_pre) {
+        page = j / pg;
+        off = j % pg;
+      } else {
+        const int jj = j - a.prefix_len;
+        page = tab[jj / pg];
+        off = jj % pg;
+        in_prefix = false;
+      }
+      base = (long long)((size_t)page * pelems + (size_t)kvh * hd * pg);
+      const T *kp = (const T *)(in_prefix ? a.k_prefix : a.k_suffix) + base + (size_t)off * hd;
+      float dot = 0.f;
+      for (int i = 0; i < hd; ++i) dot += qs[i] * Cvt<T>::to_f32(kp[i]);
+      s = dot * scale;
+    }
+    // bit 62 marks "suffix pool" so that the value pass picks the right pool
+    kbase[lane] = (base < 0) ? -1 : (in_prefix ? base : (base | (1ll << 62)));
+    koff[lane] = off;
+    const float m_new = fmaxf(m, wave_max(s));
+    const float p = (j < n_keys) ? expf(s - m_new) : 0.f;
+    const float corr = expf(m - m_new);      // m = -inf on the first block: exp(-inf) = 0
+    l = l * corr + wave_sum(p);
+    ps[lane] = p;
+    m = m_new;
+    __syncthreads();
+    const int nblk = min(64, n_keys - j0);
+#pragma unroll
+    for (int c = 0; c < MAXD; ++c) {
+      const int d = lane + 64 * c;
+      if (d < hd) {
+        float acc = o[c] * corr;
+        for (int t = 0; t < nblk; ++t) {
+          const long long kb = kbase[t];
+          const T *vp = (const T *)((kb >> 62) & 1 ? a.v_suffix : a.v_prefix) +
+                        (kb & ~(1ll << 62)) + (size_t)d * pg + koff[t];
+          acc += ps[t] * Cvt<T>::to_f32(*vp);
+        }
+        o[c] = acc;
+      }
+    }
+    __syncthreads();
+  }
+  T *out = (T *)a.out + ((size_t)r * a.n_q_heads + qh) * hd;
+#pragma unroll
+  for (int c = 0; c < MAXD; ++c) {
+    const int d = lane + 64 * c;
+    if (d < hd) out[d] = Cvt<T>::from_f32(o[c] / l);
+  }
+}
+
+int launch_attention_generic(hipStream_t st, int dtype, const AttnArgs &a) {
+  if (a.rows <= 0) return MC_OK;
+  if (a.head_dim > 256) MC_FAIL(MC_ERR_UNSUPPORTED, "head_dim %d > 256", a.head_dim);
+  dim3 grid(a.rows, a.n_q_heads);
+  if (dtype == MC_F32)
+    attention_generic_kernel<float><<<grid, 64, 0, st>>>(a);
+  else
+    attention_generic_kernel<bf16_t><<<grid, 64, 0, st>>>(a);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+// ------------------------------------------------------------------ sampling
+// Order-preserving map of a float to an unsigned integer (larger float -> larger integer).
+__device__ inline uint32_t float_order_bits(float f) {
+  const uint32_t b = __float_as_uint(f + 0.0f);       // -0 -> +0
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ inline float float_from_order_bits(uint32_t o) {
+  return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
+}
+// 64-bit key whose descending order is (z descending, id ascending)
+__device__ inline unsigned long long sample_key(float z, int id) {
+  return ((unsigned long long)float_order_bits(z) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)id);
+}
+
+__device__ inline unsigned long long block_max_u64(unsigned long long v, unsigned long long *scratch) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  for (int o = 32; o > 0; o >>= 1) {
+    unsigned long long t = __shfl_xor(v, o, 64);
+    v = t > v ? t : v;
+  }
+  __syncthreads();
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  unsigned long long t = scratch[0];
+  for (int w = 1; w < nw; ++w) t = scratch[w] > t ? scratch[w] : t;
+  return t;
+}
+
+// One block of 1024 threads per candidate.  Exact top-k by radix selection on the 64-bit key
+// (11/11/10-bit digits), a bitonic sort of the k survivors in LDS, then the softmax and the
+// cumulative walk done left to right by one thread, as the rule demands.
+__global__ __launch_bounds__(1024) void sample_kernel(
+    int V, const float *__restrict__ logits, size_t row_stride, float temperature, int top_k,
+    const float *__restrict__ uniforms, int32_t *__restrict__ out_tokens,
+    int32_t *__restrict__ out_topk) {
+  __shared__ unsigned long long sel[MC_MAX_TOP_K];
+  __shared__ float ev[MC_MAX_TOP_K];
+  __shared__ unsigned int hist[2048];
+  __shared__ unsigned long long scratch64[16];
+  __shared__ unsigned int s_bin, s_above, s_cnt;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const float *row = logits + (size_t)b * row_stride;
+
+  if (temperature <= 0.f || top_k == 1) {
+    unsigned long long best = 0;
+    for (int v = tid; v < V; v += 1024) {
+      const unsigned long long key = sample_key(row[v], v);
+      best = key > best ? key : best;
+    }
+    best = block_max_u64(best, scratch64);
+    if (tid == 0) {
+      const int tok = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+      out_tokens[b] = tok;
+      if (out_topk) out_topk[b] = tok;
+    }
+    return;
+  }
+  const int k = (top_k <= 0 || top_k >= V) ? V : top_k;
+
+  // ---- radix selection of the k-th largest key
+  unsigned long long prefix = 0, pmask = 0;
+  unsigned int need = (unsigned int)k;
+  const int shifts[6] = {53, 42, 32, 21, 10, 0};
+  const int nbits[6] = {11, 11, 10, 11, 11, 10};
+  for (int pass = 0; pass < 6; ++pass) {
+    const int shift = shifts[pass];
+    const unsigned int bmask = (1u << nbits[pass]) - 1u;
+    for (int i = tid; i < 2048; i += 1024) hist[i] = 0;
+    __syncthreads();
+    for (int v = tid; v < V; v += 1024) {
+      const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
+      if ((key & pmask) == prefix) atomicAdd(&hist[(unsigned int)(key >> shift) & bmask], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      // lane L owns bins [2048-32(L+1), 2048-32L): walk from the top bin down
+      const int hi = 2048 - 32 * tid;
+      unsigned int mine = 0;
+      for (int i = 1; i <= 32; ++i) mine += hist[hi - i];
+      unsigned int incl = mine;                   // inclusive scan over lanes 0..L
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned int t = __shfl_up(incl, o, 64);
+        if (tid >= o) incl += t;
+      }
+      const unsigned int excl = incl - mine;
+      if (excl < need && incl >= need) {          // exactly one lane
+        unsigned int above = excl;
+        for (int i = 1; i <= 32; ++i) {
+          const unsigned int c = hist[hi - i];
+          if (above + c >= need) {
+            s_bin = (unsigned int)(hi - i);
+            s_above = above;
+            s_cnt = c;
+            break;
+          }
+          above += c;
+        }
+      }
+    }
+    __syncthreads();
+    prefix |= (unsigned long long)s_bin << shift;
+    pmask |= (unsigned long long)bmask << shift;
+    need -= s_above;
+    const bool done = (s_cnt == need);            // the whole bin belongs to the top k
+    __syncthreads();
+    if (done) break;
+  }
+  // every key >= prefix (low bits zero) is selected: exactly k of them
+  if (tid == 0) s_cnt = 0;
+  __syncthreads();
+  for (int v = tid; v < V; v += 1024) {
+    const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
+    if (key >= prefix) {
+      const unsigned int slot = atomicAdd(&s_cnt, 1u);
+      if (slot < MC_MAX_TOP_K) sel[slot] = key;
+    }
+  }
+  int kp = 1;
+  while (kp < k) kp <<= 1;
+  __syncthreads();
+  for (int i = k + tid; i < kp; i += 1024) sel[i] = 0ull;
+  __syncthreads();
+  // ---- bitonic sort, descending
+  for (int size = 2; size <= kp; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int i = tid; i < kp; i += 1024) {
+        const int j = i ^ stride;
+        if (j > i) {
+          const unsigned long long x = sel[i], y = sel[j];
+          const bool desc = ((i & size) == 0);
+          if ((x < y) == desc) { sel[i] = y; sel[j] = x; }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  const float z0 = float_from_order_bits((uint32_t)(sel[0] >> 32));
+  for (int i = tid; i < k; i += 1024)
+    ev[i] = expf(float_from_order_bits((uint32_t)(sel[i] >> 32)) - z0);
+  if (out_topk)
+    for (int i = tid; i < k; i += 1024)
+      out_topk[(size_t)b * k + i] = (int)(0xFFFFFFFFu - (uint32_t)(sel[i] & 0xFFFFFFFFull));
+  __syncthreads();
+  if (tid == 0) {
+    float total = 0.f;
+    for (int i = 0; i < k; ++i) total += ev[i];
+    const float u = uniforms[b];
+    float run = 0.f;
+    int pick = k - 1;
+    for (int i = 0; i < k; ++i) {
+      run += ev[i];
+      if (__fdiv_rn(run, total) > u) { pick = i; break; }
+    }
+    out_tokens[b] = (int)(0xFFFFFFFFu - (uint32_t)(sel[pick] & 0xFFFFFFFFull));
+  }
+}
+
+int launch_sample(hipStream_t st, int n_cands, int vocab, const float *logits, size_t row_stride,
+                  float temperature, int top_k, const float *uniforms, int32_t *out_tokens,
+                  int32_t *out_topk) {
+  if (n_cands <= 0) return MC_OK;
+  sample_kernel<<<n_cands, 1024, 0, st>>>(vocab, logits, row_stride, temperature, top_k, uniforms,
+                                          out_tokens, out_topk);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+// ------------------------------------------------------------------ reward scoring
+// log-softmax over the whole vocabulary read at the reward tokens (sums kept in double)
+__global__ __launch_bounds__(1024) void reward_logprob_kernel(
+    int V, const float *__restrict__ logits, const int32_t *__restrict__ ids, int R,
+    float *__restrict__ out_lp) {
+  __shared__ float scr_f[16];
+  __shared__ double scr_d[16];
+  const float *row = logits + (size_t)blockIdx.x * V;
+  float m = -INFINITY;
+  for (int v = threadIdx.x; v < V; v += 1024) m = fmaxf(m, row[v]);
+  m = block_max(m, scr_f);
+  double s = 0.0;
+  for (int v = threadIdx.x; v < V; v += 1024) s += exp((double)row[v] - (double)m);
+  s = block_sum<double>(s, scr_d);
+  const double lse = (double)m + log(s);
+  for (int r = threadIdx.x; r < R; r += 1024)
+    out_lp[(size_t)blockIdx.x * R + r] = (float)((double)row[ids[r]] - lse);
+}
+
+// score_b = sum_r w_r softmax_r(lp_r / Ts); rank by (score descending, index ascending)
+__global__ __launch_bounds__(1024) void score_rank_kernel(
+    int B, int R, const float *__restrict__ lp, const float *__restrict__ w, float ts,
+    float *__restrict__ scores, int32_t *__restrict__ rank) {
+  extern __shared__ float sc[];
+  for (int b = threadIdx.x; b < B; b += 1024) {
+    const float *p = lp + (size_t)b * R;
+    double mx = -1e300;
+    for (int r = 0; r < R; ++r) mx = fmax(mx, (double)p[r] / (double)ts);
+    double den = 0.0, num = 0.0;
+    for (int r = 0; r < R; ++r) {
+      const double e = exp((double)p[r] / (double)ts - mx);
+      den += e;
+      num += e * (double)w[r];
+    }
+    const float v = (float)(num / den);
+    sc[b] = v;
+    if (scores) scores[b] = v;
+  }
+  __syncthreads();
+  if (rank)
+    for (int b = threadIdx.x; b < B; b += 1024) {
+      const float mine = sc[b];
+      int ahead = 0;
+      for (int c = 0; c < B; ++c) ahead += (sc[c] > mine) || (sc[c] == mine && c < b);
+      rank[ahead] = b;
+    }
+}
+
+int launch_reward_score(hipStream_t st, int n_cands, int vocab, const float *logits,
+                        const int32_t *reward_ids, const float *reward_values, int n_reward,
+                        float score_temperature, float *out_logprobs, float *out_scores,
+                        int32_t *out_rank) {
+  if (n_cands <= 0) return MC_OK;
+  reward_logprob_kernel<<<n_cands, 1024, 0, st>>>(vocab, logits, reward_ids, n_reward,
+                                                  out_logprobs);
+  MC_HIP(hipGetLastError());
+  score_rank_kernel<<<1, 1024, (size_t)n_cands * sizeof(float), st>>>(
+      n_cands, n_reward, out_logprobs, reward_values, score_temperature, out_scores, out_rank);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+}  // namespace mc

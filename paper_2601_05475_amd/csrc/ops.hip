@@ -1,0 +1,193 @@
+// Single-operation entry points of the C ABI (device pointers in, device pointers out) and the
+// dispatch between the generic ALU kernels and the bf16 MFMA kernels.
+#include <math.h>
+
+#include <algorithm>
+
+#include "common.h"
+#include "kernels_mfma.h"
+
+namespace mc {
+
+int launch_linear_generic(hipStream_t st, int dtype, int M, int N, int K, const void *a,
+                          const void *w, float *out, int n_splits);
+int launch_linear_swiglu_generic(hipStream_t st, int dtype, int M, int N, int K, const void *a,
+                                 const void *wg, const void *wu, void *out);
+
+int linear_auto_splits(int dtype, int M, int N, int K) {
+  if (dtype == MC_BF16 && skinny_linear_supported(M, N, K)) return skinny_linear_splits(M, N, K);
+  if (M > 64) return 1;
+  // generic kernel, few rows: aim at >= 256 workgroups while keeping >= 256 of K per split
+  const int tiles = (N + 63) / 64;
+  int s = 1;
+  while (tiles * s < 256 && K / (s * 2) >= 256 && s < 16) s *= 2;
+  return s;
+}
+
+int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a, const void *w,
+                  float *out, int n_splits) {
+  if (dtype == MC_BF16 && skinny_linear_supported(M, N, K))
+    return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits);
+  if (dtype == MC_BF16 && n_splits == 1 && gemm_supported(M, N, K))
+    return launch_gemm_mfma(st, M, N, K, a, w, nullptr, out, nullptr);
+  return launch_linear_generic(st, dtype, M, N, K, a, w, out, n_splits);
+}
+
+int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
+                         const void *wg, const void *wu, void *out) {
+  if (dtype == MC_BF16 && skinny_linear_supported(M, N, K))
+    return launch_linear_skinny(st, M, N, K, a, wg, wu, nullptr, out, 1);
+  if (dtype == MC_BF16 && gemm_supported(M, N, K))
+    return launch_gemm_mfma(st, M, N, K, a, wg, wu, nullptr, out);
+  return launch_linear_swiglu_generic(st, dtype, M, N, K, a, wg, wu, out);
+}
+
+// ---- decode attention: MFMA split-K kernel when the shape allows, else the generic kernel ---
+__global__ void fill_decode_rows_kernel(int B, int pos, int32_t *row_pos, int32_t *row_tab) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) {
+    row_pos[b] = pos;
+    row_tab[b] = b;
+  }
+}
+
+size_t decode_attention_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int prefix_len,
+                                 int suffix_len, int page_tokens) {
+  size_t generic = (size_t)n_cands * 2 * sizeof(int32_t) + 256;
+  size_t tuned = decode_attention_mfma_ws_bytes(n_cands, Hq, Hkv, hd, prefix_len, suffix_len, page_tokens);
+  return std::max(generic, tuned);
+}
+
+int launch_attention_decode(hipStream_t st, int dtype, const DecodeAttnArgs &a) {
+  if (a.n_cands <= 0) return MC_OK;
+  if (dtype == MC_BF16 && decode_attention_mfma_supported(a))
+    return launch_attention_decode_mfma(st, a);
+  if (a.workspace_bytes < (size_t)a.n_cands * 2 * sizeof(int32_t))
+    MC_FAIL(MC_ERR_INVALID, "attention workspace too small");
+  int32_t *row_pos = (int32_t *)a.workspace, *row_tab = row_pos + a.n_cands;
+  fill_decode_rows_kernel<<<(a.n_cands + 63) / 64, 64, 0, st>>>(
+      a.n_cands, a.prefix_len + a.suffix_len - 1, row_pos, row_tab);
+  MC_HIP(hipGetLastError());
+  AttnArgs g;
+  g.q = a.q; g.k_prefix = a.k_prefix; g.v_prefix = a.v_prefix; g.k_suffix = a.k_suffix;
+  g.v_suffix = a.v_suffix; g.row_pos = row_pos; g.row_tab = row_tab; g.page_table = a.page_table;
+  g.table_stride = a.table_stride; g.rows = a.n_cands; g.n_q_heads = a.n_q_heads;
+  g.n_kv_heads = a.n_kv_heads; g.head_dim = a.head_dim; g.page_tokens = a.page_tokens;
+  g.prefix_len = a.prefix_len; g.out = a.out;
+  return launch_attention_generic(st, dtype, g);
+}
+
+static int check_dtype(int dtype) {
+  if (dtype != MC_F32 && dtype != MC_BF16) MC_FAIL(MC_ERR_INVALID, "unknown dtype %d", dtype);
+  return MC_OK;
+}
+
+}  // namespace mc
+
+using namespace mc;
+
+extern "C" int mc_op_add_rmsnorm(void *stream, int32_t dtype, int32_t rows, int32_t d, float *x,
+                                 const float *partials, int32_t n_partials, const void *gain,
+                                 float eps, void *h_out) {
+  MC_TRY(check_dtype(dtype));
+  if (rows < 0 || d < 1 || n_partials < 0) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!x || !gain || !h_out || (n_partials && !partials)) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  return launch_add_rmsnorm((hipStream_t)stream, dtype, rows, d, x, partials, n_partials, gain, eps, h_out);
+}
+
+extern "C" int mc_op_linear(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K,
+                            const void *a, const void *w, float *out, int32_t n_splits) {
+  MC_TRY(check_dtype(dtype));
+  if (M < 0 || N < 1 || K < 1 || n_splits < 1 || n_splits > K) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!a || !w || !out) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  return launch_linear((hipStream_t)stream, dtype, M, N, K, a, w, out, n_splits);
+}
+
+extern "C" int mc_op_linear_swiglu(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K,
+                                   const void *a, const void *w_gate, const void *w_up, void *out) {
+  MC_TRY(check_dtype(dtype));
+  if (M < 0 || N < 1 || K < 1) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!a || !w_gate || !w_up || !out) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  return launch_linear_swiglu((hipStream_t)stream, dtype, M, N, K, a, w_gate, w_up, out);
+}
+
+extern "C" int mc_op_rope_kv_write(void *stream, int32_t dtype, int32_t rows, int32_t n_q_heads,
+                                   int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens,
+                                   float rope_base, const float *qkv, int32_t n_splits,
+                                   const int32_t *row_pos, const int32_t *row_page,
+                                   const int32_t *row_off, void *q_out, void *k_pages,
+                                   void *v_pages) {
+  MC_TRY(check_dtype(dtype));
+  if (rows < 0 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 2 || head_dim % 2 || page_tokens < 1 ||
+      n_splits < 1 || !(rope_base > 0.f))
+    MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!qkv || !row_pos || !row_page || !row_off || !q_out || !k_pages || !v_pages)
+    MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  return launch_rope_kv((hipStream_t)stream, dtype, rows, n_q_heads, n_kv_heads, head_dim,
+                        page_tokens, (double)rope_base, qkv, n_splits, row_pos, row_page, row_off,
+                        q_out, k_pages, v_pages);
+}
+
+extern "C" size_t mc_op_attention_decode_ws(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
+                                            int32_t head_dim, int32_t prefix_len,
+                                            int32_t suffix_len, int32_t page_tokens) {
+  if (n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 2 || prefix_len < 0 ||
+      suffix_len < 0 || page_tokens < 1)
+    return 0;
+  return decode_attention_ws_bytes(n_cands, n_q_heads, n_kv_heads, head_dim, prefix_len, suffix_len, page_tokens);
+}
+
+extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                      int32_t page_tokens, int32_t prefix_len, int32_t suffix_len,
+                                      const void *q, const void *k_prefix, const void *v_prefix,
+                                      const void *k_suffix, const void *v_suffix,
+                                      const int32_t *page_table, int32_t table_stride,
+                                      int32_t prefix_splits, void *workspace,
+                                      size_t workspace_bytes, void *out) {
+  MC_TRY(check_dtype(dtype));
+  if (n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || head_dim < 2 ||
+      head_dim > 256 || page_tokens < 1 || (page_tokens & (page_tokens - 1)) || prefix_len < 0 ||
+      suffix_len < 0 || prefix_len + suffix_len < 1 || prefix_splits < 0)
+    MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!q || !out || !workspace || (prefix_len && (!k_prefix || !v_prefix)) ||
+      (suffix_len && (!k_suffix || !v_suffix || !page_table)))
+    MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  if (suffix_len && table_stride < (suffix_len + page_tokens - 1) / page_tokens)
+    MC_FAIL(MC_ERR_INVALID, "table_stride %d too small for %d suffix tokens", table_stride, suffix_len);
+  const size_t need = decode_attention_ws_bytes(n_cands, n_q_heads, n_kv_heads, head_dim, prefix_len, suffix_len, page_tokens);
+  if (workspace_bytes < need) MC_FAIL(MC_ERR_INVALID, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  DecodeAttnArgs a;
+  a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_suffix = k_suffix; a.v_suffix = v_suffix;
+  a.page_table = page_table; a.table_stride = table_stride; a.n_cands = n_cands;
+  a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
+  a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.suffix_len = suffix_len;
+  a.prefix_splits = prefix_splits; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
+  a.out = out;
+  return launch_attention_decode((hipStream_t)stream, dtype, a);
+}
+
+extern "C" int mc_op_sample(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
+                            size_t row_stride, float temperature, int32_t top_k,
+                            const float *uniforms, int32_t *out_tokens, int32_t *out_topk) {
+  if (n_cands < 1 || vocab < 1) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!logits || !uniforms || !out_tokens) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  if (!isfinite(temperature)) MC_FAIL(MC_ERR_INVALID, "temperature is not finite");
+  const bool greedy = temperature <= 0.f || top_k == 1;
+  const int k = greedy ? 1 : ((top_k <= 0 || top_k >= vocab) ? vocab : top_k);
+  if (k > MC_MAX_TOP_K) MC_FAIL(MC_ERR_UNSUPPORTED, "top_k %d exceeds the supported %d", k, MC_MAX_TOP_K);
+  return launch_sample((hipStream_t)stream, n_cands, vocab, logits, row_stride, temperature, top_k,
+                       uniforms, out_tokens, out_topk);
+}
+
+extern "C" int mc_op_reward_score(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
+                                  const int32_t *reward_ids, const float *reward_values,
+                                  int32_t n_reward, float score_temperature, float *out_logprobs,
+                                  float *out_scores, int32_t *out_rank) {
+  if (n_cands < 1 || vocab < 1 || n_reward < 1 || n_reward > MC_MAX_REWARD) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!logits || !reward_ids || !reward_values || !out_logprobs) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  if (!(score_temperature > 0.f) || !isfinite(score_temperature)) MC_FAIL(MC_ERR_INVALID, "score_temperature must be positive");
+  if ((size_t)n_cands * sizeof(float) > 60000) MC_FAIL(MC_ERR_UNSUPPORTED, "too many candidates for one ranking block");
+  return launch_reward_score((hipStream_t)stream, n_cands, vocab, logits, reward_ids, reward_values,
+                             n_reward, score_temperature, out_logprobs, out_scores, out_rank);
+}

@@ -1,0 +1,869 @@
+// Host runtime behind the C ABI: models, sessions (shared-prefix KV block, suffix page pool,
+// page table), the four calls and the inspection hooks.  No device allocation happens here:
+// everything is carved out of the caller's arenas.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+namespace mc {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline size_t esize(int dtype) { return dtype == MC_F32 ? 4 : 2; }
+
+static int check_config(const mc_config *c) {
+  if (!c) MC_FAIL(MC_ERR_INVALID, "config is NULL");
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 ||
+      c->head_dim < 2 || c->d_ffn < 1 || c->vocab < 1)
+    MC_FAIL(MC_ERR_INVALID, "config has a non-positive dimension");
+  if (c->n_q_heads % c->n_kv_heads) MC_FAIL(MC_ERR_INVALID, "n_q_heads must be a multiple of n_kv_heads");
+  if (c->head_dim % 2 || c->head_dim > 256) MC_FAIL(MC_ERR_INVALID, "head_dim must be even and <= 256");
+  if (c->dtype != MC_F32 && c->dtype != MC_BF16) MC_FAIL(MC_ERR_INVALID, "unknown dtype %d", c->dtype);
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f) || !isfinite(c->rope_base))
+    MC_FAIL(MC_ERR_INVALID, "rms_eps / rope_base out of range");
+  return MC_OK;
+}
+
+// Bump allocator over a caller-owned device range.
+struct Bump {
+  char *base = nullptr;
+  size_t cap = 0, used = 0;
+  bool measure = false;       // only add sizes up
+  void *take(size_t bytes) {
+    const size_t at = align_up(used, 256);
+    used = at + bytes;
+    if (measure) return nullptr;
+    return (used <= cap) ? base + at : nullptr;
+  }
+};
+
+struct LayerW {
+  const void *attn_norm, *wqkv, *wo, *ffn_norm, *w_gate, *w_up, *w_down;
+};
+
+}  // namespace mc
+
+using namespace mc;
+
+struct mc_model {
+  mc_config cfg;
+  int device;
+  hipStream_t stream;
+  const void *embed, *final_norm, *lm_head;
+  std::vector<LayerW> layers;
+  int n_qkv;                // (Hq + 2 Hkv) * hd
+};
+
+namespace mc {
+
+struct ModelLayout {
+  size_t embed, final_norm, lm_head;
+  struct L { size_t attn_norm, wqkv, wo, ffn_norm, w_gate, w_up, w_down; };
+  std::vector<L> layers;
+  size_t total;
+};
+
+static void model_layout(const mc_config &c, ModelLayout &o) {
+  Bump b;
+  b.measure = true;
+  const size_t e = esize(c.dtype), d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim,
+               kd = (size_t)c.n_kv_heads * c.head_dim;
+  auto at = [&](size_t bytes) { b.take(bytes); return b.used - bytes; };
+  o.embed = at((size_t)c.vocab * d * e);
+  o.final_norm = at(d * e);
+  o.lm_head = at((size_t)c.vocab * d * e);
+  o.layers.resize(c.n_layers);
+  for (auto &l : o.layers) {
+    l.attn_norm = at(d * e);
+    l.wqkv = at((qd + 2 * kd) * d * e);
+    l.wo = at(d * qd * e);
+    l.ffn_norm = at(d * e);
+    l.w_gate = at((size_t)c.d_ffn * d * e);
+    l.w_up = at((size_t)c.d_ffn * d * e);
+    l.w_down = at(d * (size_t)c.d_ffn * e);
+  }
+  o.total = align_up(b.used, 256);
+}
+
+}  // namespace mc
+
+extern "C" size_t mc_model_bytes(const mc_config *cfg) {
+  if (check_config(cfg) != MC_OK) return 0;
+  ModelLayout lay;
+  model_layout(*cfg, lay);
+  return lay.total;
+}
+
+static int check_arena(const mc_arena *a, size_t need, const char *what) {
+  if (!a || !a->dev_base) MC_FAIL(MC_ERR_INVALID, "%s arena is NULL", what);
+  if (((uintptr_t)a->dev_base) & 255) MC_FAIL(MC_ERR_INVALID, "%s arena is not 256-byte aligned", what);
+  if (a->dev_bytes < need)
+    MC_FAIL(MC_ERR_OOM, "%s arena has %zu bytes, %zu needed", what, a->dev_bytes, need);
+  return MC_OK;
+}
+
+extern "C" int mc_model_create(const mc_config *cfg, const mc_weights *w, const mc_arena *arena,
+                               mc_model **out) {
+  MC_TRY(check_config(cfg));
+  if (!w || !out) MC_FAIL(MC_ERR_INVALID, "weights / out is NULL");
+  if (!w->embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->wq || !w->wk || !w->wv ||
+      !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+    MC_FAIL(MC_ERR_INVALID, "a weight pointer is NULL");
+  for (int l = 0; l < cfg->n_layers; ++l)
+    if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] ||
+        !w->w_gate[l] || !w->w_up[l] || !w->w_down[l])
+      MC_FAIL(MC_ERR_INVALID, "a weight pointer of layer %d is NULL", l);
+  ModelLayout lay;
+  model_layout(*cfg, lay);
+  MC_TRY(check_arena(arena, lay.total, "model"));
+  MC_HIP(hipSetDevice(arena->device));
+  hipStream_t st = (hipStream_t)arena->hip_stream;
+  char *base = (char *)arena->dev_base;
+  const mc_config &c = *cfg;
+  const size_t e = esize(c.dtype), d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim,
+               kd = (size_t)c.n_kv_heads * c.head_dim;
+  auto put = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
+    return hipMemcpyAsync(base + off, src, bytes, hipMemcpyDefault, st);
+  };
+  MC_HIP(put(lay.embed, w->embed, (size_t)c.vocab * d * e));
+  MC_HIP(put(lay.final_norm, w->final_norm, d * e));
+  MC_HIP(put(lay.lm_head, w->lm_head, (size_t)c.vocab * d * e));
+  mc_model *m = new (std::nothrow) mc_model();
+  if (!m) MC_FAIL(MC_ERR_OOM, "host allocation failed");
+  m->cfg = c;
+  m->device = arena->device;
+  m->stream = st;
+  m->embed = base + lay.embed;
+  m->final_norm = base + lay.final_norm;
+  m->lm_head = base + lay.lm_head;
+  m->n_qkv = (int)(qd + 2 * kd);
+  m->layers.resize(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l) {
+    const auto &L = lay.layers[l];
+    hipError_t err = put(L.attn_norm, w->attn_norm[l], d * e);
+    // fused QKV: rows of wq, then wk, then wv
+    if (err == hipSuccess) err = put(L.wqkv, w->wq[l], qd * d * e);
+    if (err == hipSuccess) err = put(L.wqkv + qd * d * e, w->wk[l], kd * d * e);
+    if (err == hipSuccess) err = put(L.wqkv + (qd + kd) * d * e, w->wv[l], kd * d * e);
+    if (err == hipSuccess) err = put(L.wo, w->wo[l], d * qd * e);
+    if (err == hipSuccess) err = put(L.ffn_norm, w->ffn_norm[l], d * e);
+    if (err == hipSuccess) err = put(L.w_gate, w->w_gate[l], (size_t)c.d_ffn * d * e);
+    if (err == hipSuccess) err = put(L.w_up, w->w_up[l], (size_t)c.d_ffn * d * e);
+    if (err == hipSuccess) err = put(L.w_down, w->w_down[l], d * (size_t)c.d_ffn * e);
+    if (err != hipSuccess) {
+      delete m;
+      MC_FAIL(MC_ERR_DEVICE, "weight upload of layer %d failed: %s", l, hipGetErrorString(err));
+    }
+    m->layers[l] = LayerW{base + L.attn_norm, base + L.wqkv, base + L.wo, base + L.ffn_norm,
+                          base + L.w_gate, base + L.w_up, base + L.w_down};
+  }
+  hipError_t err = hipStreamSynchronize(st);   // source buffers may be released after return
+  if (err != hipSuccess) {
+    delete m;
+    MC_FAIL(MC_ERR_DEVICE, "weight upload failed: %s", hipGetErrorString(err));
+  }
+  *out = m;
+  return MC_OK;
+}
+
+extern "C" void mc_model_destroy(mc_model *m) { delete m; }
+
+// =====================================================================================
+// Session
+// =====================================================================================
+namespace mc {
+
+enum { LOGITS_NONE = 0, LOGITS_PREFIX = 1, LOGITS_CANDS = 2, LOGITS_SCORE = 3 };
+constexpr int kMaxSplits = 16;
+constexpr int kRingSlots = 32;
+constexpr int kProfCap = 8192;
+
+struct SessionLayout {
+  size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
+      hlast, attn_ws, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
+      score_table, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
+  size_t total;
+  // derived sizes
+  int rows_cap, n_prefix_pages, n_pool_pages, pages_per_cand, n_score_pages;
+  size_t attn_ws_bytes, page_bytes, part_floats;
+};
+
+static int check_params(const mc_session_params *p) {
+  if (!p) MC_FAIL(MC_ERR_INVALID, "session params are NULL");
+  if (p->max_prefix < 1 || p->max_cands < 1 || p->max_suffix < 1)
+    MC_FAIL(MC_ERR_INVALID, "max_prefix / max_cands / max_suffix must be >= 1");
+  const int pg = p->page_tokens;
+  if (pg < 4 || pg > 128 || (pg & (pg - 1))) MC_FAIL(MC_ERR_INVALID, "page_tokens must be a power of two in 4..128");
+  if (p->chunk_rows < 0) MC_FAIL(MC_ERR_INVALID, "chunk_rows < 0");
+  return MC_OK;
+}
+
+static int effective_chunk_rows(const mc_session_params &p) {
+  int c = p.chunk_rows > 0 ? p.chunk_rows : 4096;
+  return std::max(c, p.max_suffix);     // a scoring chunk holds at least one whole candidate
+}
+
+static void session_layout(const mc_config &c, const mc_session_params &p, SessionLayout &o) {
+  Bump b;
+  b.measure = true;
+  auto at = [&](size_t bytes) { b.take(bytes); return b.used - bytes; };
+  const size_t e = esize(c.dtype), d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim,
+               nqkv = qd + 2 * (size_t)c.n_kv_heads * c.head_dim;
+  const int pg = p.page_tokens;
+  const int chunk = effective_chunk_rows(p);
+  o.rows_cap = std::max(chunk, p.max_cands);
+  o.n_prefix_pages = (p.max_prefix + pg - 1) / pg;
+  o.pages_per_cand = (p.max_suffix + pg - 1) / pg;
+  o.n_pool_pages = p.max_cands * o.pages_per_cand;
+  o.n_score_pages = chunk / pg + std::min(p.max_cands, chunk) + 1;
+  o.page_bytes = page_elems(c.n_kv_heads, c.head_dim, pg) * e;
+  const size_t R = o.rows_cap;
+  o.kpool = at((size_t)c.n_layers * (o.n_prefix_pages + o.n_pool_pages) * o.page_bytes);
+  o.vpool = at((size_t)c.n_layers * (o.n_prefix_pages + o.n_pool_pages) * o.page_bytes);
+  o.kscr = at((size_t)o.n_score_pages * o.page_bytes);
+  o.vscr = at((size_t)o.n_score_pages * o.page_bytes);
+  o.x = at(R * d * 4);
+  o.h = at(R * d * e);
+  o.part_floats = std::max(R, (size_t)p.max_cands * kMaxSplits) * std::max(nqkv, d);
+  o.part = at(o.part_floats * 4);
+  o.q = at(R * qd * e);
+  o.attn_out = at(R * qd * e);
+  o.act = at(R * (size_t)c.d_ffn * e);
+  o.logits = at((size_t)p.max_cands * c.vocab * 4);
+  o.prefix_logits = at((size_t)c.vocab * 4);
+  o.xlast = at((size_t)p.max_cands * d * 4);
+  o.hlast = at((size_t)p.max_cands * d * e);
+  o.attn_ws_bytes = decode_attention_ws_bytes(p.max_cands, c.n_q_heads, c.n_kv_heads, c.head_dim,
+                                              p.max_prefix, p.max_suffix, pg);
+  o.attn_ws = at(o.attn_ws_bytes);
+  o.row_tok = at(R * 4);
+  o.row_pos = at(R * 4);
+  o.row_page = at(R * 4);
+  o.row_off = at(R * 4);
+  o.row_tab = at(R * 4);
+  o.last_idx = at((size_t)p.max_cands * 4);
+  o.page_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
+  o.score_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
+  o.samp_tok = at((size_t)p.max_cands * 4);
+  o.samp_u = at((size_t)p.max_cands * 4);
+  o.topk = at((size_t)p.max_cands * MC_MAX_TOP_K * 4);
+  o.rw_ids = at(MC_MAX_REWARD * 4);
+  o.rw_vals = at(MC_MAX_REWARD * 4);
+  o.rw_lp = at((size_t)p.max_cands * MC_MAX_REWARD * 4);
+  o.rw_scores = at((size_t)p.max_cands * 4);
+  o.rw_rank = at((size_t)p.max_cands * 4);
+  o.total = align_up(b.used, 256);
+}
+
+}  // namespace mc
+
+extern "C" size_t mc_session_bytes(const mc_config *cfg, const mc_session_params *p) {
+  if (check_config(cfg) != MC_OK || check_params(p) != MC_OK) return 0;
+  SessionLayout lay;
+  session_layout(*cfg, *p, lay);
+  return lay.total;
+}
+
+struct mc_session {
+  const mc_model *m;
+  mc_session_params p;
+  SessionLayout lay;
+  char *base;
+  hipStream_t stream;
+  int chunk_rows;
+  // state
+  int prefix_len = 0, n_cands = 0, suffix_len = 0, logits_state = LOGITS_NONE, logits_rows = 0;
+  bool sampled_on_device = false, table_ready = false;
+  int prefix_splits = 0;
+  std::vector<int32_t> free_list;           // initial order of the pool
+  std::vector<int32_t> host_table;          // [max_cands][pages_per_cand], pool-relative ids
+  // pinned staging ring for small host->device parameter blocks
+  char *ring = nullptr;
+  size_t slot_bytes = 0;
+  int ring_next = 0;
+  hipEvent_t ring_ev[kRingSlots];
+  bool ring_used[kRingSlots];
+  // kernel-class timing
+  int prof_class = MC_K_NONE, prof_stride = 1, prof_seen = 0;
+  std::vector<hipEvent_t> prof_ev;          // pairs
+  int prof_n = 0;
+
+  template <typename T> T *ptr(size_t off) const { return (T *)(base + off); }
+  size_t layer_pool_bytes() const { return (size_t)(lay.n_prefix_pages + lay.n_pool_pages) * lay.page_bytes; }
+  char *k_layer(int l) const { return base + lay.kpool + (size_t)l * layer_pool_bytes(); }
+  char *v_layer(int l) const { return base + lay.vpool + (size_t)l * layer_pool_bytes(); }
+};
+
+namespace mc {
+
+struct ProfScope {
+  mc_session *s;
+  bool active = false;
+  ProfScope(mc_session *s_, int cls) : s(s_) {
+    if (s->prof_class != cls || cls == MC_K_NONE) return;
+    if ((s->prof_seen++ % s->prof_stride) != 0 || s->prof_n >= kProfCap) return;
+    if ((size_t)(2 * s->prof_n + 2) > s->prof_ev.size()) return;
+    active = hipEventRecord(s->prof_ev[2 * s->prof_n], s->stream) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!active) return;
+    (void)hipEventRecord(s->prof_ev[2 * s->prof_n + 1], s->stream);
+    s->prof_n++;
+  }
+};
+
+// Stage `bytes` of host data into the pinned ring and enqueue its copy to `dst`.
+static int upload(mc_session *s, void *dst, const void *src, size_t bytes) {
+  if (bytes == 0) return MC_OK;
+  if (bytes > s->slot_bytes) MC_FAIL(MC_ERR_INVALID, "internal: staging block of %zu bytes too large", bytes);
+  const int slot = s->ring_next;
+  s->ring_next = (slot + 1) % kRingSlots;
+  if (s->ring_used[slot]) MC_HIP(hipEventSynchronize(s->ring_ev[slot]));
+  char *stage = s->ring + (size_t)slot * s->slot_bytes;
+  memcpy(stage, src, bytes);
+  MC_HIP(hipMemcpyAsync(dst, stage, bytes, hipMemcpyHostToDevice, s->stream));
+  MC_HIP(hipEventRecord(s->ring_ev[slot], s->stream));
+  s->ring_used[slot] = true;
+  return MC_OK;
+}
+
+static int download(mc_session *s, void *dst_host, const void *src_dev, size_t bytes) {
+  if (bytes) MC_HIP(hipMemcpyAsync(dst_host, src_dev, bytes, hipMemcpyDeviceToHost, s->stream));
+  return MC_OK;
+}
+
+__global__ void decode_rows_kernel(int B, int pos, int page_slot, int off, int table_stride,
+                                   const int32_t *__restrict__ table, int32_t *row_pos,
+                                   int32_t *row_page, int32_t *row_off, int32_t *row_tab) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  row_pos[b] = pos;
+  row_page[b] = table[(size_t)b * table_stride + page_slot];
+  row_off[b] = off;
+  row_tab[b] = b;
+}
+
+__global__ void copy_row_kernel(int n, const float *__restrict__ src, float *__restrict__ dst) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+enum { PASS_PREFIX = 0, PASS_DECODE = 1, PASS_SCORE = 2 };
+
+// Run all layers on `rows` rows whose metadata (token, position, KV slot, table row) is on the
+// device already.  prefix_visible: number of prefix keys that exist (for PASS_PREFIX: the end of
+// this chunk).  Leaves the last down-projection's partial sums in `part` (n returned in *tail).
+static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int *tail_splits) {
+  const mc_model *m = s->m;
+  const mc_config &c = m->cfg;
+  const SessionLayout &L = s->lay;
+  hipStream_t st = s->stream;
+  const int dt = c.dtype, d = c.d_model, qd = c.n_q_heads * c.head_dim;
+  float *x = s->ptr<float>(L.x);
+  float *part = s->ptr<float>(L.part);
+  void *h = s->ptr<void>(L.h), *q = s->ptr<void>(L.q), *ao = s->ptr<void>(L.attn_out),
+       *act = s->ptr<void>(L.act);
+  const int32_t *row_pos = s->ptr<int32_t>(L.row_pos), *row_page = s->ptr<int32_t>(L.row_page),
+                *row_off = s->ptr<int32_t>(L.row_off), *row_tab = s->ptr<int32_t>(L.row_tab);
+  {
+    ProfScope ps(s, MC_K_EMBED);
+    MC_TRY(launch_embed(st, dt, rows, d, s->ptr<int32_t>(L.row_tok), m->embed, x));
+  }
+  auto splits_for = [&](int N, int K) {
+    int sp = linear_auto_splits(dt, rows, N, K);
+    sp = std::min(sp, kMaxSplits);
+    while (sp > 1 && (size_t)sp * rows * N > L.part_floats) --sp;
+    return sp;
+  };
+  int pending = 0;   // partial sums waiting in `part` to be added to x
+  const size_t prefix_bytes = (size_t)L.n_prefix_pages * L.page_bytes;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW &W = m->layers[l];
+    {
+      ProfScope ps(s, MC_K_ADD_RMSNORM);
+      MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, pending, W.attn_norm, c.rms_eps, h));
+    }
+    const int s1 = splits_for(m->n_qkv, d);
+    {
+      ProfScope ps(s, MC_K_LINEAR_QKV);
+      MC_TRY(launch_linear(st, dt, rows, m->n_qkv, d, h, W.wqkv, part, s1));
+    }
+    char *kl = s->k_layer(l), *vl = s->v_layer(l);
+    void *kdst, *vdst;
+    if (pass == PASS_PREFIX) { kdst = kl; vdst = vl; }
+    else if (pass == PASS_DECODE) { kdst = kl + prefix_bytes; vdst = vl + prefix_bytes; }
+    else { kdst = s->ptr<void>(L.kscr); vdst = s->ptr<void>(L.vscr); }
+    {
+      ProfScope ps(s, MC_K_ROPE_KV);
+      MC_TRY(launch_rope_kv(st, dt, rows, c.n_q_heads, c.n_kv_heads, c.head_dim, s->p.page_tokens,
+                            (double)c.rope_base, part, s1, row_pos, row_page, row_off, q, kdst, vdst));
+    }
+    if (pass == PASS_DECODE) {
+      DecodeAttnArgs a;
+      a.q = q; a.k_prefix = kl; a.v_prefix = vl; a.k_suffix = kdst; a.v_suffix = vdst;
+      a.page_table = s->ptr<int32_t>(L.page_table); a.table_stride = L.pages_per_cand;
+      a.n_cands = rows; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
+      a.head_dim = c.head_dim; a.page_tokens = s->p.page_tokens;
+      a.prefix_len = s->prefix_len; a.suffix_len = s->suffix_len + 1;
+      a.prefix_splits = s->prefix_splits;
+      a.workspace = s->ptr<void>(L.attn_ws); a.workspace_bytes = L.attn_ws_bytes; a.out = ao;
+      ProfScope ps(s, MC_K_ATTN_DECODE);
+      MC_TRY(launch_attention_decode(st, dt, a));
+    } else {
+      AttnArgs a;
+      a.q = q; a.k_prefix = kl; a.v_prefix = vl; a.k_suffix = kdst; a.v_suffix = vdst;
+      a.row_pos = row_pos; a.row_tab = row_tab;
+      a.page_table = (pass == PASS_SCORE) ? s->ptr<int32_t>(L.score_table) : nullptr;
+      a.table_stride = L.pages_per_cand;
+      a.rows = rows; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
+      a.head_dim = c.head_dim; a.page_tokens = s->p.page_tokens; a.prefix_len = prefix_visible;
+      a.out = ao;
+      ProfScope ps(s, MC_K_ATTN_PREFILL);
+      MC_TRY(launch_attention_generic(st, dt, a));
+    }
+    const int s2 = splits_for(d, qd);
+    {
+      ProfScope ps(s, MC_K_LINEAR_O);
+      MC_TRY(launch_linear(st, dt, rows, d, qd, ao, W.wo, part, s2));
+    }
+    {
+      ProfScope ps(s, MC_K_ADD_RMSNORM);
+      MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, s2, W.ffn_norm, c.rms_eps, h));
+    }
+    {
+      ProfScope ps(s, MC_K_LINEAR_GATE_UP);
+      MC_TRY(launch_linear_swiglu(st, dt, rows, c.d_ffn, d, h, W.w_gate, W.w_up, act));
+    }
+    const int s3 = splits_for(d, c.d_ffn);
+    {
+      ProfScope ps(s, MC_K_LINEAR_DOWN);
+      MC_TRY(launch_linear(st, dt, rows, d, c.d_ffn, act, W.w_down, part, s3));
+    }
+    pending = s3;
+  }
+  *tail_splits = pending;
+  return MC_OK;
+}
+
+// Final norm + LM head on n_rows rows gathered from x (indices on device in last_idx, or the
+// rows 0..n_rows-1 when idx_on_device is false); logits go to `dst`.
+static int lm_head(mc_session *s, int rows_in_x, int tail_splits, int n_rows, bool gather, float *dst) {
+  const mc_model *m = s->m;
+  const mc_config &c = m->cfg;
+  const SessionLayout &L = s->lay;
+  hipStream_t st = s->stream;
+  float *x = s->ptr<float>(L.x);
+  const void *hin;
+  if (gather) {
+    // fold the pending partial sums into x (normalised output unused), then gather rows
+    {
+      ProfScope ps(s, MC_K_ADD_RMSNORM);
+      MC_TRY(launch_add_rmsnorm(st, c.dtype, rows_in_x, c.d_model, x, s->ptr<float>(L.part),
+                                tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h)));
+    }
+    MC_TRY(launch_gather_rows(st, n_rows, c.d_model, x, s->ptr<int32_t>(L.last_idx),
+                              s->ptr<float>(L.xlast)));
+    MC_TRY(launch_add_rmsnorm(st, c.dtype, n_rows, c.d_model, s->ptr<float>(L.xlast), nullptr, 0,
+                              m->final_norm, c.rms_eps, s->ptr<void>(L.hlast)));
+    hin = s->ptr<void>(L.hlast);
+  } else {
+    ProfScope ps(s, MC_K_ADD_RMSNORM);
+    MC_TRY(launch_add_rmsnorm(st, c.dtype, rows_in_x, c.d_model, x, s->ptr<float>(L.part),
+                              tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h)));
+    hin = s->ptr<void>(L.h);
+  }
+  ProfScope ps(s, MC_K_LINEAR_LM_HEAD);
+  MC_TRY(launch_linear(st, c.dtype, n_rows, c.vocab, c.d_model, hin, m->lm_head, dst, 1));
+  return MC_OK;
+}
+
+static int check_tokens(const mc_config &c, const int32_t *t, size_t n) {
+  for (size_t i = 0; i < n; ++i)
+    if (t[i] < 0 || t[i] >= c.vocab) MC_FAIL(MC_ERR_INVALID, "token id %d at index %zu outside [0, %d)", t[i], i, c.vocab);
+  return MC_OK;
+}
+
+}  // namespace mc
+
+extern "C" int mc_session_create(const mc_model *m, const mc_arena *arena,
+                                 const mc_session_params *p, mc_session **out) {
+  if (!m || !out) MC_FAIL(MC_ERR_INVALID, "model / out is NULL");
+  MC_TRY(check_params(p));
+  SessionLayout lay;
+  session_layout(m->cfg, *p, lay);
+  MC_TRY(check_arena(arena, lay.total, "session"));
+  if (arena->device != m->device) MC_FAIL(MC_ERR_INVALID, "session arena is on another device than the model");
+  MC_HIP(hipSetDevice(arena->device));
+  mc_session *s = new (std::nothrow) mc_session();
+  if (!s) MC_FAIL(MC_ERR_OOM, "host allocation failed");
+  s->m = m;
+  s->p = *p;
+  s->lay = lay;
+  s->base = (char *)arena->dev_base;
+  s->stream = (hipStream_t)arena->hip_stream;
+  s->chunk_rows = effective_chunk_rows(*p);
+  s->free_list.resize(lay.n_pool_pages);
+  for (int i = 0; i < lay.n_pool_pages; ++i) s->free_list[i] = i;
+  s->host_table.assign((size_t)p->max_cands * lay.pages_per_cand, -1);
+  s->slot_bytes = align_up((size_t)lay.rows_cap * 4 * 5 + 256, 256);
+  for (int i = 0; i < kRingSlots; ++i) { s->ring_used[i] = false; s->ring_ev[i] = nullptr; }
+  hipError_t err = hipHostMalloc((void **)&s->ring, s->slot_bytes * kRingSlots, hipHostMallocDefault);
+  for (int i = 0; err == hipSuccess && i < kRingSlots; ++i)
+    err = hipEventCreateWithFlags(&s->ring_ev[i], hipEventDisableTiming);
+  // KV memory starts at zero so that unused tail slots of a page hold finite values
+  if (err == hipSuccess)
+    err = hipMemsetAsync(s->base + lay.kpool, 0, lay.vscr + (size_t)lay.n_score_pages * lay.page_bytes - lay.kpool, s->stream);
+  if (err == hipSuccess) err = hipStreamSynchronize(s->stream);
+  if (err != hipSuccess) {
+    mc_session_destroy(s);
+    MC_FAIL(MC_ERR_DEVICE, "session set-up failed: %s", hipGetErrorString(err));
+  }
+  *out = s;
+  return MC_OK;
+}
+
+extern "C" void mc_session_destroy(mc_session *s) {
+  if (!s) return;
+  (void)hipStreamSynchronize(s->stream);
+  for (int i = 0; i < kRingSlots; ++i)
+    if (s->ring_ev[i]) (void)hipEventDestroy(s->ring_ev[i]);
+  for (hipEvent_t e : s->prof_ev) (void)hipEventDestroy(e);
+  if (s->ring) (void)hipHostFree(s->ring);
+  delete s;
+}
+
+extern "C" int mc_session_sync(mc_session *s) {
+  if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
+  MC_HIP(hipStreamSynchronize(s->stream));
+  return MC_OK;
+}
+
+extern "C" int mc_session_reset_candidates(mc_session *s) {
+  if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
+  s->n_cands = 0;
+  s->suffix_len = 0;
+  s->sampled_on_device = false;
+  s->table_ready = false;
+  std::fill(s->host_table.begin(), s->host_table.end(), -1);
+  if (s->prefix_len > 0) {
+    s->logits_state = LOGITS_PREFIX;
+    s->logits_rows = 1;
+  } else {
+    s->logits_state = LOGITS_NONE;
+    s->logits_rows = 0;
+  }
+  return MC_OK;
+}
+
+extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens) {
+  if (!s || !tokens) MC_FAIL(MC_ERR_INVALID, "session / tokens is NULL");
+  if (n_tokens < 1 || n_tokens > s->p.max_prefix)
+    MC_FAIL(MC_ERR_INVALID, "n_tokens %d outside [1, %d]", n_tokens, s->p.max_prefix);
+  const mc_config &c = s->m->cfg;
+  MC_TRY(check_tokens(c, tokens, n_tokens));
+  MC_HIP(hipSetDevice(s->m->device));
+  const SessionLayout &L = s->lay;
+  const int pg = s->p.page_tokens;
+  // the old prefix and candidates are gone from here on
+  s->prefix_len = 0;
+  mc_session_reset_candidates(s);
+  std::vector<int32_t> meta;
+  int tail = 0, rows = 0;
+  for (int p0 = 0; p0 < n_tokens; p0 += s->chunk_rows) {
+    rows = std::min(s->chunk_rows, n_tokens - p0);
+    meta.resize((size_t)rows * 4);
+    for (int r = 0; r < rows; ++r) {
+      meta[r] = tokens[p0 + r];
+      meta[rows + r] = p0 + r;
+      meta[2 * rows + r] = (p0 + r) / pg;
+      meta[3 * rows + r] = (p0 + r) % pg;
+    }
+    // the four blocks land in row_tok, row_pos, row_page, row_off
+    MC_TRY(upload(s, s->ptr<void>(L.row_tok), meta.data(), (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_pos), meta.data() + rows, (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_page), meta.data() + 2 * rows, (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_off), meta.data() + 3 * rows, (size_t)rows * 4));
+    MC_TRY(run_layers(s, rows, PASS_PREFIX, p0 + rows, &tail));
+  }
+  // logits of the last position only
+  {
+    const mc_model *m = s->m;
+    hipStream_t st = s->stream;
+    ProfScope ps0(s, MC_K_ADD_RMSNORM);
+    MC_TRY(launch_add_rmsnorm(st, c.dtype, rows, c.d_model, s->ptr<float>(L.x), s->ptr<float>(L.part),
+                              tail, m->final_norm, c.rms_eps, s->ptr<void>(L.h)));
+    const char *hlast = s->ptr<char>(L.h) + (size_t)(rows - 1) * c.d_model * esize(c.dtype);
+    MC_TRY(launch_linear(st, c.dtype, 1, c.vocab, c.d_model, hlast, m->lm_head,
+                         s->ptr<float>(L.prefix_logits), 1));
+  }
+  s->prefix_len = n_tokens;
+  s->logits_state = LOGITS_PREFIX;
+  s->logits_rows = 1;
+  return MC_OK;
+}
+
+extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_cands) {
+  if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
+  if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_decode_step before mc_prefill_shared");
+  if (n_cands < 1 || n_cands > s->p.max_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
+  if (s->n_cands && n_cands != s->n_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d differs from the %d fixed earlier", n_cands, s->n_cands);
+  if (s->suffix_len >= s->p.max_suffix) MC_FAIL(MC_ERR_OOM, "suffix is full (%d tokens): page pool exhausted", s->suffix_len);
+  const mc_config &c = s->m->cfg;
+  if (tokens) MC_TRY(check_tokens(c, tokens, n_cands));
+  else if (!s->sampled_on_device) MC_FAIL(MC_ERR_STATE, "tokens is NULL but no mc_sample result is pending on the device");
+  MC_HIP(hipSetDevice(s->m->device));
+  const SessionLayout &L = s->lay;
+  const int pg = s->p.page_tokens, t = s->suffix_len;
+  if (!s->table_ready) {
+    // Page ids are a pure function of (candidate, page slot) under the lock-step rule: at the
+    // boundary t = p * page_tokens candidates take pages in ascending order from the list head.
+    std::vector<int32_t> full((size_t)s->p.max_cands * L.pages_per_cand, 0);
+    for (int p = 0; p < L.pages_per_cand; ++p)
+      for (int b = 0; b < n_cands; ++b) full[(size_t)b * L.pages_per_cand + p] = s->free_list[(size_t)p * n_cands + b];
+    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.page_table), full.data(), full.size() * 4, hipMemcpyHostToDevice, s->stream));
+    MC_HIP(hipStreamSynchronize(s->stream));
+    s->table_ready = true;
+  }
+  if (tokens) MC_TRY(upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4));
+  else MC_HIP(hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4, hipMemcpyDeviceToDevice, s->stream));
+  decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
+      n_cands, s->prefix_len + t, t / pg, t % pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
+      s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
+      s->ptr<int32_t>(L.row_tab));
+  MC_HIP(hipGetLastError());
+  int tail = 0;
+  const int saved_n = s->n_cands;
+  s->n_cands = n_cands;
+  int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, &tail);
+  if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
+  if (rc != MC_OK) { s->n_cands = saved_n; return rc; }
+  if (t % pg == 0)
+    for (int b = 0; b < n_cands; ++b)
+      s->host_table[(size_t)b * L.pages_per_cand + t / pg] = s->free_list[(size_t)(t / pg) * n_cands + b];
+  s->suffix_len = t + 1;
+  s->logits_state = LOGITS_CANDS;
+  s->logits_rows = n_cands;
+  s->sampled_on_device = false;
+  return MC_OK;
+}
+
+extern "C" int mc_sample(mc_session *s, int32_t n_cands, float temperature, int32_t top_k,
+                         const float *uniforms, int32_t *out_tokens, int32_t *out_topk_ids) {
+  if (!s || !uniforms) MC_FAIL(MC_ERR_INVALID, "session / uniforms is NULL");
+  if (s->logits_state != LOGITS_PREFIX && s->logits_state != LOGITS_CANDS)
+    MC_FAIL(MC_ERR_STATE, "mc_sample without pending logits (call mc_prefill_shared or mc_decode_step first)");
+  if (n_cands < 1 || n_cands > s->p.max_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
+  if (s->n_cands && n_cands != s->n_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d differs from the %d fixed earlier", n_cands, s->n_cands);
+  if (!isfinite(temperature)) MC_FAIL(MC_ERR_INVALID, "temperature is not finite");
+  for (int b = 0; b < n_cands; ++b)
+    if (!(uniforms[b] >= 0.f && uniforms[b] < 1.f)) MC_FAIL(MC_ERR_INVALID, "uniforms[%d] = %g outside [0, 1)", b, uniforms[b]);
+  const mc_config &c = s->m->cfg;
+  const bool greedy = temperature <= 0.f || top_k == 1;
+  const int k = greedy ? 1 : ((top_k <= 0 || top_k >= c.vocab) ? c.vocab : top_k);
+  if (k > MC_MAX_TOP_K) MC_FAIL(MC_ERR_UNSUPPORTED, "top_k %d exceeds the supported %d", k, MC_MAX_TOP_K);
+  MC_HIP(hipSetDevice(s->m->device));
+  const SessionLayout &L = s->lay;
+  MC_TRY(upload(s, s->ptr<void>(L.samp_u), uniforms, (size_t)n_cands * 4));
+  const bool shared_row = s->logits_state == LOGITS_PREFIX;
+  const float *lg = shared_row ? s->ptr<float>(L.prefix_logits) : s->ptr<float>(L.logits);
+  {
+    ProfScope ps(s, MC_K_SAMPLE);
+    MC_TRY(launch_sample(s->stream, n_cands, c.vocab, lg, shared_row ? 0 : (size_t)c.vocab,
+                         temperature, top_k, s->ptr<float>(L.samp_u), s->ptr<int32_t>(L.samp_tok),
+                         out_topk_ids ? s->ptr<int32_t>(L.topk) : nullptr));
+  }
+  s->sampled_on_device = true;
+  s->n_cands = n_cands;
+  if (out_tokens || out_topk_ids) {
+    if (out_tokens) MC_TRY(download(s, out_tokens, s->ptr<void>(L.samp_tok), (size_t)n_cands * 4));
+    if (out_topk_ids) MC_TRY(download(s, out_topk_ids, s->ptr<void>(L.topk), (size_t)n_cands * k * 4));
+    MC_HIP(hipStreamSynchronize(s->stream));
+  }
+  return MC_OK;
+}
+
+extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
+                                   const int32_t *suffix_lens, int32_t n_cands, int32_t max_len,
+                                   const int32_t *reward_ids, const float *reward_values,
+                                   int32_t n_reward, float score_temperature, float *out_logprobs,
+                                   float *out_scores, int32_t *out_rank) {
+  if (!s || !suffix_tokens || !suffix_lens || !reward_ids || !reward_values)
+    MC_FAIL(MC_ERR_INVALID, "a required pointer is NULL");
+  if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_score_candidates before mc_prefill_shared");
+  if (n_cands < 1 || n_cands > s->p.max_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
+  if (max_len < 1 || max_len > s->p.max_suffix)
+    MC_FAIL(MC_ERR_INVALID, "max_len %d outside [1, %d]", max_len, s->p.max_suffix);
+  if (n_reward < 1 || n_reward > MC_MAX_REWARD)
+    MC_FAIL(MC_ERR_INVALID, "n_reward %d outside [1, %d]", n_reward, MC_MAX_REWARD);
+  if (!(score_temperature > 0.f) || !isfinite(score_temperature))
+    MC_FAIL(MC_ERR_INVALID, "score_temperature must be positive and finite");
+  const mc_config &c = s->m->cfg;
+  for (int r = 0; r < n_reward; ++r) {
+    if (reward_ids[r] < 0 || reward_ids[r] >= c.vocab) MC_FAIL(MC_ERR_INVALID, "reward id %d outside the vocabulary", reward_ids[r]);
+    if (!isfinite(reward_values[r])) MC_FAIL(MC_ERR_INVALID, "reward value %d is not finite", r);
+    for (int q = 0; q < r; ++q)
+      if (reward_ids[q] == reward_ids[r]) MC_FAIL(MC_ERR_INVALID, "reward id %d is repeated", reward_ids[r]);
+  }
+  for (int b = 0; b < n_cands; ++b) {
+    if (suffix_lens[b] < 1 || suffix_lens[b] > max_len)
+      MC_FAIL(MC_ERR_INVALID, "suffix_lens[%d] = %d outside [1, %d]", b, suffix_lens[b], max_len);
+    MC_TRY(check_tokens(c, suffix_tokens + (size_t)b * max_len, suffix_lens[b]));
+  }
+  MC_HIP(hipSetDevice(s->m->device));
+  const SessionLayout &L = s->lay;
+  const int pg = s->p.page_tokens;
+  MC_TRY(upload(s, s->ptr<void>(L.rw_ids), reward_ids, (size_t)n_reward * 4));
+  MC_TRY(upload(s, s->ptr<void>(L.rw_vals), reward_values, (size_t)n_reward * 4));
+  std::vector<int32_t> tok, pos, page, off, tab, last, table;
+  int b0 = 0;
+  while (b0 < n_cands) {
+    // a chunk holds whole candidates, at most chunk_rows rows
+    int b1 = b0, rows = 0;
+    while (b1 < n_cands && rows + suffix_lens[b1] <= s->chunk_rows) rows += suffix_lens[b1++];
+    const int nc = b1 - b0;
+    tok.resize(rows); pos.resize(rows); page.resize(rows); off.resize(rows); tab.resize(rows);
+    last.resize(nc);
+    table.assign((size_t)nc * L.pages_per_cand, 0);
+    int r = 0, next_page = 0;
+    for (int b = b0; b < b1; ++b) {
+      const int len = suffix_lens[b];
+      for (int j = 0; j < len; ++j, ++r) {
+        if (j % pg == 0) table[(size_t)(b - b0) * L.pages_per_cand + j / pg] = next_page++;
+        tok[r] = suffix_tokens[(size_t)b * max_len + j];
+        pos[r] = s->prefix_len + j;
+        page[r] = table[(size_t)(b - b0) * L.pages_per_cand + j / pg];
+        off[r] = j % pg;
+        tab[r] = b - b0;
+      }
+      last[b - b0] = r - 1;
+    }
+    if (next_page > L.n_score_pages) MC_FAIL(MC_ERR_OOM, "internal: scoring scratch pages exhausted");
+    MC_TRY(upload(s, s->ptr<void>(L.row_tok), tok.data(), (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_pos), pos.data(), (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_page), page.data(), (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_off), off.data(), (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.row_tab), tab.data(), (size_t)rows * 4));
+    MC_TRY(upload(s, s->ptr<void>(L.last_idx), last.data(), (size_t)nc * 4));
+    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.score_table), table.data(), table.size() * 4, hipMemcpyHostToDevice, s->stream));
+    MC_HIP(hipStreamSynchronize(s->stream));   // `table` is pageable host memory reused below
+    int tail = 0;
+    MC_TRY(run_layers(s, rows, PASS_SCORE, s->prefix_len, &tail));
+    MC_TRY(lm_head(s, rows, tail, nc, true, s->ptr<float>(L.logits) + (size_t)b0 * c.vocab));
+    b0 = b1;
+  }
+  {
+    ProfScope ps(s, MC_K_REWARD);
+    MC_TRY(launch_reward_score(s->stream, n_cands, c.vocab, s->ptr<float>(L.logits),
+                               s->ptr<int32_t>(L.rw_ids), s->ptr<float>(L.rw_vals), n_reward,
+                               score_temperature, s->ptr<float>(L.rw_lp), s->ptr<float>(L.rw_scores),
+                               s->ptr<int32_t>(L.rw_rank)));
+  }
+  if (out_logprobs) MC_TRY(download(s, out_logprobs, s->ptr<void>(L.rw_lp), (size_t)n_cands * n_reward * 4));
+  if (out_scores) MC_TRY(download(s, out_scores, s->ptr<void>(L.rw_scores), (size_t)n_cands * 4));
+  if (out_rank) MC_TRY(download(s, out_rank, s->ptr<void>(L.rw_rank), (size_t)n_cands * 4));
+  MC_HIP(hipStreamSynchronize(s->stream));
+  // scoring overwrote the candidates' logits buffer: sampling must be preceded by a new step
+  s->logits_state = LOGITS_SCORE;
+  s->logits_rows = n_cands;
+  return MC_OK;
+}
+
+// ---- inspection hooks -----------------------------------------------------------------
+extern "C" int mc_debug_copy_logits(mc_session *s, float *out, int32_t n_rows) {
+  if (!s || !out) MC_FAIL(MC_ERR_INVALID, "session / out is NULL");
+  if (s->logits_state == LOGITS_NONE) MC_FAIL(MC_ERR_STATE, "no logits pending");
+  if (n_rows != s->logits_rows) MC_FAIL(MC_ERR_INVALID, "n_rows %d, but %d rows are pending", n_rows, s->logits_rows);
+  const SessionLayout &L = s->lay;
+  const float *src = s->logits_state == LOGITS_PREFIX ? s->ptr<float>(L.prefix_logits) : s->ptr<float>(L.logits);
+  MC_TRY(download(s, out, src, (size_t)n_rows * s->m->cfg.vocab * 4));
+  MC_HIP(hipStreamSynchronize(s->stream));
+  return MC_OK;
+}
+
+extern "C" int mc_debug_page_table(mc_session *s, int32_t *out, int32_t *n_pages, int32_t max_pages) {
+  if (!s || !out || !n_pages) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  const int held = (s->suffix_len + s->p.page_tokens - 1) / s->p.page_tokens;
+  if (max_pages < held) MC_FAIL(MC_ERR_INVALID, "max_pages %d < %d pages held", max_pages, held);
+  for (int b = 0; b < s->p.max_cands; ++b) {
+    n_pages[b] = b < s->n_cands ? held : 0;
+    for (int p = 0; p < max_pages; ++p)
+      out[(size_t)b * max_pages + p] = (b < s->n_cands && p < held) ? s->host_table[(size_t)b * s->lay.pages_per_cand + p] : -1;
+  }
+  return MC_OK;
+}
+
+extern "C" int32_t mc_debug_pool_pages(const mc_session *s) { return s ? s->lay.n_pool_pages : 0; }
+
+extern "C" int mc_debug_set_free_list(mc_session *s, const int32_t *perm, int32_t n) {
+  if (!s || !perm) MC_FAIL(MC_ERR_INVALID, "session / perm is NULL");
+  if (s->n_cands != 0) MC_FAIL(MC_ERR_STATE, "free list can only change while no candidate holds a page");
+  if (n != s->lay.n_pool_pages) MC_FAIL(MC_ERR_INVALID, "n %d != pool size %d", n, s->lay.n_pool_pages);
+  std::vector<char> seen(n, 0);
+  for (int i = 0; i < n; ++i) {
+    if (perm[i] < 0 || perm[i] >= n || seen[perm[i]]) MC_FAIL(MC_ERR_INVALID, "perm is not a permutation");
+    seen[perm[i]] = 1;
+  }
+  s->free_list.assign(perm, perm + n);
+  return MC_OK;
+}
+
+extern "C" int mc_debug_set_prefix_splits(mc_session *s, int32_t n_splits) {
+  if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
+  if (n_splits < 0 || n_splits > 1024) MC_FAIL(MC_ERR_INVALID, "n_splits %d outside [0, 1024]", n_splits);
+  s->prefix_splits = n_splits;
+  return MC_OK;
+}
+
+extern "C" const char *mc_last_error(void) { return g_err; }
+
+// ---- timing ----------------------------------------------------------------------------
+extern "C" int mc_profile_begin(mc_session *s, int32_t kernel_class, int32_t stride) {
+  if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
+  if (kernel_class < 0 || kernel_class >= MC_K_COUNT) MC_FAIL(MC_ERR_INVALID, "unknown kernel class %d", kernel_class);
+  if (stride < 1) MC_FAIL(MC_ERR_INVALID, "stride must be >= 1");
+  MC_HIP(hipSetDevice(s->m->device));
+  if (kernel_class != MC_K_NONE && s->prof_ev.empty()) {
+    s->prof_ev.resize(2 * kProfCap);
+    for (auto &e : s->prof_ev) MC_HIP(hipEventCreate(&e));
+  }
+  s->prof_class = kernel_class;
+  s->prof_stride = stride;
+  s->prof_seen = 0;
+  s->prof_n = 0;
+  return MC_OK;
+}
+
+extern "C" int mc_profile_end(mc_session *s, int32_t *n_timed, double *total_ms) {
+  if (!s || !n_timed || !total_ms) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  MC_HIP(hipStreamSynchronize(s->stream));
+  double tot = 0.0;
+  for (int i = 0; i < s->prof_n; ++i) {
+    float ms = 0.f;
+    MC_HIP(hipEventElapsedTime(&ms, s->prof_ev[2 * i], s->prof_ev[2 * i + 1]));
+    tot += ms;
+  }
+  *n_timed = s->prof_n;
+  *total_ms = tot;
+  s->prof_class = MC_K_NONE;
+  return MC_OK;
+}

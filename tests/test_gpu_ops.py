@@ -1,0 +1,205 @@
+"""Kernel-level parity: each single-operation entry point against the CPU oracle."""
+import numpy as np
+import pytest
+
+from oracle import sampling as osamp
+from oracle import transformer as otf
+from paper_2601_05475_amd import binding, synth
+
+from gpu_common import check_sampler_on_logits
+
+pytestmark = pytest.mark.gpu
+
+
+def to_dev(a, dtype):
+    """numpy fp32 values -> device tensor of the model dtype; returns (tensor, values as fp32)."""
+    import torch
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda(), np.asarray(a, np.float32)
+    t = torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(torch.bfloat16)
+    return t.cuda(), t.to(torch.float32).numpy()
+
+
+def rnd(seed, shape, std=1.0):
+    return synth.normal(seed, 9, shape, 0.0, std, "f32")
+
+
+TOL = {"f32": 2e-5, "bf16": 1e-2}      # relative to the output scale; bf16 outputs are rounded
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_add_rmsnorm(dtype):
+    import torch
+    rows, d, S = 5, 300, 3
+    x = rnd(1, (rows, d)); parts = rnd(2, (S, rows, d), 0.3); g = 1 + rnd(3, (d,), 0.1)
+    gd, gv = to_dev(g, dtype)
+    xd = torch.from_numpy(x.copy()).cuda(); pd = torch.from_numpy(parts).cuda()
+    h = binding.op_add_rmsnorm(xd, pd, gd, 1e-6)
+    xs = x.astype(np.float64) + parts.astype(np.float64).sum(0)
+    np.testing.assert_allclose(xd.cpu().numpy(), xs, rtol=0, atol=1e-6)
+    want = otf.rmsnorm(xs, gv, 1e-6)
+    np.testing.assert_allclose(h.float().cpu().numpy(), want, rtol=0, atol=TOL[dtype] * 4)
+    h0 = binding.op_add_rmsnorm(xd, None, gd, 1e-6)          # no partials: x untouched
+    np.testing.assert_array_equal(h0.float().cpu().numpy(), h.float().cpu().numpy())
+
+
+@pytest.mark.parametrize("dtype,M,N,K,S", [
+    ("f32", 3, 70, 100, 1), ("f32", 3, 70, 100, 3), ("f32", 130, 65, 33, 1),
+    ("bf16", 4, 96, 200, 2), ("bf16", 32, 256, 512, 4), ("bf16", 16, 3072, 2048, 1),
+    ("bf16", 200, 128, 256, 1), ("bf16", 33, 130, 72, 1),
+])
+def test_linear(dtype, M, N, K, S):
+    a = rnd(4, (M, K)); w = rnd(5, (N, K), 0.05)
+    ad, av = to_dev(a, dtype); wd, wv = to_dev(w, dtype)
+    print("case: linear", dtype, M, N, K, S, flush=True)
+    out = binding.op_linear(ad, wd, S).cpu().numpy().astype(np.float64).sum(0)
+    want = otf.linear(av, wv)
+    np.testing.assert_allclose(out, want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
+
+
+@pytest.mark.parametrize("dtype,M,N,K", [("f32", 5, 70, 100), ("bf16", 4, 96, 200), ("bf16", 32, 512, 256),
+                                         ("bf16", 150, 128, 128)])
+def test_linear_swiglu(dtype, M, N, K):
+    a = rnd(6, (M, K)); wg = rnd(7, (N, K), 0.2); wu = rnd(8, (N, K), 0.2)
+    ad, av = to_dev(a, dtype); gd, gv = to_dev(wg, dtype); ud, uv = to_dev(wu, dtype)
+    out = binding.op_linear_swiglu(ad, gd, ud).float().cpu().numpy()
+    want = otf.silu(otf.linear(av, gv)) * otf.linear(av, uv)
+    np.testing.assert_allclose(out, want, rtol=0, atol=TOL[dtype] * np.abs(want).max())
+
+
+def make_pools(dtype, n_pages, Hkv, pg, hd, seed):
+    """Random K / V page pools in the library's layout; returns device tensors and fp32 views
+    k[page, kvh, j, :], v[page, kvh, j, :] (v un-transposed for the oracle)."""
+    k = rnd(seed, (n_pages, Hkv, pg, hd)); v = rnd(seed + 1, (n_pages, Hkv, pg, hd))
+    kd, kv = to_dev(k, dtype)
+    vd, vv = to_dev(np.ascontiguousarray(v.transpose(0, 1, 3, 2)), dtype)
+    return kd, vd, kv, vv.transpose(0, 1, 3, 2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rope_kv_write(dtype):
+    import torch
+    rows, Hq, Hkv, hd, pg, S, base = 7, 4, 2, 64, 8, 2, 10000.0
+    nq = (Hq + 2 * Hkv) * hd
+    qkv = rnd(10, (S, rows, nq))
+    pos = np.array([0, 1, 5, 130, 4095, 17000, 3], np.int32)
+    page = np.array([3, 0, 2, 2, 1, 4, 0], np.int32)
+    off = np.array([0, 7, 1, 2, 5, 6, 3], np.int32)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    kp = torch.zeros((5, Hkv, pg, hd), dtype=tdt, device="cuda")
+    vp = torch.zeros((5, Hkv, hd, pg), dtype=tdt, device="cuda")
+    q = binding.op_rope_kv_write(torch.from_numpy(qkv).cuda(), torch.from_numpy(pos).cuda(),
+                                 torch.from_numpy(page).cuda(), torch.from_numpy(off).cuda(),
+                                 Hq, Hkv, hd, pg, base, kp, vp)
+    full = qkv.astype(np.float64).sum(0).reshape(rows, Hq + 2 * Hkv, hd)
+    wq = otf.rope(full[:, :Hq], pos, base)
+    wk = otf.rope(full[:, Hq:Hq + Hkv], pos, base)
+    wv = full[:, Hq + Hkv:]
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    np.testing.assert_allclose(q.float().cpu().numpy(), wq, rtol=0, atol=tol)
+    kh, vh = kp.float().cpu().numpy(), vp.float().cpu().numpy()
+    for r in range(rows):
+        np.testing.assert_allclose(kh[page[r], :, off[r], :], wk[r], rtol=0, atol=tol)
+        np.testing.assert_allclose(vh[page[r], :, :, off[r]], wv[r], rtol=0, atol=tol)
+    written = np.zeros((5, pg), bool); written[page, off] = True
+    assert np.all(kh[~written[:, None, :, None].repeat(Hkv, 1).repeat(hd, 3)] == 0)
+
+
+def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20):
+    import torch
+    n_pre = -(-P // pg) if P else 0
+    per = -(-t // pg) if t else 0
+    kpd, vpd, kpv, vpv = make_pools(dtype, max(n_pre, 1), Hkv, pg, hd, seed)
+    ksd, vsd, ksv, vsv = make_pools(dtype, max(B * per, 1), Hkv, pg, hd, seed + 2)
+    table = np.random.default_rng(seed).permutation(max(B * per, 1)).astype(np.int32).reshape(B, -1) if per else np.zeros((B, 1), np.int32)
+    q = rnd(seed + 4, (B, Hq, hd))
+    qd, qv = to_dev(q, dtype)
+    print("case: attention", dtype, B, Hq, Hkv, hd, pg, P, t, splits, flush=True)
+    out = binding.op_attention_decode(qd, kpd if P else None, vpd if P else None, ksd if t else None,
+                                      vsd if t else None, torch.from_numpy(table).cuda() if t else None,
+                                      P, t, pg, splits).float().cpu().numpy()
+    G = Hq // Hkv
+    worst = 0.0
+    for b in range(B):
+        for a in range(Hq):
+            c = a // G
+            keys = [kpv[:, c].reshape(-1, hd)[:P]] if P else []
+            vals = [vpv[:, c].reshape(-1, hd)[:P]] if P else []
+            if t:
+                keys.append(ksv[table[b, :per], c].reshape(-1, hd)[:t])
+                vals.append(vsv[table[b, :per], c].reshape(-1, hd)[:t])
+            want = otf.attention_one(qv[b, a], np.concatenate(keys), np.concatenate(vals))
+            worst = max(worst, np.abs(out[b, a] - want).max())
+    return worst, out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,hd,pg,P,t", [
+    (4, 4, 2, 64, 4, 128, 16), (3, 8, 2, 128, 64, 300, 70), (2, 4, 4, 32, 8, 0, 9),
+    (5, 6, 2, 64, 16, 77, 0), (1, 4, 1, 128, 64, 1, 1), (32, 32, 8, 128, 64, 1024, 130),
+])
+def test_attention_decode(dtype, B, Hq, Hkv, hd, pg, P, t):
+    worst, _ = attention_case(dtype, B, Hq, Hkv, hd, pg, P, t)
+    assert worst < (2e-5 if dtype == "f32" else 1.5e-2), worst
+
+
+def test_attention_split_count_invariance():
+    outs = [attention_case("bf16", 8, 32, 8, 128, 64, 2048, 100, splits=s)[1] for s in (1, 2, 8, 32)]
+    for o in outs[1:]:
+        np.testing.assert_allclose(o, outs[0], rtol=0, atol=8e-3)   # bf16 output rounding only
+
+
+def test_sample_op_cases():
+    import torch
+    V, B = 128256, 32
+    lg = rnd(30, (B, V), 1.28)
+    us = synth.uniforms(31, 1, (B,))
+    ld, ud = torch.from_numpy(lg).cuda(), torch.from_numpy(us).cuda()
+    toks, topk = binding.op_sample(ld, 0.7, 50, ud, want_topk=True)
+    toks, topk = toks.cpu().numpy(), topk.cpu().numpy()
+    ok = sum(check_sampler_on_logits(lg[b], 0.7, 50, us[b], toks[b], topk[b]) for b in range(B))
+    assert ok >= B - 1
+    # shared row: every candidate reads row 0
+    t2 = binding.op_sample(ld, 0.7, 50, ud, shared_row=True).cpu().numpy()
+    for b in range(B):
+        check_sampler_on_logits(lg[0], 0.7, 50, us[b], t2[b])
+    # all logits equal: the floor(u k)-th lowest id; k not a power of two; ties cut by id
+    eq = torch.zeros((4, 4096), device="cuda")
+    u4 = torch.tensor([0.0, 0.26, 0.5, 0.99], device="cuda")
+    t3, k3 = binding.op_sample(eq, 0.7, 10, u4, want_topk=True)
+    assert t3.cpu().tolist() == [0, 2, 5, 9] and k3.cpu().numpy().tolist() == [list(range(10))] * 4
+    # duplicates straddling the cut, negative values, -0.0 vs +0.0
+    row = np.array([1.0, -0.0, 0.0, 1.0, -3.0, 0.0, 1.0, 2.0] + [-9.0] * 56, np.float32)
+    t4, k4 = binding.op_sample(torch.from_numpy(row[None]).cuda(), 1.0, 5, torch.tensor([0.999], device="cuda"), want_topk=True)
+    assert k4.cpu().numpy().tolist() == [[7, 0, 3, 6, 1]]
+    assert check_sampler_on_logits(row, 1.0, 5, 0.999, int(t4.cpu()[0]))
+    # argmax, lowest id on ties
+    g = binding.op_sample(torch.from_numpy(row[None]).cuda(), 0.0, 5, torch.tensor([0.5], device="cuda"))
+    assert int(g.cpu()[0]) == 7
+    g = binding.op_sample(eq, 1.0, 1, u4)
+    assert g.cpu().tolist() == [0, 0, 0, 0]
+    # u just below 1 -> last entry; tiny vocab below k
+    small = torch.from_numpy(rnd(32, (2, 7))).cuda()
+    t5, k5 = binding.op_sample(small, 0.9, 50, torch.tensor([1 - 2 ** -24, 0.0], device="cuda"), want_topk=True)
+    assert k5.shape == (2, 7) and int(t5.cpu()[0]) == int(k5.cpu()[0, -1]) and int(t5.cpu()[1]) == int(k5.cpu()[1, 0])
+
+
+def test_reward_score_op():
+    import torch
+    V, B, R = 128256, 64, 8
+    lg = rnd(40, (B, V), 1.28)
+    ids = synth.reward_token_ids(synth.WORKLOADS["8b-rerank"], R)
+    vals = np.arange(R, dtype=np.float32)
+    lp, sc, rk = binding.op_reward_score(torch.from_numpy(lg).cuda(), torch.from_numpy(ids).cuda(),
+                                         torch.from_numpy(vals).cuda(), 0.7)
+    lp, sc, rk = lp.cpu().numpy(), sc.cpu().numpy(), rk.cpu().numpy()
+    want_lp = np.stack([osamp.reward_logprobs(lg[b], ids) for b in range(B)])
+    np.testing.assert_allclose(lp, want_lp, rtol=0, atol=2e-5)
+    want_sc = np.array([osamp.expected_value(want_lp[b], vals, 0.7) for b in range(B)])
+    np.testing.assert_allclose(sc, want_sc, rtol=0, atol=2e-5)
+    assert list(rk) == list(osamp.rank(sc))
+    # equal reward logits with labels 0..4 -> exactly 2; ties ranked by index
+    flat = np.zeros((3, 100), np.float32); flat[1, 50] = 5.0
+    lp, sc, rk = binding.op_reward_score(torch.from_numpy(flat).cuda(), torch.arange(5, dtype=torch.int32, device="cuda"),
+                                         torch.arange(5, dtype=torch.float32, device="cuda"), 1.0)
+    assert sc.cpu().tolist() == [2.0, 2.0, 2.0] and rk.cpu().tolist() == [0, 1, 2]

@@ -1,0 +1,205 @@
+"""End-to-end parity of the four calls against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+
+from oracle import paging as opaging
+from oracle import sampling as osamp
+from paper_2601_05475_amd import binding, synth
+
+from gpu_common import (SAMPLE_MARGIN, assert_logits_close, check_sampler_on_logits, oracle_shared,
+                        teacher_forced_gpu)
+from helpers import small_shape
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    wl = synth.WORKLOADS["tiny"]
+    w = synth.make_weights(wl.shape, wl.seed_weights)
+    return wl, w
+
+
+def test_tiny_config_teacher_forced_logits_pages_and_sampler(tiny):
+    """The tiny fp32 workload as specified: 128-token prefix, 4 candidates, 16 steps, pages of 4."""
+    wl, w = tiny
+    s = wl.shape
+    prefix, suffix, us = synth.prefix_tokens(wl), synth.suffix_tokens(wl), synth.step_uniforms(wl)
+    B, N = suffix.shape
+    print("case: tiny teacher-forced", s, flush=True)
+    pl, steps, sess, model = teacher_forced_gpu(s, w, prefix, suffix, wl.page_tokens)
+    want_pl, want = oracle_shared(s, w, prefix, suffix)
+    assert_logits_close(pl[None], want_pl[None], "f32", "prefix logits")
+    assert_logits_close(steps, want, "f32", "decode logits")
+    tab, n = sess.page_table()
+    ref = opaging.page_tables(B, N, wl.page_tokens, range(sess.pool_pages()))
+    assert list(n) == [ref.shape[1]] * B
+    np.testing.assert_array_equal(tab[:, :ref.shape[1]], ref)
+
+
+def test_tiny_sampler_on_device_logits(tiny):
+    wl, w = tiny
+    s = wl.shape
+    prefix, suffix, us = synth.prefix_tokens(wl, 40), synth.suffix_tokens(wl, 4, 6), synth.step_uniforms(wl, 4, 7)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, 64, 4, 8, 4)
+    sess.prefill_shared(prefix)
+    row = sess.logits(1)[0]
+    toks, topk = sess.sample(4, wl.temperature, wl.top_k, us[0], want_topk=True)
+    for b in range(4):
+        check_sampler_on_logits(row, wl.temperature, wl.top_k, us[0][b], toks[b], topk[b])
+    exact = 0
+    for t in range(6):
+        sess.decode_step(suffix[:, t])
+        lg = sess.logits(4)
+        toks, topk = sess.sample(4, wl.temperature, wl.top_k, us[t + 1], want_topk=True)
+        for b in range(4):
+            exact += check_sampler_on_logits(lg[b], wl.temperature, wl.top_k, us[t + 1][b], toks[b], topk[b])
+    assert exact >= 22          # excuses must stay rare
+    # greedy and full-vocabulary modes
+    g = sess.sample(4, 0.0, 50, us[0])
+    assert list(g) == [int(np.argmax(lg[b])) for b in range(4)]
+    toks, topk = sess.sample(4, 1.0, 0, us[1], want_topk=True)
+    assert topk.shape == (4, s.vocab)
+    for b in range(4):
+        check_sampler_on_logits(lg[b], 1.0, 0, us[1][b], toks[b], topk[b])
+
+
+def test_free_running_matches_oracle(tiny):
+    """Sample, feed back, repeat: the sequences equal the oracle's, apart from steps the oracle
+    marks ambiguous (after such a step nothing more is compared for that candidate)."""
+    from oracle import transformer as otf
+    from helpers import oracle_config
+    wl, w = tiny
+    s = wl.shape
+    cfg = oracle_config(s)
+    P, B, N = 32, 4, 8
+    prefix, us = synth.prefix_tokens(wl, P), synth.step_uniforms(wl, B, N)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P, B, N, 4)
+    sess.prefill_shared(prefix)
+    got = []
+    for t in range(N):
+        toks = sess.sample(B, wl.temperature, wl.top_k, us[t])
+        got.append(toks.copy())
+        sess.decode_step(None if t % 2 else toks, B)      # alternate host / device hand-over
+    got = np.stack(got, 1)                                  # [B, N]
+    plog, pcache = otf.forward(cfg, w, prefix)
+    compared = 0
+    for b in range(B):
+        cache, lg = pcache.copy(), plog[-1]
+        for t in range(N):
+            tok, _, margin = osamp.sample(lg.astype(np.float32), wl.temperature, wl.top_k, us[t][b])
+            if margin < 20 * SAMPLE_MARGIN:     # fp32 logits differ in the last bits too
+                break
+            assert tok == got[b, t], (b, t)
+            compared += 1
+            lg = otf.forward(cfg, w, np.array([tok]), cache)[0][0]
+    assert compared >= B * N // 2
+
+
+def test_physical_page_order_and_candidate_order_do_not_matter(tiny):
+    wl, w = tiny
+    s = wl.shape
+    prefix, suffix = synth.prefix_tokens(wl, 50), synth.suffix_tokens(wl, 4, 10)
+    _, base, sess, _ = teacher_forced_gpu(s, w, prefix, suffix, 4)
+    n = sess.pool_pages()
+    perm = np.random.default_rng(0).permutation(n).astype(np.int32)
+    _, shuffled, sess2, _ = teacher_forced_gpu(s, w, prefix, suffix, 4, free_list=perm)
+    np.testing.assert_array_equal(base, shuffled)                 # bit-identical
+    tab, cnt = sess2.page_table()
+    ref = opaging.page_tables(4, 10, 4, perm)
+    np.testing.assert_array_equal(tab[:, :ref.shape[1]], ref)
+    order = np.array([2, 0, 3, 1])
+    _, permuted, _, _ = teacher_forced_gpu(s, w, prefix, suffix[order], 4)
+    np.testing.assert_array_equal(permuted, base[:, order])
+
+
+def test_reset_keeps_prefix_and_state_errors(tiny):
+    wl, w = tiny
+    s = wl.shape
+    prefix, suffix = synth.prefix_tokens(wl, 20), synth.suffix_tokens(wl, 3, 5)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, 32, 4, 5, 4)
+    with pytest.raises(binding.McError) as e:
+        sess.decode_step(suffix[:, 0])
+    assert e.value.code == -2
+    with pytest.raises(binding.McError) as e:
+        sess.sample(3, 0.8, 50, np.zeros(3, np.float32))
+    assert e.value.code == -2
+    sess.prefill_shared(prefix)
+    first = sess.logits(1).copy()
+    runs = []
+    for rep in range(2):
+        out = []
+        for t in range(5):
+            sess.decode_step(suffix[:, t])
+            out.append(sess.logits(3))
+        runs.append(np.stack(out))
+        with pytest.raises(binding.McError) as e:      # suffix capacity reached
+            sess.decode_step(suffix[:, 0])
+        assert e.value.code == -3
+        sess.reset_candidates()
+        np.testing.assert_array_equal(sess.logits(1), first)
+    np.testing.assert_array_equal(runs[0], runs[1])
+    # argument errors leave the session usable
+    bad = suffix[:, 0].copy(); bad[1] = s.vocab
+    for call in (lambda: sess.decode_step(bad), lambda: sess.decode_step(suffix[:, 0][:2].repeat(3)[:5]),
+                 lambda: sess.sample(3, 0.8, 50, np.array([0.1, 1.0, 0.2], np.float32)),
+                 lambda: sess.prefill_shared(np.zeros(33, np.int32))):
+        with pytest.raises(binding.McError) as e:
+            call()
+        assert e.value.code == -1
+    sess.decode_step(suffix[:, 0])
+    np.testing.assert_array_equal(sess.logits(3), runs[0][0])
+
+
+def test_score_candidates_tiny(tiny):
+    """Reranking on the tiny shape with ragged suffixes; the paper's five labels 0..4."""
+    wl, w = tiny
+    s = wl.shape
+    B, Ls = 6, 11
+    prefix, suffix = synth.prefix_tokens(wl, 45), synth.suffix_tokens(wl, B, Ls)
+    lens = np.array([11, 3, 7, 1, 11, 4], np.int32)
+    ids = synth.reward_token_ids(wl, 5)
+    vals = np.arange(5, dtype=np.float32)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, 64, B, 12, 4, chunk_rows=16)     # forces several chunks
+    sess.prefill_shared(prefix)
+    lp, sc, rk = sess.score_candidates(suffix, lens, ids, vals, 0.7)
+    _, ref = oracle_shared(s, w, prefix, suffix)                  # [Ls, B, V]
+    want_lp = np.stack([osamp.reward_logprobs(ref[lens[b] - 1, b], ids) for b in range(B)])
+    np.testing.assert_allclose(lp, want_lp, rtol=0, atol=1e-4)
+    want_sc = np.array([osamp.expected_value(want_lp[b], vals, 0.7) for b in range(B)])
+    np.testing.assert_allclose(sc, want_sc, rtol=0, atol=1e-4)
+    # ranking: exact on the device's own scores; equals the oracle's where gaps are clear
+    assert list(rk) == list(osamp.rank(sc))
+    gaps = np.abs(np.diff(np.sort(want_sc)))
+    if gaps.min() > 1e-3:
+        assert list(rk) == list(osamp.rank(want_sc))
+    got_logits = sess.logits(B)
+    assert_logits_close(got_logits, np.stack([ref[lens[b] - 1, b] for b in range(B)]), "f32", "score logits")
+    # scoring leaves the decode state alone: decoding afterwards equals decoding without it
+    sess.decode_step(suffix[:4, 0])
+    a = sess.logits(4)
+    assert_logits_close(a, ref[0, :4], "f32", "decode after score")
+    with pytest.raises(binding.McError):
+        sess.score_candidates(suffix, lens, np.array([1, 1, 2, 3, 4]), vals)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, P=70, B=3, N=9, pg=8),
+    dict(L=1, d=192, Hq=6, Hkv=1, hd=64, F=96, V=777, P=1, B=5, N=5, pg=4),
+    dict(L=2, d=256, Hq=4, Hkv=4, hd=128, F=300, V=512, P=130, B=1, N=3, pg=16),
+])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_odd_shapes_both_dtypes(kw, dtype):
+    s = small_shape("odd", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 77)
+    prefix = synth.tokens(5, 1, (kw["P"],), s.vocab)
+    suffix = synth.tokens(5, 2, (kw["B"], kw["N"]), s.vocab)
+    print("case: odd shape", kw, dtype, flush=True)
+    pl, steps, _, _ = teacher_forced_gpu(s, w, prefix, suffix, kw["pg"], chunk_rows=32)
+    want_pl, want = oracle_shared(s, w, prefix, suffix)
+    assert_logits_close(pl[None], want_pl[None], dtype, "prefix logits")
+    assert_logits_close(steps, want, dtype, "decode logits")
