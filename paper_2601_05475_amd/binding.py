@@ -98,7 +98,14 @@ def load_library(path: str = LIB_PATH):
         if not os.path.exists(path):
             raise RuntimeError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                                "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  Import it first so that
+        # this library binds to the runtime that owns the arenas and streams, not a second copy.
+        import torch  # noqa: F401
         lib = C.CDLL(path)
+        with open("/proc/self/maps") as f:
+            runtimes = {ln.split()[-1] for ln in f if "libamdhip64" in ln}
+        if len(runtimes) > 1:
+            raise RuntimeError(f"two HIP runtimes in one process: {sorted(runtimes)}")
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
             fn.restype, fn.argtypes = res, args
