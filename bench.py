@@ -1,0 +1,181 @@
+"""Benchmark of the shared-prefix decode hot path on one MI355X.
+
+A "step" is one pass of the whole hot path for one batch: draw the next token of every
+candidate (temperature / top-k sampling from the pending logits) and run one decode step for
+all B candidates (embedding, 32 x {norm, QKV, RoPE + KV write, shared-prefix attention, O,
+norm, SwiGLU FFN}, final norm, LM head).  The workload is the 8B-shape headline configuration:
+B = 32 candidates on a 4096-token shared prefix, free-running sampling at T = 0.7 / top-k 50,
+seeded synthetic weights and token ids.  The prefix prefill is done before the timed region and
+reported separately.  Everything is resident in HBM when the clock starts; nothing crosses to
+the host inside the timed region (sampled ids stay on the device).
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+
+
+def gate_up_bytes(s, n_cands):
+    """Algorithmic bytes of one gate/up launch: both weight matrices once, the activations in
+    and the SwiGLU product out (bf16)."""
+    return 2 * s.d_ffn * s.d_model * 2 + n_cands * s.d_model * 2 + n_cands * s.d_ffn * 2
+
+
+def attention_bytes(s, n_cands, prefix_len, suffix_len):
+    """Algorithmic bytes of one decode-attention launch: prefix K and V once, every candidate's
+    suffix K and V once, q in and o out (bf16)."""
+    kv_tok = 2 * s.n_kv_heads * s.head_dim * 2
+    return prefix_len * kv_tok + n_cands * suffix_len * kv_tok + 2 * n_cands * s.n_q_heads * s.head_dim * 2
+
+
+def cpu_baseline(wl, weights, n_layers_sample=2, n_cands_sample=4):
+    """The oracle, as it stands, on a bounded sample of the same workload: one decode step at
+    suffix length 1 for `n_cands_sample` of the B candidates through `n_layers_sample` layers
+    (random bf16 prefix keys/values of the real shape) plus the final norm and LM head; times are
+    scaled linearly to all candidates and the full depth."""
+    from oracle import transformer as otf
+    from paper_2601_05475_amd import synth
+    s = wl.shape
+    cfg = otf.Config(s.n_layers, s.d_model, s.n_q_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab,
+                     s.rope_base, s.rms_eps, "bf16")
+    B, P = wl.n_cands, wl.prefix_len
+    layers = [{k: synth.bf16_bits_to_f32(v) for k, v in weights["layers"][l].items()} for l in range(n_layers_sample)]
+    head = {"final_norm": synth.bf16_bits_to_f32(weights["final_norm"]),
+            "lm_head": synth.bf16_bits_to_f32(weights["lm_head"])}
+    kv = [(synth.bf16_bits_to_f32(synth.normal(7, 50 + l, (P, s.n_kv_heads, s.head_dim), 0.0, 1.0, "bf16")).astype(np.float64),
+           synth.bf16_bits_to_f32(synth.normal(7, 80 + l, (P, s.n_kv_heads, s.head_dim), 0.0, 1.0, "bf16")).astype(np.float64))
+          for l in range(n_layers_sample)]
+    x0 = synth.bf16_bits_to_f32(weights["embed"][synth.suffix_tokens(wl, B, 1)[:, 0]]).astype(np.float64)
+    t0 = time.perf_counter()
+    outs = []
+    for b in range(n_cands_sample):            # candidates are independent sequences
+        x = x0[b:b + 1]
+        for l in range(n_layers_sample):
+            x, _, _ = otf.layer_forward(cfg, layers[l], x, np.array([P]), kv[l][0], kv[l][1])
+        outs.append(x)
+    t_layers = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    otf.lm_logits(cfg, head, np.concatenate(outs))
+    t_head = time.perf_counter() - t0
+    step_s = (t_layers / n_layers_sample * s.n_layers + t_head) * B / n_cands_sample
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": B / step_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one decode step (suffix length 1, prefix {P}) for {n_cands_sample} of {B} candidates "
+                      f"through {n_layers_sample} of {s.n_layers} layers + final norm + LM head, scaled "
+                      f"linearly to {B} candidates and {s.n_layers} layers ({t_layers:.1f} s layers, "
+                      f"{t_head:.1f} s head measured)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="8b", choices=["8b", "1b"])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (diagnosis only; marks the line invalid)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_05475_amd import binding, synth
+    binding.load_library()                      # raises if the HIP library is not built
+    wl = synth.WORKLOADS[args.workload]
+    s = wl.shape if not args.layers else wl.shape.with_layers(args.layers)
+    B, P = wl.n_cands, wl.prefix_len
+    K, W = args.steps, args.warmup
+    if K < 1 or K > wl.n_steps or W < 0 or W > wl.n_steps:
+        print(f"bench.py: steps must be in [1, {wl.n_steps}] and warmup in [0, {wl.n_steps}]", file=sys.stderr)
+        sys.exit(2)
+
+    t0 = time.perf_counter()
+    weights = synth.make_weights(s, wl.seed_weights)
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    model = binding.Model(s, weights)
+    sess = binding.Session(model, P, B, wl.n_steps, wl.page_tokens, chunk_rows=2048)
+    torch.cuda.synchronize()
+    t_upload = time.perf_counter() - t0
+
+    prefix = synth.prefix_tokens(wl)
+    us = synth.step_uniforms(wl, B, wl.n_steps)
+    t0 = time.perf_counter()
+    sess.prefill_shared(prefix)
+    sess.sync()
+    t_prefill = time.perf_counter() - t0
+
+    def run_steps(n):
+        for t in range(n):
+            sess.sample(B, wl.temperature, wl.top_k, us[t], want_tokens=False)
+            sess.decode_step(None, B)
+
+    run_steps(W)
+    sess.sync()
+    sess.reset_candidates()
+
+    # timed region; every 4th gate/up launch is bracketed by HIP events on the session stream
+    stride = max(1, (s.n_layers * K + 8191) // 8192)
+    sess.profile_begin("linear_gate_up", stride)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(K)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_gu, ms_gu = sess.profile_end()
+
+    # second pass (untimed): the decode-attention kernel, averaged over the same K steps
+    sess.reset_candidates()
+    sess.profile_begin("attn_decode", stride)
+    run_steps(K)
+    n_at, ms_at = sess.profile_end()
+    at_bytes = float(np.mean([attention_bytes(s, B, P, t + 1) for t in range(K)]))
+
+    gu_us = ms_gu * 1e3 / max(n_gu, 1)
+    at_us = ms_at * 1e3 / max(n_at, 1)
+    gu_gbs = gate_up_bytes(s, B) / gu_us / 1e3
+    at_gbs = at_bytes / at_us / 1e3
+    out = {
+        "metric": "generated tokens/s at B candidates (8B-shape decode); % HBM roofline attn",
+        "value": B * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shape decode: {s.n_layers} layers, d {s.d_model}, "
+                               f"{s.n_q_heads}/{s.n_kv_heads} heads of {s.head_dim}, FFN {s.d_ffn}, vocab {s.vocab}; "
+                               f"B={B} candidates, shared prefix {P}, suffix 0..{K}, T={wl.temperature}, top-k {wl.top_k}",
+                   "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens},
+        "roofline": {"bound": "hbm", "kernel": "skinny_linear_kernel (gate/up + SwiGLU)",
+                     "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "launches_timed": n_gu, "avg_us": gu_us},
+        "roofline_attn": {"bound": "hbm", "kernel": "decode attention (all launches of one layer-step)",
+                          "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
+                          "traffic": None, "launches_timed": n_at, "avg_us": at_us},
+        "prefill_s": t_prefill, "setup_s": {"generate_weights": t_gen, "upload_and_pack": t_upload},
+    }
+    if args.layers:
+        out["invalid"] = "layer count overridden"
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, weights)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

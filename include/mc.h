@@ -186,20 +186,37 @@ int mc_profile_end(mc_session *s, int32_t *n_timed, double *total_ms);
 /* All pointers below are DEVICE pointers unless marked host; `stream` is a hipStream_t
  * (NULL = default).  `dtype` selects float or bf16 for buffers marked (T). */
 
+/* Tiled operand layout of the bf16 MFMA linear kernels.  A [rows][K] matrix (K % 64 == 0) is
+ * stored as 4 KB blocks, rows padded to a multiple of 32: block (row / 32, k / 64) sits at byte
+ * ((row / 32) * (K / 64) + k / 64) * 4096, and inside it the 16-byte chunk c = (k % 32) / 8 of
+ * lane l = row % 32 + 32 * ((k % 64) / 32), at byte (c * 64 + l) * 16, holds the 8 elements
+ * k - k % 8 .. +7 of that row.  mc_op_tiled_bytes gives the buffer size (0 if K is unsuitable);
+ * mc_op_pack_tiled converts a row-major bf16 matrix (padding rows are zero-filled). */
+size_t mc_op_tiled_bytes(int32_t rows, int32_t K);
+int mc_op_pack_tiled(void *stream, int32_t rows, int32_t K, const void *src, void *dst);
+
 /* Residual update + RMSNorm: x[r][:] += sum_s partials[s][r][:] (n_partials may be 0),
- * then h[r][:] = (T)(x * gain / sqrt(mean(x^2) + eps)).  x: fp32 [rows][d], in/out. */
+ * then h[r][:] = (T)(x * gain / sqrt(mean(x^2) + eps)).  x: fp32 [rows][d], in/out.
+ * h_tiled = 1 stores h in the tiled layout (bf16, d % 64 == 0). */
 int mc_op_add_rmsnorm(void *stream, int32_t dtype, int32_t rows, int32_t d, float *x,
                       const float *partials, int32_t n_partials, const void *gain /*(T)[d]*/,
-                      float eps, void *h_out /*(T)[rows][d]*/);
+                      float eps, void *h_out /*(T)[rows][d]*/, int32_t h_tiled);
 
 /* out[s][m][n] = sum over the s-th K range of a[m][k] * w[n][k]; n_splits partial sums
- * (fp32) that add up to a * w^T.  a: (T)[M][K], w: (T)[N][K], out: fp32 [n_splits][M][N]. */
+ * (fp32, row-major) that add up to a * w^T.  a: (T)[M][K], w: (T)[N][K], out: fp32
+ * [n_splits][M][N].  tiled = 1: a and w are in the tiled layout (bf16, N % 128 == 0,
+ * K % 256 == 0; M <= 64 streams the weights once and n_splits must divide K / 256; larger M
+ * runs the MFMA GEMM with n_splits = 1).  mc_op_linear_splits: the split count the session
+ * would choose. */
 int mc_op_linear(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K, const void *a,
-                 const void *w, float *out, int32_t n_splits);
+                 const void *w, float *out, int32_t n_splits, int32_t tiled);
+int32_t mc_op_linear_splits(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t tiled);
 
-/* out[m][n] = (T)( silu(a . w_gate[n]) * (a . w_up[n]) ).  out: (T)[M][N]. */
+/* out[m][n] = (T)( silu(a . w_gate[n]) * (a . w_up[n]) ).  out: (T)[M][N]; with tiled = 1 the
+ * inputs and the output are tiled. */
 int mc_op_linear_swiglu(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K,
-                        const void *a, const void *w_gate, const void *w_up, void *out);
+                        const void *a, const void *w_gate, const void *w_up, void *out,
+                        int32_t tiled);
 
 /* Sum the n_splits partial QKV rows, rotate q and k of row r by position row_pos[r],
  * store q as (T)[rows][Hq][hd] and write k, v of row r into KV page row_page[r] at
@@ -215,7 +232,8 @@ int mc_op_rope_kv_write(void *stream, int32_t dtype, int32_t rows, int32_t n_q_h
  * prefix_len keys of the shared prefix (pages 0.. of k_prefix/v_prefix, in order) and
  * to its own suffix_len keys (pages page_table[b][0..] of k_suffix/v_suffix).
  * q, out: (T)[n_cands][Hq][hd].  workspace: fp32 scratch of mc_op_attention_decode_ws
- * bytes.  prefix_splits: key-axis splits of the prefix (0 = automatic). */
+ * bytes.  prefix_splits: key-axis splits of the prefix (0 = automatic).  out_tiled = 1 stores
+ * out as a tiled [n_cands][Hq*hd] matrix. */
 size_t mc_op_attention_decode_ws(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
                                  int32_t head_dim, int32_t prefix_len, int32_t suffix_len,
                                  int32_t page_tokens);
@@ -225,7 +243,7 @@ int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t
                            const void *k_prefix, const void *v_prefix, const void *k_suffix,
                            const void *v_suffix, const int32_t *page_table,
                            int32_t table_stride, int32_t prefix_splits, void *workspace,
-                           size_t workspace_bytes, void *out);
+                           size_t workspace_bytes, void *out, int32_t out_tiled);
 
 /* Sampling from fp32 logits [rows][vocab] (row_stride 0 = every candidate reads row 0).
  * uniforms: device [n_cands].  out_tokens: device [n_cands]; out_topk: device

@@ -19,6 +19,16 @@ the architecture open; the readings taken here are:
 Weights arrive as fp32 arrays (for bf16 models: the bf16 values widened, i.e. the
 same numbers the GPU holds); everything else is float64.
 
+Precision of bf16 models.  The bf16 workloads are specified as "bf16 weights and
+activations with fp32 accumulation".  Read literally, every activation tensor the
+model defines is a bf16 tensor: the RMSNorm outputs, q/k/v after the projection and
+rotation (which is also what the KV cache holds), the attention output and the SwiGLU
+product.  With ``Config.act_dtype == "bf16"`` the oracle rounds exactly those tensors
+to the nearest bf16 value (ties to even) and nothing else: the residual stream, all
+sums, the softmax and its probabilities stay float64.  With "f64" (default) nothing
+is rounded; that mode is the reference of fp32 models and shows how far bf16
+arithmetic itself is from exact.
+
 Parity pins live in tests/test_oracle_*.py: an element-by-element brute force on
 tiny shapes, closed forms for RMSNorm / RoPE / softmax, shared == unshared,
 decode == prefill.  Matrix products use numpy's matmul as a library step.
@@ -44,6 +54,22 @@ class Config:
     vocab: int
     rope_base: float
     rms_eps: float = 1e-6
+    act_dtype: str = "f64"        # "f64": nothing rounded; "bf16": activation tensors are bf16
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 value (8 significand bits, ties to even) of each element, as float64.
+
+    Done on the fp32 bit pattern: add 0x7FFF plus the lowest kept bit, clear the low 16 bits."""
+    f = np.ascontiguousarray(x, np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(F64)
+
+
+def store(cfg: "Config", x: np.ndarray) -> np.ndarray:
+    """An activation tensor as the model holds it."""
+    return round_bf16(x) if cfg.act_dtype == "bf16" else np.asarray(x, F64)
 
 
 def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
@@ -122,30 +148,30 @@ def layer_forward(cfg: Config, lw: Dict[str, np.ndarray], x: np.ndarray, pos: np
     Returns (x_out, k_all, v_all)."""
     T = x.shape[0]
     Hq, Hkv, hd = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
-    h = rmsnorm(x, lw["attn_norm"], cfg.rms_eps)
+    h = store(cfg, rmsnorm(x, lw["attn_norm"], cfg.rms_eps))
     q = (h @ np.asarray(lw["wq"], F64).T).reshape(T, Hq, hd)
     k = (h @ np.asarray(lw["wk"], F64).T).reshape(T, Hkv, hd)
-    v = (h @ np.asarray(lw["wv"], F64).T).reshape(T, Hkv, hd)
-    q = rope(q, pos, cfg.rope_base)
-    k = rope(k, pos, cfg.rope_base)
+    v = store(cfg, (h @ np.asarray(lw["wv"], F64).T).reshape(T, Hkv, hd))
+    q = store(cfg, rope(q, pos, cfg.rope_base))
+    k = store(cfg, rope(k, pos, cfg.rope_base))
     if k_past is not None:
         k_all = np.concatenate([k_past, k], axis=0)
         v_all = np.concatenate([v_past, v], axis=0)
         k_pos = np.concatenate([np.arange(k_past.shape[0]), np.asarray(pos)])
     else:
         k_all, v_all, k_pos = k, v, np.asarray(pos)
-    o = attention(q, k_all, v_all, pos, k_pos).reshape(T, Hq * hd)
+    o = store(cfg, attention(q, k_all, v_all, pos, k_pos).reshape(T, Hq * hd))
     x = x + o @ np.asarray(lw["wo"], F64).T
-    h2 = rmsnorm(x, lw["ffn_norm"], cfg.rms_eps)
+    h2 = store(cfg, rmsnorm(x, lw["ffn_norm"], cfg.rms_eps))
     gate = h2 @ np.asarray(lw["w_gate"], F64).T
     up = h2 @ np.asarray(lw["w_up"], F64).T
-    x = x + (silu(gate) * up) @ np.asarray(lw["w_down"], F64).T
+    x = x + store(cfg, silu(gate) * up) @ np.asarray(lw["w_down"], F64).T
     return x, k_all, v_all
 
 
 def lm_logits(cfg: Config, w: Dict[str, object], x: np.ndarray) -> np.ndarray:
     """Final RMSNorm and LM head on rows x [T, d] -> [T, V]."""
-    return rmsnorm(x, w["final_norm"], cfg.rms_eps) @ np.asarray(w["lm_head"], F64).T
+    return store(cfg, rmsnorm(x, w["final_norm"], cfg.rms_eps)) @ np.asarray(w["lm_head"], F64).T
 
 
 def forward(cfg: Config, w: Dict[str, object], tokens: np.ndarray,

@@ -78,12 +78,15 @@ SIGNATURES = {
     "mc_last_error": (C.c_char_p, []),
     "mc_profile_begin": (C.c_int, [_vp, _i32, _i32]),
     "mc_profile_end": (C.c_int, [_vp, _pi32, C.POINTER(C.c_double)]),
-    "mc_op_add_rmsnorm": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _i32, _vp, _f32, _vp]),
-    "mc_op_linear": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32]),
-    "mc_op_linear_swiglu": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "mc_op_tiled_bytes": (_sz, [_i32, _i32]),
+    "mc_op_pack_tiled": (C.c_int, [_vp, _i32, _i32, _vp, _vp]),
+    "mc_op_add_rmsnorm": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _i32, _vp, _f32, _vp, _i32]),
+    "mc_op_linear": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _i32]),
+    "mc_op_linear_splits": (_i32, [_i32] * 5),
+    "mc_op_linear_swiglu": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32]),
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
-    "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp]),
+    "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _i32]),
     "mc_op_sample": (C.c_int, [_vp, _i32, _i32, _vp, _sz, _f32, _i32, _vp, _vp, _vp]),
     "mc_op_reward_score": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
 }
@@ -296,36 +299,73 @@ def _code_of(t) -> int:
     return {torch.float32: MC_F32, torch.bfloat16: MC_BF16}[t.dtype]
 
 
-def op_add_rmsnorm(x, partials, gain, eps: float):
-    """x: fp32 [rows, d] (updated in place); partials: fp32 [S, rows, d] or None.  Returns h."""
+def op_pack_tiled(t):
+    """Row-major bf16 [rows, K] -> the tiled layout (a flat bf16 tensor of padded size)."""
     import torch
-    rows, d = x.shape
-    h = torch.empty((rows, d), dtype=gain.dtype, device=x.device)
-    S = 0 if partials is None else partials.shape[0]
-    _check(load_library().mc_op_add_rmsnorm(_stream(), _code_of(gain), rows, d, x.data_ptr(),
-                                            None if partials is None else partials.data_ptr(), S,
-                                            gain.data_ptr(), eps, h.data_ptr()))
-    return h
-
-
-def op_linear(a, w, n_splits: int = 1):
-    """a: [M, K], w: [N, K] (same dtype).  Returns fp32 [n_splits, M, N] partial sums."""
-    import torch
-    M, K = a.shape
-    N = w.shape[0]
-    out = torch.empty((n_splits, M, N), dtype=torch.float32, device=a.device)
-    _check(load_library().mc_op_linear(_stream(), _code_of(a), M, N, K, a.data_ptr(), w.data_ptr(),
-                                       out.data_ptr(), n_splits))
+    rows, K = t.shape
+    lib = load_library()
+    nbytes = lib.mc_op_tiled_bytes(rows, K)
+    if nbytes == 0:
+        raise McError(-1, "K must be a positive multiple of 64")
+    out = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=t.device)
+    _check(lib.mc_op_pack_tiled(_stream(), rows, K, t.contiguous().data_ptr(), out.data_ptr()))
     return out
 
 
-def op_linear_swiglu(a, w_gate, w_up):
+def tiled_to_rowmajor(flat, rows: int, K: int):
+    """Inverse of the tiled layout on the host (numpy/torch indexing only), for checks."""
+    rp = (rows + 31) // 32 * 32
+    v = flat.reshape(rp // 32, K // 64, 4, 2, 32, 8)          # [rt][u][c][h][row][j]
+    return v.permute(0, 4, 1, 3, 2, 5).reshape(rp, K)[:rows]
+
+
+def op_add_rmsnorm(x, partials, gain, eps: float, tiled: bool = False):
+    """x: fp32 [rows, d] (updated in place); partials: fp32 [S, rows, d] or None.  Returns h
+    ([rows, d], or the flat tiled buffer when tiled)."""
     import torch
-    M, K = a.shape
-    N = w_gate.shape[0]
-    out = torch.empty((M, N), dtype=a.dtype, device=a.device)
+    rows, d = x.shape
+    if tiled:
+        h = torch.zeros(load_library().mc_op_tiled_bytes(rows, d) // 2, dtype=gain.dtype, device=x.device)
+    else:
+        h = torch.empty((rows, d), dtype=gain.dtype, device=x.device)
+    S = 0 if partials is None else partials.shape[0]
+    _check(load_library().mc_op_add_rmsnorm(_stream(), _code_of(gain), rows, d, x.data_ptr(),
+                                            None if partials is None else partials.data_ptr(), S,
+                                            gain.data_ptr(), eps, h.data_ptr(), int(tiled)))
+    return h
+
+
+def op_linear(a, w, n_splits: int = 1, tiled_shape=None):
+    """a: [M, K], w: [N, K] (same dtype).  Returns fp32 [n_splits, M, N] partial sums.
+    tiled_shape=(M, N, K): a and w are flat tiled buffers."""
+    import torch
+    if tiled_shape is None:
+        M, K = a.shape
+        N = w.shape[0]
+    else:
+        M, N, K = tiled_shape
+    out = torch.empty((n_splits, M, N), dtype=torch.float32, device=a.device)
+    _check(load_library().mc_op_linear(_stream(), _code_of(a), M, N, K, a.data_ptr(), w.data_ptr(),
+                                       out.data_ptr(), n_splits, int(tiled_shape is not None)))
+    return out
+
+
+def op_linear_splits(dtype: str, M: int, N: int, K: int, tiled: bool) -> int:
+    return load_library().mc_op_linear_splits(_dtype_code(dtype), M, N, K, int(tiled))
+
+
+def op_linear_swiglu(a, w_gate, w_up, tiled_shape=None):
+    import torch
+    if tiled_shape is None:
+        M, K = a.shape
+        N = w_gate.shape[0]
+        out = torch.empty((M, N), dtype=a.dtype, device=a.device)
+    else:
+        M, N, K = tiled_shape
+        out = torch.zeros(load_library().mc_op_tiled_bytes(M, N) // 2, dtype=a.dtype, device=a.device)
     _check(load_library().mc_op_linear_swiglu(_stream(), _code_of(a), M, N, K, a.data_ptr(),
-                                              w_gate.data_ptr(), w_up.data_ptr(), out.data_ptr()))
+                                              w_gate.data_ptr(), w_up.data_ptr(), out.data_ptr(),
+                                              int(tiled_shape is not None)))
     return out
 
 
@@ -344,22 +384,25 @@ def op_rope_kv_write(qkv, row_pos, row_page, row_off, n_q_heads, n_kv_heads, hea
 
 
 def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, prefix_len,
-                        suffix_len, page_tokens, prefix_splits: int = 0):
+                        suffix_len, page_tokens, prefix_splits: int = 0, out_tiled: bool = False):
     """q: [B, Hq, hd]; pools: [n_pages, Hkv, pg, hd] (K) and [n_pages, Hkv, hd, pg] (V);
-    page_table: int32 [B, stride].  Returns out [B, Hq, hd]."""
+    page_table: int32 [B, stride].  Returns out [B, Hq, hd] (or the flat tiled [B, Hq*hd])."""
     import torch
     lib = load_library()
     B, Hq, hd = q.shape
     Hkv = (k_prefix if k_prefix is not None else k_suffix).shape[1]
     ws_bytes = lib.mc_op_attention_decode_ws(B, Hq, Hkv, hd, prefix_len, suffix_len, page_tokens)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=q.device)
-    out = torch.empty_like(q)
+    if out_tiled:
+        out = torch.zeros(lib.mc_op_tiled_bytes(B, Hq * hd) // 2, dtype=q.dtype, device=q.device)
+    else:
+        out = torch.empty_like(q)
     p = lambda t: None if t is None else t.data_ptr()
     _check(lib.mc_op_attention_decode(
         _stream(), _code_of(q), B, Hq, Hkv, hd, page_tokens, prefix_len, suffix_len, q.data_ptr(),
         p(k_prefix), p(v_prefix), p(k_suffix), p(v_suffix), p(page_table),
         0 if page_table is None else page_table.shape[1], prefix_splits, ws.data_ptr(), ws.numel(),
-        out.data_ptr()))
+        out.data_ptr(), int(out_tiled)))
     return out
 
 

@@ -62,6 +62,16 @@ inline size_t page_elems(int n_kv_heads, int head_dim, int page_tokens) {
   return (size_t)n_kv_heads * head_dim * page_tokens;
 }
 
+// ---- tiled operand layout of the bf16 MFMA kernels --------------------------------------
+// A [rows][K] matrix (rows padded to a multiple of 32, K % 64 == 0) is kept as 4 KB blocks;
+// block (row / 32, k / 64) holds, as chunk c = (k % 32) / 8 of lane l = row % 32 + 32 ((k % 64) / 32),
+// the 8 elements k - k % 8 .. +7.  This is the element offset of (row, k).
+__host__ __device__ inline size_t tiled_offset(int row, int k, int K) {
+  const int U = K >> 6;
+  return ((size_t)(row >> 5) * U + (k >> 6)) * 2048 +
+         (size_t)(((k & 31) >> 3) * 64 + (row & 31) + 32 * ((k & 63) >> 5)) * 8 + (k & 7);
+}
+
 // ---- kernel launchers (defined in kernels_*.hip) -----------------------------------
 // Every launcher validates nothing: callers (runtime.cpp, ops.cpp) check shapes first.
 
@@ -74,7 +84,8 @@ struct AttnArgs {
   int32_t table_stride;
   int32_t rows, n_q_heads, n_kv_heads, head_dim, page_tokens;
   int32_t prefix_len;            // keys at positions < prefix_len live in prefix pages pos / page_tokens
-  void *out;                     // (T)[rows][Hq][hd]
+  void *out;                     // (T)[rows][Hq][hd], or the tiled [rows][Hq*hd] layout
+  int32_t out_tiled;
 };
 
 struct DecodeAttnArgs {
@@ -88,18 +99,22 @@ struct DecodeAttnArgs {
   void *workspace;
   size_t workspace_bytes;
   void *out;
+  int32_t out_tiled;
 };
 
 int launch_embed(hipStream_t st, int dtype, int rows, int d, const int32_t *tokens,
                  const void *table, float *x);
 int launch_add_rmsnorm(hipStream_t st, int dtype, int rows, int d, float *x, const float *partials,
-                       int n_partials, const void *gain, float eps, void *h_out);
+                       int n_partials, const void *gain, float eps, void *h_out, int h_tiled);
 int launch_gather_rows(hipStream_t st, int rows, int d, const float *x, const int32_t *idx,
                        float *out);
+// tiled != 0: a, w (and the SwiGLU output) are in the tiled layout; bf16 only
 int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a, const void *w,
-                  float *out, int n_splits);
+                  float *out, int n_splits, int tiled);
 int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
-                         const void *wg, const void *wu, void *out);
+                         const void *wg, const void *wu, void *out, int tiled);
+int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst);
+bool tiled_shapes_ok(int M, int N, int K);
 int launch_rope_kv(hipStream_t st, int dtype, int rows, int Hq, int Hkv, int hd, int page_tokens,
                    double rope_base, const float *qkv, int n_splits, const int32_t *row_pos,
                    const int32_t *row_page, const int32_t *row_off, void *q_out, void *k_pages,
@@ -117,6 +132,6 @@ int launch_reward_score(hipStream_t st, int n_cands, int vocab, const float *log
                         int32_t *out_rank);
 
 // number of K-axis splits the linear kernels use for an [M x N x K] product
-int linear_auto_splits(int dtype, int M, int N, int K);
+int linear_auto_splits(int dtype, int M, int N, int K, int tiled);
 
 }  // namespace mc

@@ -69,8 +69,9 @@ int launch_embed(hipStream_t st, int dtype, int rows, int d, const int32_t *toke
 template <typename T>
 __global__ __launch_bounds__(256) void add_rmsnorm_kernel(
     int d, float *__restrict__ x, const float *__restrict__ partials, int n_partials,
-    size_t pstride, const T *__restrict__ gain, float eps, T *__restrict__ h) {
+    size_t pstride, const T *__restrict__ gain, float eps, T *__restrict__ h, int h_tiled) {
   __shared__ float scratch[16];
+  const int r = blockIdx.x;
   const size_t row = (size_t)blockIdx.x * d;
   float ss = 0.f;
   for (int i = threadIdx.x; i < d; i += 256) {
@@ -81,20 +82,22 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(
   }
   ss = block_sum<float>(ss, scratch);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256)
-    h[row + i] = Cvt<T>::from_f32(x[row + i] * inv * Cvt<T>::to_f32(gain[i]));
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const size_t at = h_tiled ? tiled_offset(r, i, d) : row + i;
+    h[at] = Cvt<T>::from_f32(x[row + i] * inv * Cvt<T>::to_f32(gain[i]));
+  }
 }
 
 int launch_add_rmsnorm(hipStream_t st, int dtype, int rows, int d, float *x, const float *partials,
-                       int n_partials, const void *gain, float eps, void *h_out) {
+                       int n_partials, const void *gain, float eps, void *h_out, int h_tiled) {
   if (rows <= 0) return MC_OK;
   const size_t ps = (size_t)rows * d;
   if (dtype == MC_F32)
     add_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps,
-                                                    (const float *)gain, eps, (float *)h_out);
+                                                    (const float *)gain, eps, (float *)h_out, h_tiled);
   else
     add_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps,
-                                                     (const bf16_t *)gain, eps, (bf16_t *)h_out);
+                                                     (const bf16_t *)gain, eps, (bf16_t *)h_out, h_tiled);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }
@@ -348,11 +351,15 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(AttnArgs a) {
     }
     __syncthreads();
   }
-  T *out = (T *)a.out + ((size_t)r * a.n_q_heads + qh) * hd;
+  T *out = (T *)a.out;
 #pragma unroll
   for (int c = 0; c < MAXD; ++c) {
     const int d = lane + 64 * c;
-    if (d < hd) out[d] = Cvt<T>::from_f32(o[c] / l);
+    if (d < hd) {
+      const size_t at = a.out_tiled ? tiled_offset(r, qh * hd + d, a.n_q_heads * hd)
+                                    : ((size_t)r * a.n_q_heads + qh) * hd + d;
+      out[at] = Cvt<T>::from_f32(o[c] / l);
+    }
   }
 }
 

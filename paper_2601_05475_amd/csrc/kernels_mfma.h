@@ -5,8 +5,9 @@
 
 namespace mc {
 
+// All operands of these linear kernels are in the tiled layout (see tiled_offset).
 // Few-row linear layer (M <= 64): out = a w^T streamed once over the weights.
-// w2 != nullptr selects the SwiGLU form (out_t = silu(a wg^T) * (a wu^T), bf16).
+// w2 != nullptr selects the SwiGLU form (out_t = silu(a wg^T) * (a wu^T), bf16, tiled).
 bool skinny_linear_supported(int M, int N, int K);
 int skinny_linear_splits(int M, int N, int K);
 int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, const void *w,

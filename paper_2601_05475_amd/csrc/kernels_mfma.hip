@@ -6,6 +6,13 @@
 //   D: lane l holds column (l % 32); register r holds row 8*(r / 4) + 4*(l / 32) + (r % 4)
 // Only the pairing of A and B slots matters for a dot product, so kernels are free to map a slot
 // to any element of the contracted axis as long as both operands use the same map.
+//
+// Tiled operand layout ("tiled" below).  A [rows][K] bf16 matrix, rows % 32 == 0 and K % 64 == 0,
+// is stored as 4 KB blocks, block (row tile rt, unit u) at ((rt * K/64 + u) * 4096) bytes, and
+// inside a block chunk c (0..3) of lane l (0..63) at (c * 64 + l) * 16 bytes holds
+//   M[32 rt + l % 32][64 u + 32 (l / 32) + 8 c + 0..7].
+// One wave-wide 16-byte load of chunk c therefore reads 1 KB of contiguous memory and lands
+// directly in the A (or B) operand registers of four consecutive MFMA steps.
 #include "kernels_mfma.h"
 
 #include <algorithm>
@@ -29,11 +36,44 @@ __device__ inline uint2 pack4_bf16(float a, float b, float c, float d) {
   return r;
 }
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+// streaming 16-byte load: the data is used once, keep it out of the way of reusable lines
+__device__ inline uint4 load_stream(const bf16_t *p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// ---- row-major -> tiled repack (one thread per 16-byte chunk of the destination) -----------
+__global__ void pack_tiled_kernel(int rows, int rows_pad, int K, const bf16_t *__restrict__ src,
+                                  bf16_t *__restrict__ dst) {
+  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)rows_pad * K / 8;
+  if (chunk >= total) return;
+  const int lane = chunk & 63, c = (chunk >> 6) & 3;
+  const size_t blk = chunk >> 8;
+  const int U = K >> 6;
+  const int rt = (int)(blk / U), u = (int)(blk % U);
+  const int row = 32 * rt + (lane & 31), k = 64 * u + 32 * (lane >> 5) + 8 * c;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < rows) v = *(const uint4 *)(src + (size_t)row * K + k);
+  *(uint4 *)(dst + chunk * 8) = v;
+}
+
+int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst) {
+  if (rows <= 0) return MC_OK;
+  if (K % 64) MC_FAIL(MC_ERR_UNSUPPORTED, "tiled layout needs K %% 64 == 0 (K = %d)", K);
+  const int rows_pad = (rows + 31) / 32 * 32;
+  const size_t chunks = (size_t)rows_pad * K / 8;
+  pack_tiled_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(rows, rows_pad, K, (const bf16_t *)src, (bf16_t *)dst);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
 // =====================================================================================
-// Few-row linear layer: weights streamed once, straight from HBM into MFMA operands.
-// A workgroup owns 32 weight rows; its 4 waves take 4 different slices of the K range and
-// meet in LDS.  Lane (row n, half h) reads 64 contiguous bytes of its weight row per step,
-// the activation operand uses the same slot map.  MB = number of 32-row blocks of `a`.
+// Few-row linear layer on tiled operands: weights streamed once from HBM straight into MFMA
+// operands.  A workgroup owns one 32-row weight tile; its 4 waves take 4 slices of the K range
+// and meet in LDS.  Loads run two units (2 x 4 KB per operand) ahead of the MFMAs.
+// MB = number of 32-row tiles of the activations (M <= 32 MB).
 // =====================================================================================
 template <int MB, bool SWIGLU>
 __global__ __launch_bounds__(256) void skinny_linear_kernel(
@@ -43,13 +83,12 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   constexpr int NW = SWIGLU ? 2 : 1;
   __shared__ float4 red[4][NW][MB][4][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
-  const int n0 = blockIdx.x * 32, split = blockIdx.y;
-  const size_t k_begin = ((size_t)(split * 4 + wave) * units_per_wave) * 64 + 32 * h;
-  const bf16_t *wrow = w + (size_t)(n0 + nl) * K + k_begin;
-  const bf16_t *urow = SWIGLU ? w2 + (size_t)(n0 + nl) * K + k_begin : nullptr;
-  const bf16_t *arow[MB];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb) arow[mb] = a + (size_t)min(mb * 32 + nl, M - 1) * K + k_begin;
+  const int rt = blockIdx.x, split = blockIdx.y;
+  const int U = K >> 6;
+  const int u0 = (split * 4 + wave) * units_per_wave;
+  const bf16_t *wp = w + ((size_t)rt * U + u0) * 2048 + lane * 8;
+  const bf16_t *up = SWIGLU ? w2 + ((size_t)rt * U + u0) * 2048 + lane * 8 : nullptr;
+  const bf16_t *ap = a + (size_t)u0 * 2048 + lane * 8;      // activation tile mb adds mb * U * 2048
   f32x16 acc[NW][MB];
 #pragma unroll
   for (int i = 0; i < NW; ++i)
@@ -58,26 +97,36 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][mb][r] = 0.f;
 
-#pragma unroll 2
-  for (int u = 0; u < units_per_wave; ++u) {
-    uint4 wf[4], uf[4], af[MB][4];
+  uint4 wf[2][4], uf[2][4], af[2][MB][4];
+  auto issue = [&](int slot, int u) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      wf[c] = *(const uint4 *)(wrow + u * 64 + 8 * c);
-      if (SWIGLU) uf[c] = *(const uint4 *)(urow + u * 64 + 8 * c);
+      wf[slot][c] = load_stream(wp + (size_t)u * 2048 + c * 512);
+      if (SWIGLU) uf[slot][c] = load_stream(up + (size_t)u * 2048 + c * 512);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        af[slot][mb][c] = *(const uint4 *)(ap + ((size_t)mb * U + u) * 2048 + c * 512);
     }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) af[mb][c] = *(const uint4 *)(arow[mb] + u * 64 + 8 * c);
+  };
+  auto compute = [&](int slot) {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        acc[0][mb] = mfma32(wf[c], af[mb][c], acc[0][mb]);
-        if (SWIGLU) acc[1][mb] = mfma32(uf[c], af[mb][c], acc[1][mb]);
+        acc[0][mb] = mfma32(wf[slot][c], af[slot][mb][c], acc[0][mb]);
+        if (SWIGLU) acc[NW - 1][mb] = mfma32(uf[slot][c], af[slot][mb][c], acc[NW - 1][mb]);
       }
+  };
+  issue(0, 0);
+  int u = 0;
+  for (; u + 2 <= units_per_wave; u += 2) {
+    issue(1, u + 1);
+    compute(0);
+    if (u + 2 < units_per_wave) issue(0, u + 2);
+    compute(1);
   }
+  if (u < units_per_wave) compute(0);
+
 #pragma unroll
   for (int i = 0; i < NW; ++i)
 #pragma unroll
@@ -89,7 +138,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   __syncthreads();
   // thread (r4 = wave, lane) adds the four waves' quads in a fixed order and stores 4 outputs
   const int r4 = wave;
-  const int n = n0 + 8 * r4 + 4 * h;
+  const int n = 32 * rt + 8 * r4 + 4 * h;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     const int m = mb * 32 + nl;
@@ -105,7 +154,8 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
     }
     if (m < M) {
       if (SWIGLU) {
-        *(uint2 *)(out_t + (size_t)m * N + n) =
+        // the product feeds the next linear layer: store it tiled, as a [*][N] activation
+        *(uint2 *)(out_t + tiled_offset(m, n, N)) =
             pack4_bf16(silu_f(s[0].x) * s[NW - 1].x, silu_f(s[0].y) * s[NW - 1].y,
                        silu_f(s[0].z) * s[NW - 1].z, silu_f(s[0].w) * s[NW - 1].w);
       } else {
@@ -137,6 +187,7 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   if (!skinny_linear_supported(M, N, K) || n_splits < 1 || units % (4 * n_splits))
     MC_FAIL(MC_ERR_UNSUPPORTED, "few-row linear: M=%d N=%d K=%d splits=%d not covered", M, N, K, n_splits);
   if (w2 && n_splits != 1) MC_FAIL(MC_ERR_INVALID, "the SwiGLU form cannot be split over K");
+  if (w2 && N % 64) MC_FAIL(MC_ERR_UNSUPPORTED, "tiled SwiGLU output needs N %% 64 == 0");
   const int upw = units / (4 * n_splits);
   dim3 grid(N / 32, n_splits);
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
@@ -153,30 +204,31 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
 }
 
 // =====================================================================================
-// Many-row GEMM: out[m][n] = sum_k a[m][k] w[n][k].  128 x 128 tile per workgroup, 64-deep
-// slabs staged through LDS, 2 x 2 waves each owning 64 x 64 (2 x 2 MFMA tiles).  Weight rows
-// feed the A operand so that a lane ends up with runs of 4 consecutive n for 16-byte stores.
+// Many-row GEMM on tiled operands: out[m][n] = sum_k a[m][k] w[n][k].  128 x 128 tile per
+// workgroup, one 64-deep unit per step staged through LDS as whole 4 KB blocks (the block layout
+// is already the MFMA operand layout, so LDS reads are conflict-free without padding).  2 x 2
+// waves, each 64 x 64 (2 x 2 MFMA tiles).  Weight rows feed the A operand so that a lane ends up
+// with runs of 4 consecutive n for 16-byte stores.
 // =====================================================================================
-constexpr int GB = 128, GK = 64, GLD = GK + 8;   // LDS row stride in elements (144 bytes)
-
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(
     int M, int N, int K, const bf16_t *__restrict__ a, const bf16_t *__restrict__ w,
     const bf16_t *__restrict__ w2, float *__restrict__ out, bf16_t *__restrict__ out_t) {
   constexpr int NW = SWIGLU ? 2 : 1;
-  __shared__ __attribute__((aligned(16))) bf16_t As[GB * GLD];
-  __shared__ __attribute__((aligned(16))) bf16_t Ws[NW][GB * GLD];
+  __shared__ uint4 As[4 * 256];            // 4 row tiles x (4 chunks x 64 lanes)
+  __shared__ uint4 Ws[NW][4 * 256];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, h = lane >> 5;
   const int wn = wave & 1, wm = wave >> 1;
-  const int n0 = blockIdx.x * GB, m0 = blockIdx.y * GB;
-  // staging: thread t moves 16-byte chunk (t % 8) of rows t / 8 + 32 i
-  const int srow = tid >> 3, schunk = (tid & 7) * 8;
-  const bf16_t *ag[4], *wg[4], *ug[4];
+  const int U = K >> 6;
+  const int nt0 = blockIdx.x * 4, mt0 = blockIdx.y * 4;
+  const int m_tiles = (M + 31) >> 5;
+  // staging: thread t copies chunk t of every block (4 blocks per operand)
+  const uint4 *ag[4], *wg[4], *ug[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    ag[i] = a + (size_t)min(m0 + srow + 32 * i, M - 1) * K + schunk;
-    wg[i] = w + (size_t)(n0 + srow + 32 * i) * K + schunk;
-    ug[i] = SWIGLU ? w2 + (size_t)(n0 + srow + 32 * i) * K + schunk : nullptr;
+    ag[i] = (const uint4 *)(a + (size_t)min(mt0 + i, m_tiles - 1) * U * 2048) + tid;
+    wg[i] = (const uint4 *)(w + (size_t)(nt0 + i) * U * 2048) + tid;
+    ug[i] = SWIGLU ? (const uint4 *)(w2 + (size_t)(nt0 + i) * U * 2048) + tid : nullptr;
   }
   f32x16 acc[NW][2][2];
 #pragma unroll
@@ -190,35 +242,35 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(
   uint4 pa[4], pw[4], pu[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    pa[i] = *(const uint4 *)(ag[i]);
-    pw[i] = *(const uint4 *)(wg[i]);
-    if (SWIGLU) pu[i] = *(const uint4 *)(ug[i]);
+    pa[i] = ag[i][0];
+    pw[i] = wg[i][0];
+    if (SWIGLU) pu[i] = ug[i][0];
   }
-  for (int k0 = 0; k0 < K; k0 += GK) {
-    __syncthreads();           // everyone is done reading the previous slab
+  for (int u = 0; u < U; ++u) {
+    __syncthreads();           // everyone is done reading the previous unit
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      *(uint4 *)(As + (srow + 32 * i) * GLD + schunk) = pa[i];
-      *(uint4 *)(Ws[0] + (srow + 32 * i) * GLD + schunk) = pw[i];
-      if (SWIGLU) *(uint4 *)(Ws[NW - 1] + (srow + 32 * i) * GLD + schunk) = pu[i];
+      As[i * 256 + tid] = pa[i];
+      Ws[0][i * 256 + tid] = pw[i];
+      if (SWIGLU) Ws[NW - 1][i * 256 + tid] = pu[i];
     }
     __syncthreads();
-    if (k0 + GK < K) {
+    if (u + 1 < U) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        pa[i] = *(const uint4 *)(ag[i] + k0 + GK);
-        pw[i] = *(const uint4 *)(wg[i] + k0 + GK);
-        if (SWIGLU) pu[i] = *(const uint4 *)(ug[i] + k0 + GK);
+        pa[i] = ag[i][(size_t)(u + 1) * 256];
+        pw[i] = wg[i][(size_t)(u + 1) * 256];
+        if (SWIGLU) pu[i] = ug[i][(size_t)(u + 1) * 256];
       }
     }
 #pragma unroll
-    for (int ks = 0; ks < GK / 16; ++ks) {
+    for (int c = 0; c < 4; ++c) {
       uint4 fa[2], fw[NW][2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        fa[t] = *(const uint4 *)(As + (64 * wm + 32 * t + j) * GLD + 16 * ks + 8 * h);
-        fw[0][t] = *(const uint4 *)(Ws[0] + (64 * wn + 32 * t + j) * GLD + 16 * ks + 8 * h);
-        if (SWIGLU) fw[NW - 1][t] = *(const uint4 *)(Ws[NW - 1] + (64 * wn + 32 * t + j) * GLD + 16 * ks + 8 * h);
+        fa[t] = As[(2 * wm + t) * 256 + c * 64 + lane];
+        fw[0][t] = Ws[0][(2 * wn + t) * 256 + c * 64 + lane];
+        if (SWIGLU) fw[NW - 1][t] = Ws[NW - 1][(2 * wn + t) * 256 + c * 64 + lane];
       }
 #pragma unroll
       for (int i = 0; i < NW; ++i)
@@ -230,19 +282,19 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(
   }
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
-    const int m = m0 + 64 * wm + 32 * mt + j;
+    const int m = 32 * (mt0 + 2 * wm + mt) + j;
     if (m >= M) continue;
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int n = n0 + 64 * wn + 32 * nt + 8 * r4 + 4 * h;
+        const int n = 32 * (nt0 + 2 * wn + nt) + 8 * r4 + 4 * h;
         const f32x16 &g = acc[0][nt][mt];
         if (SWIGLU) {
-          const f32x16 &u = acc[NW - 1][nt][mt];
-          *(uint2 *)(out_t + (size_t)m * N + n) =
-              pack4_bf16(silu_f(g[4 * r4]) * u[4 * r4], silu_f(g[4 * r4 + 1]) * u[4 * r4 + 1],
-                         silu_f(g[4 * r4 + 2]) * u[4 * r4 + 2], silu_f(g[4 * r4 + 3]) * u[4 * r4 + 3]);
+          const f32x16 &uu = acc[NW - 1][nt][mt];
+          *(uint2 *)(out_t + tiled_offset(m, n, N)) =
+              pack4_bf16(silu_f(g[4 * r4]) * uu[4 * r4], silu_f(g[4 * r4 + 1]) * uu[4 * r4 + 1],
+                         silu_f(g[4 * r4 + 2]) * uu[4 * r4 + 2], silu_f(g[4 * r4 + 3]) * uu[4 * r4 + 3]);
         } else {
           *(float4 *)(out + (size_t)m * N + n) =
               make_float4(g[4 * r4], g[4 * r4 + 1], g[4 * r4 + 2], g[4 * r4 + 3]);
@@ -251,12 +303,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(
   }
 }
 
-bool gemm_supported(int M, int N, int K) { return M > 64 && N % GB == 0 && K % GK == 0; }
+bool gemm_supported(int M, int N, int K) { return M >= 1 && N % 128 == 0 && K % 64 == 0; }
 
 int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                      const void *w2, float *out, void *out_t) {
   if (!gemm_supported(M, N, K)) MC_FAIL(MC_ERR_UNSUPPORTED, "GEMM: M=%d N=%d K=%d not covered", M, N, K);
-  dim3 grid(N / GB, (M + GB - 1) / GB);
+  dim3 grid(N / 128, (M + 127) / 128);
   if (w2)
     gemm_mfma_kernel<true><<<grid, 256, 0, st>>>(M, N, K, (const bf16_t *)a, (const bf16_t *)w,
                                                  (const bf16_t *)w2, out, (bf16_t *)out_t);

@@ -14,8 +14,15 @@ int launch_linear_generic(hipStream_t st, int dtype, int M, int N, int K, const 
 int launch_linear_swiglu_generic(hipStream_t st, int dtype, int M, int N, int K, const void *a,
                                  const void *wg, const void *wu, void *out);
 
-int linear_auto_splits(int dtype, int M, int N, int K) {
-  if (dtype == MC_BF16 && skinny_linear_supported(M, N, K)) return skinny_linear_splits(M, N, K);
+// Shapes the tiled bf16 kernels cover for every row count: few rows go to the weight-streaming
+// kernel (K % 256), many rows to the tiled GEMM (N % 128).
+bool tiled_shapes_ok(int M, int N, int K) {
+  (void)M;
+  return N % 128 == 0 && K % 256 == 0;
+}
+
+int linear_auto_splits(int dtype, int M, int N, int K, int tiled) {
+  if (tiled) return (dtype == MC_BF16 && M <= 64) ? skinny_linear_splits(M, N, K) : 1;
   if (M > 64) return 1;
   // generic kernel, few rows: aim at >= 256 workgroups while keeping >= 256 of K per split
   const int tiles = (N + 63) / 64;
@@ -25,21 +32,22 @@ int linear_auto_splits(int dtype, int M, int N, int K) {
 }
 
 int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a, const void *w,
-                  float *out, int n_splits) {
-  if (dtype == MC_BF16 && skinny_linear_supported(M, N, K))
-    return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits);
-  if (dtype == MC_BF16 && n_splits == 1 && gemm_supported(M, N, K))
-    return launch_gemm_mfma(st, M, N, K, a, w, nullptr, out, nullptr);
-  return launch_linear_generic(st, dtype, M, N, K, a, w, out, n_splits);
+                  float *out, int n_splits, int tiled) {
+  if (!tiled) return launch_linear_generic(st, dtype, M, N, K, a, w, out, n_splits);
+  if (dtype != MC_BF16 || !tiled_shapes_ok(M, N, K))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
+  if (M <= 64) return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits);
+  if (n_splits != 1) MC_FAIL(MC_ERR_UNSUPPORTED, "the many-row GEMM does not split K");
+  return launch_gemm_mfma(st, M, N, K, a, w, nullptr, out, nullptr);
 }
 
 int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
-                         const void *wg, const void *wu, void *out) {
-  if (dtype == MC_BF16 && skinny_linear_supported(M, N, K))
-    return launch_linear_skinny(st, M, N, K, a, wg, wu, nullptr, out, 1);
-  if (dtype == MC_BF16 && gemm_supported(M, N, K))
-    return launch_gemm_mfma(st, M, N, K, a, wg, wu, nullptr, out);
-  return launch_linear_swiglu_generic(st, dtype, M, N, K, a, wg, wu, out);
+                         const void *wg, const void *wu, void *out, int tiled) {
+  if (!tiled) return launch_linear_swiglu_generic(st, dtype, M, N, K, a, wg, wu, out);
+  if (dtype != MC_BF16 || !tiled_shapes_ok(M, N, K))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
+  if (M <= 64) return launch_linear_skinny(st, M, N, K, a, wg, wu, nullptr, out, 1);
+  return launch_gemm_mfma(st, M, N, K, a, wg, wu, nullptr, out);
 }
 
 // ---- decode attention: MFMA split-K kernel when the shape allows, else the generic kernel ---
@@ -73,7 +81,7 @@ int launch_attention_decode(hipStream_t st, int dtype, const DecodeAttnArgs &a) 
   g.v_suffix = a.v_suffix; g.row_pos = row_pos; g.row_tab = row_tab; g.page_table = a.page_table;
   g.table_stride = a.table_stride; g.rows = a.n_cands; g.n_q_heads = a.n_q_heads;
   g.n_kv_heads = a.n_kv_heads; g.head_dim = a.head_dim; g.page_tokens = a.page_tokens;
-  g.prefix_len = a.prefix_len; g.out = a.out;
+  g.prefix_len = a.prefix_len; g.out = a.out; g.out_tiled = a.out_tiled;
   return launch_attention_generic(st, dtype, g);
 }
 
@@ -82,33 +90,60 @@ static int check_dtype(int dtype) {
   return MC_OK;
 }
 
+static int check_tiled(int dtype, int tiled, int K) {
+  if (tiled != 0 && tiled != 1) MC_FAIL(MC_ERR_INVALID, "tiled must be 0 or 1");
+  if (tiled && (dtype != MC_BF16 || K % 64)) MC_FAIL(MC_ERR_UNSUPPORTED, "the tiled layout is bf16 with K %% 64 == 0");
+  return MC_OK;
+}
+
 }  // namespace mc
 
 using namespace mc;
 
+extern "C" size_t mc_op_tiled_bytes(int32_t rows, int32_t K) {
+  if (rows < 1 || K < 64 || K % 64) return 0;
+  return (size_t)((rows + 31) / 32 * 32) * K * 2;
+}
+
+extern "C" int mc_op_pack_tiled(void *stream, int32_t rows, int32_t K, const void *src, void *dst) {
+  if (rows < 0 || K < 64 || K % 64) MC_FAIL(MC_ERR_INVALID, "bad sizes (K must be a multiple of 64)");
+  if (!src || !dst) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  return launch_pack_tiled((hipStream_t)stream, rows, K, src, dst);
+}
+
 extern "C" int mc_op_add_rmsnorm(void *stream, int32_t dtype, int32_t rows, int32_t d, float *x,
                                  const float *partials, int32_t n_partials, const void *gain,
-                                 float eps, void *h_out) {
+                                 float eps, void *h_out, int32_t h_tiled) {
   MC_TRY(check_dtype(dtype));
   if (rows < 0 || d < 1 || n_partials < 0) MC_FAIL(MC_ERR_INVALID, "bad sizes");
   if (!x || !gain || !h_out || (n_partials && !partials)) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
-  return launch_add_rmsnorm((hipStream_t)stream, dtype, rows, d, x, partials, n_partials, gain, eps, h_out);
+  MC_TRY(check_tiled(dtype, h_tiled, d));
+  return launch_add_rmsnorm((hipStream_t)stream, dtype, rows, d, x, partials, n_partials, gain, eps, h_out, h_tiled);
 }
 
 extern "C" int mc_op_linear(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K,
-                            const void *a, const void *w, float *out, int32_t n_splits) {
+                            const void *a, const void *w, float *out, int32_t n_splits,
+                            int32_t tiled) {
   MC_TRY(check_dtype(dtype));
   if (M < 0 || N < 1 || K < 1 || n_splits < 1 || n_splits > K) MC_FAIL(MC_ERR_INVALID, "bad sizes");
   if (!a || !w || !out) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
-  return launch_linear((hipStream_t)stream, dtype, M, N, K, a, w, out, n_splits);
+  MC_TRY(check_tiled(dtype, tiled, K));
+  return launch_linear((hipStream_t)stream, dtype, M, N, K, a, w, out, n_splits, tiled);
+}
+
+extern "C" int32_t mc_op_linear_splits(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t tiled) {
+  if (M < 1 || N < 1 || K < 1) return 0;
+  return linear_auto_splits(dtype, M, N, K, tiled);
 }
 
 extern "C" int mc_op_linear_swiglu(void *stream, int32_t dtype, int32_t M, int32_t N, int32_t K,
-                                   const void *a, const void *w_gate, const void *w_up, void *out) {
+                                   const void *a, const void *w_gate, const void *w_up, void *out,
+                                   int32_t tiled) {
   MC_TRY(check_dtype(dtype));
   if (M < 0 || N < 1 || K < 1) MC_FAIL(MC_ERR_INVALID, "bad sizes");
   if (!a || !w_gate || !w_up || !out) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
-  return launch_linear_swiglu((hipStream_t)stream, dtype, M, N, K, a, w_gate, w_up, out);
+  MC_TRY(check_tiled(dtype, tiled, K));
+  return launch_linear_swiglu((hipStream_t)stream, dtype, M, N, K, a, w_gate, w_up, out, tiled);
 }
 
 extern "C" int mc_op_rope_kv_write(void *stream, int32_t dtype, int32_t rows, int32_t n_q_heads,
@@ -144,7 +179,7 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
                                       const void *k_suffix, const void *v_suffix,
                                       const int32_t *page_table, int32_t table_stride,
                                       int32_t prefix_splits, void *workspace,
-                                      size_t workspace_bytes, void *out) {
+                                      size_t workspace_bytes, void *out, int32_t out_tiled) {
   MC_TRY(check_dtype(dtype));
   if (n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || head_dim < 2 ||
       head_dim > 256 || page_tokens < 1 || (page_tokens & (page_tokens - 1)) || prefix_len < 0 ||
@@ -153,6 +188,7 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   if (!q || !out || !workspace || (prefix_len && (!k_prefix || !v_prefix)) ||
       (suffix_len && (!k_suffix || !v_suffix || !page_table)))
     MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  MC_TRY(check_tiled(dtype, out_tiled, n_q_heads * head_dim));
   if (suffix_len && table_stride < (suffix_len + page_tokens - 1) / page_tokens)
     MC_FAIL(MC_ERR_INVALID, "table_stride %d too small for %d suffix tokens", table_stride, suffix_len);
   const size_t need = decode_attention_ws_bytes(n_cands, n_q_heads, n_kv_heads, head_dim, prefix_len, suffix_len, page_tokens);
@@ -163,7 +199,7 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
   a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.suffix_len = suffix_len;
   a.prefix_splits = prefix_splits; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
-  a.out = out;
+  a.out = out; a.out_tiled = out_tiled;
   return launch_attention_decode((hipStream_t)stream, dtype, a);
 }
 

@@ -67,16 +67,28 @@ struct mc_model {
   const void *embed, *final_norm, *lm_head;
   std::vector<LayerW> layers;
   int n_qkv;                // (Hq + 2 Hkv) * hd
+  int tiled;                // matrices (not the embedding) are kept in the tiled MFMA layout
 };
 
 namespace mc {
 
 struct ModelLayout {
-  size_t embed, final_norm, lm_head;
+  size_t embed, final_norm, lm_head, staging;
   struct L { size_t attn_norm, wqkv, wo, ffn_norm, w_gate, w_up, w_down; };
   std::vector<L> layers;
-  size_t total;
+  size_t total, staging_bytes;
+  int tiled, staging_rows;
 };
+
+// bf16 models whose every matrix fits the tiled MFMA kernels run entirely on them
+static int model_is_tiled(const mc_config &c) {
+  const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim;
+  const char *force = getenv("MC_FORCE_GENERIC");      // diagnosis: run bf16 on the ALU kernels
+  if (force && force[0] == '1') return 0;
+  return c.dtype == MC_BF16 && kd % 32 == 0 && tiled_shapes_ok(0, qd + 2 * kd, c.d_model) &&
+         tiled_shapes_ok(0, c.d_model, qd) && tiled_shapes_ok(0, c.d_ffn, c.d_model) &&
+         tiled_shapes_ok(0, c.d_model, c.d_ffn) && tiled_shapes_ok(0, c.vocab, c.d_model);
+}
 
 static void model_layout(const mc_config &c, ModelLayout &o) {
   Bump b;
@@ -84,6 +96,10 @@ static void model_layout(const mc_config &c, ModelLayout &o) {
   const size_t e = esize(c.dtype), d = c.d_model, qd = (size_t)c.n_q_heads * c.head_dim,
                kd = (size_t)c.n_kv_heads * c.head_dim;
   auto at = [&](size_t bytes) { b.take(bytes); return b.used - bytes; };
+  o.tiled = model_is_tiled(c);
+  o.staging_rows = 2048;
+  o.staging_bytes = o.tiled ? (size_t)o.staging_rows * std::max({d, qd, (size_t)c.d_ffn}) * e : 0;
+  o.staging = at(o.staging_bytes);
   o.embed = at((size_t)c.vocab * d * e);
   o.final_norm = at(d * e);
   o.lm_head = at((size_t)c.vocab * d * e);
@@ -140,9 +156,28 @@ extern "C" int mc_model_create(const mc_config *cfg, const mc_weights *w, const 
   auto put = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
     return hipMemcpyAsync(base + off, src, bytes, hipMemcpyDefault, st);
   };
+  // A matrix [rows][K]: plain copy, or (tiled models) repacked through the staging area in
+  // row chunks.  row0 places it below earlier rows of a fused matrix (multiple of 32).
+  auto put_matrix = [&](size_t off, size_t row0, const void *src, size_t rows, size_t K) -> hipError_t {
+    if (!lay.tiled) return put(off + row0 * K * e, src, rows * K * e);
+    for (size_t r = 0; r < rows; r += lay.staging_rows) {
+      const size_t n = std::min(rows - r, (size_t)lay.staging_rows);
+      hipError_t err = hipMemcpyAsync(base + lay.staging, (const char *)src + r * K * e, n * K * e,
+                                      hipMemcpyDefault, st);
+      if (err != hipSuccess) return err;
+      if (launch_pack_tiled(st, (int)n, (int)K, base + lay.staging,
+                            base + off + (row0 + r) / 32 * (K / 64) * 4096) != MC_OK)
+        return hipErrorLaunchFailure;
+      // the staging area is reused by the next chunk: a copy from pageable host memory is not
+      // guaranteed to wait for kernels enqueued earlier on the stream
+      err = hipStreamSynchronize(st);
+      if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+  };
   MC_HIP(put(lay.embed, w->embed, (size_t)c.vocab * d * e));
   MC_HIP(put(lay.final_norm, w->final_norm, d * e));
-  MC_HIP(put(lay.lm_head, w->lm_head, (size_t)c.vocab * d * e));
+  MC_HIP(put_matrix(lay.lm_head, 0, w->lm_head, c.vocab, d));
   mc_model *m = new (std::nothrow) mc_model();
   if (!m) MC_FAIL(MC_ERR_OOM, "host allocation failed");
   m->cfg = c;
@@ -152,19 +187,20 @@ extern "C" int mc_model_create(const mc_config *cfg, const mc_weights *w, const 
   m->final_norm = base + lay.final_norm;
   m->lm_head = base + lay.lm_head;
   m->n_qkv = (int)(qd + 2 * kd);
+  m->tiled = lay.tiled;
   m->layers.resize(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l) {
     const auto &L = lay.layers[l];
     hipError_t err = put(L.attn_norm, w->attn_norm[l], d * e);
     // fused QKV: rows of wq, then wk, then wv
-    if (err == hipSuccess) err = put(L.wqkv, w->wq[l], qd * d * e);
-    if (err == hipSuccess) err = put(L.wqkv + qd * d * e, w->wk[l], kd * d * e);
-    if (err == hipSuccess) err = put(L.wqkv + (qd + kd) * d * e, w->wv[l], kd * d * e);
-    if (err == hipSuccess) err = put(L.wo, w->wo[l], d * qd * e);
+    if (err == hipSuccess) err = put_matrix(L.wqkv, 0, w->wq[l], qd, d);
+    if (err == hipSuccess) err = put_matrix(L.wqkv, qd, w->wk[l], kd, d);
+    if (err == hipSuccess) err = put_matrix(L.wqkv, qd + kd, w->wv[l], kd, d);
+    if (err == hipSuccess) err = put_matrix(L.wo, 0, w->wo[l], d, qd);
     if (err == hipSuccess) err = put(L.ffn_norm, w->ffn_norm[l], d * e);
-    if (err == hipSuccess) err = put(L.w_gate, w->w_gate[l], (size_t)c.d_ffn * d * e);
-    if (err == hipSuccess) err = put(L.w_up, w->w_up[l], (size_t)c.d_ffn * d * e);
-    if (err == hipSuccess) err = put(L.w_down, w->w_down[l], d * (size_t)c.d_ffn * e);
+    if (err == hipSuccess) err = put_matrix(L.w_gate, 0, w->w_gate[l], c.d_ffn, d);
+    if (err == hipSuccess) err = put_matrix(L.w_up, 0, w->w_up[l], c.d_ffn, d);
+    if (err == hipSuccess) err = put_matrix(L.w_down, 0, w->w_down[l], d, c.d_ffn);
     if (err != hipSuccess) {
       delete m;
       MC_FAIL(MC_ERR_DEVICE, "weight upload of layer %d failed: %s", l, hipGetErrorString(err));
@@ -237,17 +273,19 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.vpool = at((size_t)c.n_layers * (o.n_prefix_pages + o.n_pool_pages) * o.page_bytes);
   o.kscr = at((size_t)o.n_score_pages * o.page_bytes);
   o.vscr = at((size_t)o.n_score_pages * o.page_bytes);
+  // activation buffers that may be kept tiled hold whole 32-row tiles
+  const size_t Rp = align_up(R, 32), Cp = align_up((size_t)p.max_cands, 32);
   o.x = at(R * d * 4);
-  o.h = at(R * d * e);
+  o.h = at(Rp * d * e);
   o.part_floats = std::max(R, (size_t)p.max_cands * kMaxSplits) * std::max(nqkv, d);
   o.part = at(o.part_floats * 4);
   o.q = at(R * qd * e);
-  o.attn_out = at(R * qd * e);
-  o.act = at(R * (size_t)c.d_ffn * e);
+  o.attn_out = at(Rp * qd * e);
+  o.act = at(Rp * (size_t)c.d_ffn * e);
   o.logits = at((size_t)p.max_cands * c.vocab * 4);
   o.prefix_logits = at((size_t)c.vocab * 4);
   o.xlast = at((size_t)p.max_cands * d * 4);
-  o.hlast = at((size_t)p.max_cands * d * e);
+  o.hlast = at(Cp * d * e);
   o.attn_ws_bytes = decode_attention_ws_bytes(p.max_cands, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                               p.max_prefix, p.max_suffix, pg);
   o.attn_ws = at(o.attn_ws_bytes);
@@ -384,8 +422,9 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
     ProfScope ps(s, MC_K_EMBED);
     MC_TRY(launch_embed(st, dt, rows, d, s->ptr<int32_t>(L.row_tok), m->embed, x));
   }
+  const int tl = m->tiled;
   auto splits_for = [&](int N, int K) {
-    int sp = linear_auto_splits(dt, rows, N, K);
+    int sp = linear_auto_splits(dt, rows, N, K, tl);
     sp = std::min(sp, kMaxSplits);
     while (sp > 1 && (size_t)sp * rows * N > L.part_floats) --sp;
     return sp;
@@ -396,12 +435,12 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
     const LayerW &W = m->layers[l];
     {
       ProfScope ps(s, MC_K_ADD_RMSNORM);
-      MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, pending, W.attn_norm, c.rms_eps, h));
+      MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, pending, W.attn_norm, c.rms_eps, h, tl));
     }
     const int s1 = splits_for(m->n_qkv, d);
     {
       ProfScope ps(s, MC_K_LINEAR_QKV);
-      MC_TRY(launch_linear(st, dt, rows, m->n_qkv, d, h, W.wqkv, part, s1));
+      MC_TRY(launch_linear(st, dt, rows, m->n_qkv, d, h, W.wqkv, part, s1, tl));
     }
     char *kl = s->k_layer(l), *vl = s->v_layer(l);
     void *kdst, *vdst;
@@ -422,6 +461,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       a.prefix_len = s->prefix_len; a.suffix_len = s->suffix_len + 1;
       a.prefix_splits = s->prefix_splits;
       a.workspace = s->ptr<void>(L.attn_ws); a.workspace_bytes = L.attn_ws_bytes; a.out = ao;
+      a.out_tiled = tl;
       ProfScope ps(s, MC_K_ATTN_DECODE);
       MC_TRY(launch_attention_decode(st, dt, a));
     } else {
@@ -432,27 +472,27 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       a.table_stride = L.pages_per_cand;
       a.rows = rows; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
       a.head_dim = c.head_dim; a.page_tokens = s->p.page_tokens; a.prefix_len = prefix_visible;
-      a.out = ao;
+      a.out = ao; a.out_tiled = tl;
       ProfScope ps(s, MC_K_ATTN_PREFILL);
       MC_TRY(launch_attention_generic(st, dt, a));
     }
     const int s2 = splits_for(d, qd);
     {
       ProfScope ps(s, MC_K_LINEAR_O);
-      MC_TRY(launch_linear(st, dt, rows, d, qd, ao, W.wo, part, s2));
+      MC_TRY(launch_linear(st, dt, rows, d, qd, ao, W.wo, part, s2, tl));
     }
     {
       ProfScope ps(s, MC_K_ADD_RMSNORM);
-      MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, s2, W.ffn_norm, c.rms_eps, h));
+      MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, s2, W.ffn_norm, c.rms_eps, h, tl));
     }
     {
       ProfScope ps(s, MC_K_LINEAR_GATE_UP);
-      MC_TRY(launch_linear_swiglu(st, dt, rows, c.d_ffn, d, h, W.w_gate, W.w_up, act));
+      MC_TRY(launch_linear_swiglu(st, dt, rows, c.d_ffn, d, h, W.w_gate, W.w_up, act, tl));
     }
     const int s3 = splits_for(d, c.d_ffn);
     {
       ProfScope ps(s, MC_K_LINEAR_DOWN);
-      MC_TRY(launch_linear(st, dt, rows, d, c.d_ffn, act, W.w_down, part, s3));
+      MC_TRY(launch_linear(st, dt, rows, d, c.d_ffn, act, W.w_down, part, s3, tl));
     }
     pending = s3;
   }
@@ -474,21 +514,21 @@ static int lm_head(mc_session *s, int rows_in_x, int tail_splits, int n_rows, bo
     {
       ProfScope ps(s, MC_K_ADD_RMSNORM);
       MC_TRY(launch_add_rmsnorm(st, c.dtype, rows_in_x, c.d_model, x, s->ptr<float>(L.part),
-                                tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h)));
+                                tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h), m->tiled));
     }
     MC_TRY(launch_gather_rows(st, n_rows, c.d_model, x, s->ptr<int32_t>(L.last_idx),
                               s->ptr<float>(L.xlast)));
     MC_TRY(launch_add_rmsnorm(st, c.dtype, n_rows, c.d_model, s->ptr<float>(L.xlast), nullptr, 0,
-                              m->final_norm, c.rms_eps, s->ptr<void>(L.hlast)));
+                              m->final_norm, c.rms_eps, s->ptr<void>(L.hlast), m->tiled));
     hin = s->ptr<void>(L.hlast);
   } else {
     ProfScope ps(s, MC_K_ADD_RMSNORM);
     MC_TRY(launch_add_rmsnorm(st, c.dtype, rows_in_x, c.d_model, x, s->ptr<float>(L.part),
-                              tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h)));
+                              tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h), m->tiled));
     hin = s->ptr<void>(L.h);
   }
   ProfScope ps(s, MC_K_LINEAR_LM_HEAD);
-  MC_TRY(launch_linear(st, c.dtype, n_rows, c.vocab, c.d_model, hin, m->lm_head, dst, 1));
+  MC_TRY(launch_linear(st, c.dtype, n_rows, c.vocab, c.d_model, hin, m->lm_head, dst, 1, m->tiled));
   return MC_OK;
 }
 
@@ -602,14 +642,9 @@ extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n
   }
   // logits of the last position only
   {
-    const mc_model *m = s->m;
-    hipStream_t st = s->stream;
-    ProfScope ps0(s, MC_K_ADD_RMSNORM);
-    MC_TRY(launch_add_rmsnorm(st, c.dtype, rows, c.d_model, s->ptr<float>(L.x), s->ptr<float>(L.part),
-                              tail, m->final_norm, c.rms_eps, s->ptr<void>(L.h)));
-    const char *hlast = s->ptr<char>(L.h) + (size_t)(rows - 1) * c.d_model * esize(c.dtype);
-    MC_TRY(launch_linear(st, c.dtype, 1, c.vocab, c.d_model, hlast, m->lm_head,
-                         s->ptr<float>(L.prefix_logits), 1));
+    const int32_t last = rows - 1;
+    MC_TRY(upload(s, s->ptr<void>(L.last_idx), &last, 4));
+    MC_TRY(lm_head(s, rows, tail, 1, true, s->ptr<float>(L.prefix_logits)));
   }
   s->prefix_len = n_tokens;
   s->logits_state = LOGITS_PREFIX;

@@ -73,5 +73,7 @@ def test_invalid_configs_are_rejected(lib):
     assert lib.mc_prefill_shared(None, None, 1) == -1
     h = C.c_void_p()
     assert lib.mc_model_create(C.byref(cfg), None, None, C.byref(h)) == -1
-    assert lib.mc_op_linear(None, 0, 4, 4, 4, None, None, None, 1) == -1
+    assert lib.mc_op_linear(None, 0, 4, 4, 4, None, None, None, 1, 0) == -1
+    assert lib.mc_op_tiled_bytes(33, 128) == 64 * 128 * 2 and lib.mc_op_tiled_bytes(33, 100) == 0
+    assert lib.mc_op_linear_splits(1, 32, 6144, 4096, 1) >= 1
     assert lib.mc_op_sample(None, 0, 10, None, 0, 1.0, 5, None, None, None) == -1

@@ -203,3 +203,64 @@ def test_reward_score_op():
     lp, sc, rk = binding.op_reward_score(torch.from_numpy(flat).cuda(), torch.arange(5, dtype=torch.int32, device="cuda"),
                                          torch.arange(5, dtype=torch.float32, device="cuda"), 1.0)
     assert sc.cpu().tolist() == [2.0, 2.0, 2.0] and rk.cpu().tolist() == [0, 1, 2]
+
+
+# ---------------------------------------------------------------- tiled bf16 MFMA kernels
+def test_pack_tiled_roundtrip():
+    import torch
+    for rows, K in [(32, 64), (33, 128), (100, 256), (4096, 512)]:
+        t = torch.from_numpy(rnd(50, (rows, K))).to(torch.bfloat16).cuda()
+        flat = binding.op_pack_tiled(t)
+        assert flat.numel() == ((rows + 31) // 32 * 32) * K
+        back = binding.tiled_to_rowmajor(flat.cpu(), rows, K)
+        assert torch.equal(back, t.cpu())
+        pad = binding.tiled_to_rowmajor(flat.cpu(), (rows + 31) // 32 * 32, K)[rows:]
+        assert torch.all(pad == 0)
+
+
+@pytest.mark.parametrize("M,N,K,S", [
+    (32, 256, 512, 1), (32, 256, 512, 2), (16, 3072, 2048, 0), (1, 128, 256, 1), (33, 128, 1024, 2),
+    (64, 384, 768, 1), (5, 6144, 4096, 0), (32, 4096, 14336, 0),
+    (65, 128, 256, 1), (200, 256, 512, 1), (130, 384, 1024, 1), (4096, 128, 256, 1),
+])
+def test_linear_tiled(M, N, K, S):
+    a = rnd(60, (M, K)); w = rnd(61, (N, K), 0.05)
+    ad, av = to_dev(a, "bf16"); wd, wv = to_dev(w, "bf16")
+    if S == 0:
+        S = binding.op_linear_splits("bf16", M, N, K, True)
+    print("case: linear tiled", M, N, K, S, flush=True)
+    out = binding.op_linear(binding.op_pack_tiled(ad), binding.op_pack_tiled(wd), S, tiled_shape=(M, N, K))
+    out = out.cpu().numpy().astype(np.float64).sum(0)
+    want = otf.linear(av, wv)
+    np.testing.assert_allclose(out, want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
+
+
+@pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512)])
+def test_linear_swiglu_tiled(M, N, K):
+    a = rnd(62, (M, K)); wg = rnd(63, (N, K), 0.05); wu = rnd(64, (N, K), 0.05)
+    ad, av = to_dev(a, "bf16"); gd, gv = to_dev(wg, "bf16"); ud, uv = to_dev(wu, "bf16")
+    print("case: swiglu tiled", M, N, K, flush=True)
+    flat = binding.op_linear_swiglu(binding.op_pack_tiled(ad), binding.op_pack_tiled(gd),
+                                    binding.op_pack_tiled(ud), tiled_shape=(M, N, K))
+    out = binding.tiled_to_rowmajor(flat.cpu(), M, N).float().numpy()
+    want = otf.silu(otf.linear(av, gv)) * otf.linear(av, uv)
+    np.testing.assert_allclose(out, want, rtol=0, atol=TOL["bf16"] * np.abs(want).max())
+
+
+def test_tiled_outputs_of_rmsnorm_and_attention():
+    import torch
+    rows, d = 37, 256
+    x = rnd(65, (rows, d)); g = 1 + rnd(66, (d,), 0.1)
+    gd, gv = to_dev(g, "bf16")
+    h_plain = binding.op_add_rmsnorm(torch.from_numpy(x.copy()).cuda(), None, gd, 1e-6)
+    h_tiled = binding.op_add_rmsnorm(torch.from_numpy(x.copy()).cuda(), None, gd, 1e-6, tiled=True)
+    assert torch.equal(binding.tiled_to_rowmajor(h_tiled.cpu(), rows, d), h_plain.cpu())
+    # attention output, [B][Hq*hd] tiled
+    B, Hq, Hkv, hd, pg, P, t = 5, 4, 2, 64, 16, 40, 9
+    kpd, vpd, _, _ = make_pools("bf16", 3, Hkv, pg, hd, 70)
+    ksd, vsd, _, _ = make_pools("bf16", B, Hkv, pg, hd, 72)
+    table = torch.arange(B, dtype=torch.int32, device="cuda").reshape(B, 1)
+    qd, _ = to_dev(rnd(74, (B, Hq, hd)), "bf16")
+    o_plain = binding.op_attention_decode(qd, kpd, vpd, ksd, vsd, table, P, t, pg)
+    o_tiled = binding.op_attention_decode(qd, kpd, vpd, ksd, vsd, table, P, t, pg, out_tiled=True)
+    assert torch.equal(binding.tiled_to_rowmajor(o_tiled.cpu(), B, Hq * hd), o_plain.cpu().reshape(B, Hq * hd))

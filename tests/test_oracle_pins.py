@@ -279,3 +279,37 @@ def test_page_table_reference_small_example():
     # exactly one page when n_steps == page size; two when one more
     assert paging.page_tables(1, 4, 4, range(4)).tolist() == [[0]]
     assert paging.page_tables(1, 5, 4, range(4)).tolist() == [[0, 1]]
+
+
+# ---------------------------------------------------------------- bf16 activation mode
+def test_round_bf16_against_closed_forms_and_library():
+    import torch
+    r = otf.round_bf16
+    # 8 significand bits: spacing 2^-7 in [1, 2); ties go to the even neighbour
+    assert r(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert r(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert r(np.array([1.0 + 2.0 ** -8 + 2.0 ** -20]))[0] == 1.0 + 2.0 ** -7
+    assert r(np.array([-0.3]))[0] == -0.30078125
+    assert np.array_equal(r(np.array([0.0, 1.0, -2.5, 2.0 ** -100])), [0.0, 1.0, -2.5, 2.0 ** -100])
+    x = synth.normal(8, 1, (20000,), 0.0, 3.0, "f32")
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(r(x), want)
+    assert np.abs(r(x) - x).max() <= np.abs(x).max() * 2.0 ** -8
+
+
+def test_bf16_activation_mode_rounds_only_activation_tensors():
+    s = small_shape(L=2, d=32, Hq=4, Hkv=2, hd=8, F=40, V=64, dtype="bf16")
+    w = synth.weights_as_f32(synth.make_weights(s, 9))
+    toks = synth.tokens(9, 1, (12,), s.vocab)
+    exact = otf.forward(oracle_config(s, exact=True), w, toks)[0]
+    rounded, cache = otf.forward(oracle_config(s), w, toks)
+    rel = np.linalg.norm(rounded - exact) / np.linalg.norm(exact)
+    assert 1e-5 < rel < 2e-2            # it does round, and only at the bf16 level
+    for l in range(s.n_layers):         # the cache holds bf16 values
+        assert np.array_equal(cache.k[l], otf.round_bf16(cache.k[l]))
+        assert np.array_equal(cache.v[l], otf.round_bf16(cache.v[l]))
+    assert oracle_config(small_shape()).act_dtype == "f64"
+    # shared == unshared and decode == prefill hold in this mode too (same values are rounded)
+    cfg = oracle_config(s)
+    plast, shared = otf.forward_shared(cfg, w, toks[:7], toks[7:][None])
+    np.testing.assert_allclose(shared[0], rounded[7:], rtol=0, atol=1e-12)
