@@ -88,16 +88,78 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(
   }
 }
 
+// The same, four elements per thread and the row kept in registers between the two phases
+// (d % 4 == 0, d <= 4 * VEC * blockDim).  bf16 output goes out as 8-byte stores; in the tiled
+// layout four consecutive k stay inside one 16-byte chunk.
+template <typename T, int VEC>
+__global__ __launch_bounds__(1024) void add_rmsnorm_vec_kernel(
+    int d, float *__restrict__ x, const float *__restrict__ partials, int n_partials,
+    size_t pstride, const T *__restrict__ gain, float eps, T *__restrict__ h, int h_tiled) {
+  __shared__ float scratch[16];
+  const int r = blockIdx.x, nt = blockDim.x;
+  const size_t row = (size_t)r * d;
+  float4 v[VEC];
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) {
+    const int i = 4 * (threadIdx.x + j * nt);
+    v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < d) {
+      v[j] = *(const float4 *)(x + row + i);
+      for (int s = 0; s < n_partials; ++s) {
+        const float4 p = *(const float4 *)(partials + s * pstride + row + i);
+        v[j].x += p.x; v[j].y += p.y; v[j].z += p.z; v[j].w += p.w;
+      }
+      if (n_partials) *(float4 *)(x + row + i) = v[j];
+      ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+    }
+  }
+  ss = block_sum<float>(ss, scratch);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) {
+    const int i = 4 * (threadIdx.x + j * nt);
+    if (i < d) {
+      const size_t at = h_tiled ? tiled_offset(r, i, d) : row + i;
+      const float o0 = v[j].x * inv * Cvt<T>::to_f32(gain[i]), o1 = v[j].y * inv * Cvt<T>::to_f32(gain[i + 1]),
+                  o2 = v[j].z * inv * Cvt<T>::to_f32(gain[i + 2]), o3 = v[j].w * inv * Cvt<T>::to_f32(gain[i + 3]);
+      if (sizeof(T) == 2) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(o0) | ((uint32_t)f32_to_bf16(o1) << 16);
+        pk.y = (uint32_t)f32_to_bf16(o2) | ((uint32_t)f32_to_bf16(o3) << 16);
+        *(uint2 *)(h + at) = pk;
+      } else {
+        *(float4 *)(h + at) = make_float4(o0, o1, o2, o3);
+      }
+    }
+  }
+}
+
+template <typename T>
+static void launch_add_rmsnorm_t(hipStream_t st, int rows, int d, float *x, const float *partials,
+                                 int n_partials, size_t ps, const T *gain, float eps, T *h, int h_tiled) {
+  if (d % 4 == 0 && d <= 16384) {
+    // enough threads for one float4 each where possible; at least one wave
+    const int quads = d / 4;
+    int nt = 64;
+    while (nt < 1024 && nt < quads) nt *= 2;
+    const int vec = (quads + nt - 1) / nt;
+    if (vec <= 1) add_rmsnorm_vec_kernel<T, 1><<<rows, nt, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+    else if (vec <= 2) add_rmsnorm_vec_kernel<T, 2><<<rows, nt, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+    else add_rmsnorm_vec_kernel<T, 4><<<rows, nt, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+  } else {
+    add_rmsnorm_kernel<T><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+  }
+}
+
 int launch_add_rmsnorm(hipStream_t st, int dtype, int rows, int d, float *x, const float *partials,
                        int n_partials, const void *gain, float eps, void *h_out, int h_tiled) {
   if (rows <= 0) return MC_OK;
   const size_t ps = (size_t)rows * d;
   if (dtype == MC_F32)
-    add_rmsnorm_kernel<float><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps,
-                                                    (const float *)gain, eps, (float *)h_out, h_tiled);
+    launch_add_rmsnorm_t<float>(st, rows, d, x, partials, n_partials, ps, (const float *)gain, eps, (float *)h_out, h_tiled);
   else
-    add_rmsnorm_kernel<bf16_t><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps,
-                                                     (const bf16_t *)gain, eps, (bf16_t *)h_out, h_tiled);
+    launch_add_rmsnorm_t<bf16_t>(st, rows, d, x, partials, n_partials, ps, (const bf16_t *)gain, eps, (bf16_t *)h_out, h_tiled);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }

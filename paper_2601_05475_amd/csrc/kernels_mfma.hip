@@ -21,8 +21,12 @@ namespace mc {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+// 16-byte register quantity as a native vector: arrays of it are promoted to registers (arrays
+// of the runtime's struct-based uint4 that are updated under a condition end up in scratch)
+typedef __attribute__((ext_vector_type(4))) uint32_t v4u;
+__device__ inline v4u make_v4u(uint32_t a, uint32_t b, uint32_t c, uint32_t d) { return v4u{a, b, c, d}; }
 
-__device__ inline f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
+__device__ inline f32x16 mfma32(v4u a, v4u b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
@@ -38,9 +42,9 @@ __device__ inline uint2 pack4_bf16(float a, float b, float c, float d) {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 // streaming 16-byte load: the data is used once, keep it out of the way of reusable lines
-__device__ inline uint4 load_stream(const bf16_t *p) {
+__device__ inline v4u load_stream(const bf16_t *p) {
   const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
-  return make_uint4(v[0], v[1], v[2], v[3]);
+  return make_v4u(v[0], v[1], v[2], v[3]);
 }
 
 // ---- row-major -> tiled repack (one thread per 16-byte chunk of the destination) -----------
@@ -54,9 +58,9 @@ __global__ void pack_tiled_kernel(int rows, int rows_pad, int K, const bf16_t *_
   const int U = K >> 6;
   const int rt = (int)(blk / U), u = (int)(blk % U);
   const int row = 32 * rt + (lane & 31), k = 64 * u + 32 * (lane >> 5) + 8 * c;
-  uint4 v = make_uint4(0, 0, 0, 0);
-  if (row < rows) v = *(const uint4 *)(src + (size_t)row * K + k);
-  *(uint4 *)(dst + chunk * 8) = v;
+  v4u v = make_v4u(0, 0, 0, 0);
+  if (row < rows) v = *(const v4u *)(src + (size_t)row * K + k);
+  *(v4u *)(dst + chunk * 8) = v;
 }
 
 int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst) {
@@ -97,18 +101,18 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][mb][r] = 0.f;
 
-  uint4 wf[2][4], uf[2][4], af[2][MB][4];
-  auto issue = [&](int slot, int u) {
+  v4u wf[2][4], uf[2][4], af[2][MB][4];
+  auto issue = [&](int slot, int u) __attribute__((always_inline)) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       wf[slot][c] = load_stream(wp + (size_t)u * 2048 + c * 512);
       if (SWIGLU) uf[slot][c] = load_stream(up + (size_t)u * 2048 + c * 512);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
-        af[slot][mb][c] = *(const uint4 *)(ap + ((size_t)mb * U + u) * 2048 + c * 512);
+        af[slot][mb][c] = *(const v4u *)(ap + ((size_t)mb * U + u) * 2048 + c * 512);
     }
   };
-  auto compute = [&](int slot) {
+  auto compute = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -215,20 +219,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(
     int M, int N, int K, const bf16_t *__restrict__ a, const bf16_t *__restrict__ w,
     const bf16_t *__restrict__ w2, float *__restrict__ out, bf16_t *__restrict__ out_t) {
   constexpr int NW = SWIGLU ? 2 : 1;
-  __shared__ uint4 As[4 * 256];            // 4 row tiles x (4 chunks x 64 lanes)
-  __shared__ uint4 Ws[NW][4 * 256];
+  __shared__ v4u As[4 * 256];            // 4 row tiles x (4 chunks x 64 lanes)
+  __shared__ v4u Ws[NW][4 * 256];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, h = lane >> 5;
   const int wn = wave & 1, wm = wave >> 1;
   const int U = K >> 6;
   const int nt0 = blockIdx.x * 4, mt0 = blockIdx.y * 4;
   const int m_tiles = (M + 31) >> 5;
   // staging: thread t copies chunk t of every block (4 blocks per operand)
-  const uint4 *ag[4], *wg[4], *ug[4];
+  const v4u *ag[4], *wg[4], *ug[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    ag[i] = (const uint4 *)(a + (size_t)min(mt0 + i, m_tiles - 1) * U * 2048) + tid;
-    wg[i] = (const uint4 *)(w + (size_t)(nt0 + i) * U * 2048) + tid;
-    ug[i] = SWIGLU ? (const uint4 *)(w2 + (size_t)(nt0 + i) * U * 2048) + tid : nullptr;
+    ag[i] = (const v4u *)(a + (size_t)min(mt0 + i, m_tiles - 1) * U * 2048) + tid;
+    wg[i] = (const v4u *)(w + (size_t)(nt0 + i) * U * 2048) + tid;
+    ug[i] = SWIGLU ? (const v4u *)(w2 + (size_t)(nt0 + i) * U * 2048) + tid : nullptr;
   }
   f32x16 acc[NW][2][2];
 #pragma unroll
@@ -239,7 +243,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(
       for (int y = 0; y < 2; ++y)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][x][y][r] = 0.f;
-  uint4 pa[4], pw[4], pu[4];
+  v4u pa[4], pw[4], pu[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     pa[i] = ag[i][0];
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      uint4 fa[2], fw[NW][2];
+      v4u fa[2], fw[NW][2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         fa[t] = As[(2 * wm + t) * 256 + c * 64 + lane];
@@ -318,9 +322,5 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const v
   MC_HIP(hipGetLastError());
   return MC_OK;
 }
-
-bool decode_attention_mfma_supported(const DecodeAttnArgs &) { return false; }
-size_t decode_attention_mfma_ws_bytes(int, int, int, int, int, int, int) { return 0; }
-int launch_attention_decode_mfma(hipStream_t, const DecodeAttnArgs &) { MC_FAIL(MC_ERR_UNSUPPORTED, "not built"); }
 
 }  // namespace mc

@@ -105,7 +105,7 @@ def test_rope_kv_write(dtype):
     assert np.all(kh[~written[:, None, :, None].repeat(Hkv, 1).repeat(hd, 3)] == 0)
 
 
-def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20):
+def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20, stride=1):
     import torch
     n_pre = -(-P // pg) if P else 0
     per = -(-t // pg) if t else 0
@@ -122,6 +122,8 @@ def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20):
     worst = 0.0
     for b in range(B):
         for a in range(Hq):
+            if (b * Hq + a) % stride:
+                continue
             c = a // G
             keys = [kpv[:, c].reshape(-1, hd)[:P]] if P else []
             vals = [vpv[:, c].reshape(-1, hd)[:P]] if P else []
@@ -141,6 +143,20 @@ def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20):
 def test_attention_decode(dtype, B, Hq, Hkv, hd, pg, P, t):
     worst, _ = attention_case(dtype, B, Hq, Hkv, hd, pg, P, t)
     assert worst < (2e-5 if dtype == "f32" else 1.5e-2), worst
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,hd,P,t,stride", [
+    (32, 32, 8, 128, 4096, 512, 7),      # 8B-shape headline workload at its last step
+    (32, 32, 8, 128, 4096, 1, 7),        # ... and at its first
+    (16, 32, 8, 64, 2048, 256, 5),       # 1B shape
+    (64, 40, 8, 128, 16384, 1024, 41),   # 32B shape: 320 query rows per KV head, 3 row blocks
+    (64, 32, 8, 128, 4096, 0, 13),       # reranking fan-out, prefix only
+    (2, 8, 8, 128, 63, 65, 1), (3, 8, 4, 64, 65, 64, 1), (5, 16, 2, 128, 129, 127, 1),
+    (1, 32, 1, 64, 128, 129, 1), (7, 4, 2, 128, 0, 200, 1), (33, 8, 2, 128, 257, 1, 1),
+])
+def test_attention_decode_mfma_shapes(B, Hq, Hkv, hd, P, t, stride):
+    worst, _ = attention_case("bf16", B, Hq, Hkv, hd, 64, P, t, stride=stride)
+    assert worst < 1.5e-2, worst
 
 
 def test_attention_split_count_invariance():
