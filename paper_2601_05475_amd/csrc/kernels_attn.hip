@@ -53,14 +53,18 @@ template <int HD> struct AttnTile {
   static constexpr int CPT = CHUNKS / 256;              // chunks per thread per page per tensor
 };
 
+constexpr int kMaxPids = 512;                // suffix page ids kept in LDS (longer suffixes read them from memory)
+
 struct AttnItems {
   int n_prefix_items, n_suffix_items;
   int splits, row_blocks, pages_per_split;   // prefix
   int n_prefix_pages, rows;                  // rows = B * G
+  int pid_offset;                            // byte offset of the page-id array in LDS
 };
 
 template <int HD>
-__global__ __launch_bounds__(256) void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
                                                                float *__restrict__ part_o,
                                                                float *__restrict__ part_ml) {
   using TL = AttnTile<HD>;
@@ -121,45 +125,50 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(DecodeAttnArgs a,
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  // ---- staging: thread t carries chunk t + 256 i of K and of V of both pages
+  // ---- staging: thread t carries chunks t + 256 i of the K and of the V page in flight
   const size_t page_stride = (size_t)Hkv * PG * HD;           // elements per page (all kv heads)
   const size_t head_off = (size_t)kvh * PG * HD;
-  v4u sk[2][TL::CPT], sv[2][TL::CPT];
-  auto page_id = [&](int pi) __attribute__((always_inline)) -> int { return table ? table[pi] : pi; };
-  auto issue = [&](int it_idx) __attribute__((always_inline)) {
+  // three register stages: pages i + 1, i + 2, i + 3 are in flight while page i is consumed
+  v4u sk[3][TL::CPT], sv[3][TL::CPT];
+  // A suffix item's page ids are copied to LDS once: fetching one from global memory inside the
+  // loop would put a full memory round trip in front of every prefetch.
+  int *pids = (int *)(lds_raw + it.pid_offset);
+  const bool pids_in_lds = table != nullptr && n_pages <= kMaxPids;
+  if (pids_in_lds) {
+    for (int i = tid; i < n_pages; i += 256) pids[i] = table[i];
+    __syncthreads();
+  }
+  auto page_id = [&](int pi) __attribute__((always_inline)) -> int {
+    return table ? (pids_in_lds ? pids[pi] : table[pi]) : pi;
+  };
+  // Every call issues the same number of loads, whether or not page pi exists: past the end all
+  // lanes re-read one 16-byte piece of the item's first page (the data is never used).  With no
+  // branch around the loads the compiler's load counters stay exact, so a commit waits for its own
+  // stage only and the two younger stages stay in flight.
+  auto issue = [&](int stage, int pi) __attribute__((always_inline)) {
+    const bool real = pi < n_pages;
+    const size_t base = (size_t)page_id(first_page + (real ? pi : 0)) * page_stride + head_off;
+    const size_t lane_off = real ? (size_t)tid * 8 : 0, step = real ? 256 * 8 : 0;
 #pragma unroll
-    for (int pp = 0; pp < 2; ++pp) {
-      const int pi = 2 * it_idx + pp;
-      if (pi < n_pages) {
-        const size_t base = (size_t)page_id(first_page + pi) * page_stride + head_off;
-#pragma unroll
-        for (int i = 0; i < TL::CPT; ++i) {
-          sk[pp][i] = *(const v4u *)(kpool + base + (size_t)(tid + 256 * i) * 8);
-          sv[pp][i] = *(const v4u *)(vpool + base + (size_t)(tid + 256 * i) * 8);
-        }
-      }
+    for (int i = 0; i < TL::CPT; ++i) {
+      sk[stage][i] = *(const v4u *)(kpool + base + lane_off + step * i);
+      sv[stage][i] = *(const v4u *)(vpool + base + lane_off + step * i);
     }
   };
-  auto commit = [&](int it_idx) __attribute__((always_inline)) {
+  auto commit = [&](int stage, int buf) __attribute__((always_inline)) {
+    bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
 #pragma unroll
-    for (int pp = 0; pp < 2; ++pp) {
-      const int pi = 2 * it_idx + pp;
-      if (pi < n_pages) {
-        bf16_t *kt = lds + pp * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
-#pragma unroll
-        for (int i = 0; i < TL::CPT; ++i) {
-          const int ci = tid + 256 * i;
-          *(v4u *)(kt + (ci / (HD / 8)) * TL::KLD + (ci % (HD / 8)) * 8) = sk[pp][i];
-          *(v4u *)(vt + (ci / (PG / 8)) * TL::VLD + (ci % (PG / 8)) * 8) = sv[pp][i];
-        }
-      }
+    for (int i = 0; i < TL::CPT; ++i) {
+      const int ci = tid + 256 * i;
+      *(v4u *)(kt + (ci / (HD / 8)) * TL::KLD + (ci % (HD / 8)) * 8) = sk[stage][i];
+      *(v4u *)(vt + (ci / (PG / 8)) * TL::VLD + (ci % (PG / 8)) * 8) = sv[stage][i];
     }
   };
 
-  // one 32-key block: blk = 2 * (page in pair) + (half of the page)
-  auto process = [&](int blk, int n_valid) __attribute__((always_inline)) {
-    const bf16_t *kt = lds + (blk >> 1) * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
-    const int kb = (blk & 1) * 32;
+  // one 32-key block: half `blk` of the page held in LDS buffer `buf`
+  auto process = [&](int buf, int blk, int n_valid) __attribute__((always_inline)) {
+    const bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
+    const int kb = blk * 32;
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -179,23 +188,30 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(DecodeAttnArgs a,
 #pragma unroll
     for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx * scale2);    // finite: a processed block has a valid key
-    const float corr = __builtin_amdgcn_exp2f(m - m_new);
-    float rs = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m_new));
-      rs += s[r];
-    }
-    rs += __shfl_xor(rs, 32, 64);
-    l = l * corr + rs;
-    m = m_new;
-    if (__any(corr != 1.0f)) {                    // the maximum rarely moves after the first blocks
+    // Lazy reference: m only has to stay within kTau of the true running maximum (then every
+    // 2^(score - m) <= 2^kTau, harmless in fp32 and bf16); sums and weighted values are all taken
+    // against the same m, so the normalised result does not depend on it.  The costly rescale of
+    // the 16 * HD/32 accumulators then happens in the first block(s) only.
+    constexpr float kTau = 8.0f;
+    const float mx2 = mx * scale2;                // finite: a processed block has a valid key
+    if (__any(mx2 > m + kTau)) {
+      const float m_new = fmaxf(m, mx2);
+      const float corr = __builtin_amdgcn_exp2f(m - m_new);   // m = -inf at the start: 0
+      l *= corr;
+      m = m_new;
 #pragma unroll
       for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] *= corr;
     }
+    float rs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m));
+      rs += s[r];
+    }
+    rs += __shfl_xor(rs, 32, 64);
+    l += rs;
     // probabilities as the B operand: slab sl holds keys kmap(8 sl .. 8 sl + 7)
     v4u pb[2];
     pb[0] = make_v4u(pack2_bf16(s[0], s[1]), pack2_bf16(s[2], s[3]), pack2_bf16(s[4], s[5]), pack2_bf16(s[6], s[7]));
@@ -210,23 +226,37 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(DecodeAttnArgs a,
       }
   };
 
-  const int n_iter = (n_pages + 1) / 2;
-  if (n_iter > 0) issue(0);
-  for (int i = 0; i < n_iter; ++i) {
-    __syncthreads();                 // the previous pair has been consumed
-    commit(i);
-    __syncthreads();
-    if (i + 1 < n_iter) issue(i + 1);
-    const int key0 = i * 2 * PG;     // first key of this pair, relative to the item's first page
+  // Page i is consumed from LDS buffer i % 2 while page i + 1 is in flight to registers.  One
+  // barrier per page: commit(i + 1) overwrites the buffer read during page i - 1, and every wave
+  // has left that page before it reaches the barrier of page i.
+  auto consume = [&](int i) __attribute__((always_inline)) {
+    const int buf = i & 1;
+    const int key0 = i * PG;         // first key of this page, relative to the item's first page
     if (is_prefix) {
 #pragma unroll
-      for (int blk = 0; blk < 4; ++blk) {
+      for (int blk = 0; blk < 2; ++blk) {
         const int nv = min(32, n_keys - (key0 + 32 * blk));
-        if (nv > 0) process(blk, nv);
+        if (nv > 0) process(buf, blk, nv);
       }
-    } else {
+    } else if (wave < 2) {           // a suffix page has two blocks: waves 2, 3 only help to stage
       const int nv = min(32, n_keys - (key0 + 32 * wave));
-      if (nv > 0) process(wave, nv);
+      if (nv > 0) process(buf, wave, nv);
+    }
+  };
+  // Page pi is consumed from LDS buffer pi % 2.  One barrier per page is enough: commit(pi)
+  // overwrites the buffer read during page pi - 2, and every wave has left that page before it
+  // arrives at the barrier of page pi - 1.  Stages past the last page run as no-ops on dummy
+  // data (n_pages >= 1 for every item).
+#pragma unroll
+  for (int st = 0; st < 3; ++st) issue(st, st);
+  for (int i = 0; i < n_pages; i += 3) {
+#pragma unroll
+    for (int st = 0; st < 3; ++st) {
+      const int pi = i + st;
+      commit(st, pi & 1);
+      __syncthreads();
+      issue(st, pi + 3);
+      if (pi < n_pages) consume(pi);
     }
   }
 
@@ -294,16 +324,36 @@ template <int HD>
 __global__ __launch_bounds__(HD) void decode_attention_merge_kernel(
     int n_parts, int B, int Hq, const float *__restrict__ part_o, const float *__restrict__ part_ml,
     bf16_t *__restrict__ out, int out_tiled) {
+  // The (m, l) pairs are fetched by one thread each, in parallel, and turned into weights in
+  // LDS; the value sums then run over independent loads, eight parts in flight at a time.
+  constexpr int kMaxParts = 1024;
+  __shared__ float sw[kMaxParts], sl[kMaxParts];
   const int bh = blockIdx.x, d = threadIdx.x;
   const size_t stride = (size_t)B * Hq;
-  float M = -INFINITY;
-  for (int p = 0; p < n_parts; ++p) M = fmaxf(M, part_ml[(p * stride + bh) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int p = 0; p < n_parts; ++p) {
-    const float f = __builtin_amdgcn_exp2f(part_ml[(p * stride + bh) * 2] - M);
-    num += f * part_o[(p * stride + bh) * HD + d];
-    den += f * part_ml[(p * stride + bh) * 2 + 1];
+  for (int p = d; p < n_parts; p += HD) {
+    const float2 ml = *(const float2 *)(part_ml + (p * stride + bh) * 2);
+    sw[p] = ml.x;
+    sl[p] = ml.y;
   }
+  __syncthreads();
+  float M = -INFINITY;
+  for (int p = 0; p < n_parts; ++p) M = fmaxf(M, sw[p]);
+  __syncthreads();
+  for (int p = d; p < n_parts; p += HD) sw[p] = __builtin_amdgcn_exp2f(sw[p] - M);
+  __syncthreads();
+  float den = 0.f;
+  for (int p = 0; p < n_parts; ++p) den += sw[p] * sl[p];
+  float num = 0.f;
+  const float *po = part_o + (size_t)bh * HD + d;
+  int p = 0;
+  for (; p + 8 <= n_parts; p += 8) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = po[(p + j) * stride * HD];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) num += sw[p + j] * v[j];
+  }
+  for (; p < n_parts; ++p) num += sw[p] * po[p * stride * HD];
   const int b = bh / Hq, head = bh % Hq;
   const size_t at = out_tiled ? tiled_offset(b, head * HD + d, Hq * HD) : (size_t)bh * HD + d;
   out[at] = f32_to_bf16(num / den);
@@ -320,10 +370,10 @@ static AttnItems plan_items(const DecodeAttnArgs &a) {
     const int pairs = (it.n_prefix_pages + 1) / 2;
     splits = a.prefix_splits;
     if (splits <= 0) {
-      // enough items to cover the chip, but at least two page pairs (256 keys) per item so that
+      // enough items to cover the chip, but at least four page pairs (512 keys) per item so that
       // the partial sums written per item stay small next to the keys/values read
       const int per_head = std::max(1, 256 / std::max(1, a.n_kv_heads * it.row_blocks));
-      splits = std::min(per_head, std::max(1, pairs / 2));
+      splits = std::min(per_head, std::max(1, pairs / 4));
     }
     splits = std::max(1, std::min(splits, pairs));
     it.pages_per_split = ((pairs + splits - 1) / splits) * 2;
@@ -354,16 +404,20 @@ size_t decode_attention_mfma_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int 
 }
 
 template <int HD>
-static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, const AttnItems &it) {
+static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, const AttnItems &it_in) {
   using TL = AttnTile<HD>;
-  const int n_parts = (a.prefix_len > 0 ? it.splits : 0) + (a.suffix_len > 0 ? 1 : 0);
+  const int n_parts = (a.prefix_len > 0 ? it_in.splits : 0) + (a.suffix_len > 0 ? 1 : 0);
   const size_t rows = (size_t)a.n_cands * a.n_q_heads;
   const size_t need = (size_t)n_parts * rows * (HD + 2) * sizeof(float);
   if (a.workspace_bytes < need) MC_FAIL(MC_ERR_INVALID, "attention workspace has %zu bytes, %zu needed", a.workspace_bytes, need);
+  if (n_parts > 1024) MC_FAIL(MC_ERR_UNSUPPORTED, "decode attention: %d partial states exceed 1024", n_parts);
   float *part_o = (float *)a.workspace;
   float *part_ml = part_o + (size_t)n_parts * rows * HD;
   const int G = a.n_q_heads / a.n_kv_heads;
-  const size_t lds = std::max((size_t)TL::LDS_BYTES, (size_t)(256 + 4 * G * HD) * sizeof(float));
+  const size_t lds_main = (std::max((size_t)TL::LDS_BYTES, (size_t)(256 + 4 * G * HD) * sizeof(float)) + 15) / 16 * 16;
+  const size_t lds = lds_main + kMaxPids * sizeof(int);
+  AttnItems it = it_in;
+  it.pid_offset = (int)lds_main;
   static bool attr_set = false;          // per template instance
   if (!attr_set) {
     MC_HIP(hipFuncSetAttribute((const void *)decode_attention_kernel<HD>,
