@@ -245,6 +245,19 @@ int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t
                            int32_t table_stride, int32_t prefix_splits, void *workspace,
                            size_t workspace_bytes, void *out, int32_t out_tiled);
 
+/* Causal attention for many query rows (prefix prefill, candidate scoring); bf16, 64-token
+ * pages, head_dim 64 or 128.  items: device int32 [n_items][4] = (first row, rows <= 32,
+ * position of the first row, page-table row or -1): 32 consecutive positions of one sequence.
+ * A row at position p attends to keys 0..p: positions < prefix_len from the prefix pages (in
+ * order), later ones from pages page_table[row][.] of the suffix pool.  q: [rows][Hq][hd];
+ * out: [rows][Hq*hd], row-major or tiled (out_tiled = 1). */
+int mc_op_attention_prefill(void *stream, int32_t n_items, const int32_t *items,
+                            int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                            int32_t page_tokens, int32_t prefix_len, const void *q,
+                            const void *k_prefix, const void *v_prefix, const void *k_suffix,
+                            const void *v_suffix, const int32_t *page_table,
+                            int32_t table_stride, void *out, int32_t out_tiled);
+
 /* Sampling from fp32 logits [rows][vocab] (row_stride 0 = every candidate reads row 0).
  * uniforms: device [n_cands].  out_tokens: device [n_cands]; out_topk: device
  * [n_cands][k] or NULL.  Same rule as mc_sample. */

@@ -87,6 +87,7 @@ SIGNATURES = {
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
     "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _i32]),
+    "mc_op_attention_prefill": (C.c_int, [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32]),
     "mc_op_sample": (C.c_int, [_vp, _i32, _i32, _vp, _sz, _f32, _i32, _vp, _vp, _vp]),
     "mc_op_reward_score": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
 }
@@ -403,6 +404,27 @@ def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, p
         p(k_prefix), p(v_prefix), p(k_suffix), p(v_suffix), p(page_table),
         0 if page_table is None else page_table.shape[1], prefix_splits, ws.data_ptr(), ws.numel(),
         out.data_ptr(), int(out_tiled)))
+    return out
+
+
+def op_attention_prefill(q, items, k_prefix, v_prefix, k_suffix, v_suffix, page_table, prefix_len,
+                         page_tokens, out_tiled: bool = False):
+    """q: bf16 [rows, Hq, hd]; items: int32 [n, 4] on device (first row, rows, first position,
+    table row or -1).  Returns out [rows, Hq, hd] (or the flat tiled [rows, Hq*hd])."""
+    import torch
+    lib = load_library()
+    rows, Hq, hd = q.shape
+    Hkv = k_prefix.shape[1]
+    if out_tiled:
+        out = torch.zeros(lib.mc_op_tiled_bytes(rows, Hq * hd) // 2, dtype=q.dtype, device=q.device)
+    else:
+        out = torch.empty_like(q)
+    p = lambda t: None if t is None else t.data_ptr()
+    _check(lib.mc_op_attention_prefill(
+        _stream(), items.shape[0], items.data_ptr(), Hq, Hkv, hd, page_tokens, prefix_len,
+        q.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(), p(k_suffix), p(v_suffix),
+        p(page_table), 0 if page_table is None else page_table.shape[1], out.data_ptr(),
+        int(out_tiled)))
     return out
 
 

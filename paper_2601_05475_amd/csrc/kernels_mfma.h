@@ -18,6 +18,23 @@ bool gemm_supported(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                      const void *w2, float *out, void *out_t);
 
+// Causal attention over many rows.  items[i] = (first row, rows <= 32, position of the first
+// row, page-table row or -1): 32 consecutive positions of one sequence.  Keys at positions
+// < prefix_len come from the prefix pages, later ones from the sequence's suffix pages.
+struct PrefillAttnArgs {
+  const void *q;                 // bf16 [rows][Hq][hd]
+  const void *k_prefix, *v_prefix, *k_suffix, *v_suffix;
+  const int4 *items;             // device
+  int32_t n_items;
+  const int32_t *page_table;
+  int32_t table_stride;
+  int32_t n_q_heads, n_kv_heads, head_dim, page_tokens, prefix_len;
+  void *out;                     // bf16 [rows][Hq*hd], row-major or tiled
+  int32_t out_tiled;
+};
+bool prefill_attention_mfma_supported(int page_tokens, int head_dim, int Hq, int Hkv);
+int launch_attention_prefill_mfma(hipStream_t st, const PrefillAttnArgs &a);
+
 bool decode_attention_mfma_supported(const DecodeAttnArgs &a);
 size_t decode_attention_mfma_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int prefix_len,
                                       int suffix_len, int page_tokens);

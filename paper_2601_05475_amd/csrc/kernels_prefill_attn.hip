@@ -1,0 +1,247 @@
+// Causal attention for many query rows (prefix prefill and candidate scoring), bf16, gfx950 MFMA.
+//
+// A work item is 32 consecutive positions of one sequence, one KV head and up to four of its
+// query heads: wave w owns head 4 * hg + w of the group, the 32 positions are its MFMA columns.
+// Keys are streamed page by page (64 keys) through LDS and shared by the four waves: first the
+// shared-prefix pages that are visible to the block, then (scoring) the sequence's own suffix
+// pages.  Each item sees all keys of its rows, so it normalises and writes bf16 itself.
+// Tile layout, operand mapping and the softmax scheme are those of the decode kernel
+// (transposed scores, lazy base-2 reference maximum); the addition is the causal mask, applied
+// only to blocks that reach past the first position of the item.
+#include "kernels_mfma.h"
+
+#include <algorithm>
+
+namespace mc {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t v4u;
+typedef __attribute__((ext_vector_type(2))) uint32_t v2u;
+
+__device__ inline f32x16 mfma32p(v4u a, v4u b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ inline uint32_t pack2p_bf16(float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
+}
+
+constexpr int PPG = 64;                       // keys per page
+
+template <int HD> struct PTile {
+  static constexpr int KLD = HD + 8, VLD = PPG + 8;
+  static constexpr int K_ELEMS = PPG * KLD, V_ELEMS = HD * VLD, PAGE_ELEMS = K_ELEMS + V_ELEMS;
+  static constexpr int LDS_BYTES = 2 * PAGE_ELEMS * 2;
+  static constexpr int CPT = PPG * HD / 8 / 256;
+};
+
+constexpr int kPrefillMaxPids = 1024;
+
+template <int HD>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void prefill_attention_kernel(PrefillAttnArgs a) {
+  using TL = PTile<HD>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char plds_raw[];
+  bf16_t *lds = (bf16_t *)plds_raw;
+  int *pids = (int *)(plds_raw + TL::LDS_BYTES);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, h = lane >> 5;
+  const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, G = Hq / Hkv, HG = (G + 3) / 4;
+
+  int id = blockIdx.x;
+  const int hg = id % HG; id /= HG;
+  const int kvh = id % Hkv; id /= Hkv;
+  const int4 item = a.items[id];               // row_start, n_rows (<= 32), pos_start, table row
+  const int row_start = item.x, n_rows = item.y, pos_start = item.z, tab = item.w;
+  const int g = 4 * hg + wave;
+  const bool wave_active = g < G;               // uniform per wave
+  const int head = kvh * G + (wave_active ? g : 0);
+  const bool col_valid = col < n_rows;
+  const int my_pos = pos_start + (col_valid ? col : 0);
+
+  // visible keys: prefix [0, nA), then own suffix [0, nB) at absolute positions prefix_len + j
+  const int last_pos = pos_start + n_rows - 1;
+  const int nA = min(a.prefix_len, last_pos + 1);
+  const int nB = (tab >= 0 && last_pos >= a.prefix_len) ? last_pos - a.prefix_len + 1 : 0;
+  const int nPA = (nA + PPG - 1) / PPG, nPB = (nB + PPG - 1) / PPG, n_pages = nPA + nPB;
+  const int32_t *table = (nPB > 0) ? a.page_table + (size_t)tab * a.table_stride : nullptr;
+  const bool pids_in_lds = nPB <= kPrefillMaxPids;
+  if (nPB > 0 && pids_in_lds) {
+    for (int i = tid; i < nPB; i += 256) pids[i] = table[i];
+    __syncthreads();
+  }
+
+  v4u qf[HD / 16];
+  {
+    const bf16_t *qrow = (const bf16_t *)a.q + ((size_t)(row_start + (col_valid ? col : 0)) * Hq + head) * HD + 8 * h;
+#pragma unroll
+    for (int c = 0; c < HD / 16; ++c) qf[c] = *(const v4u *)(qrow + 16 * c);
+  }
+  const float scale2 = 1.4426950408889634f / sqrtf((float)HD);
+  f32x16 o[HD / 32];
+#pragma unroll
+  for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  const size_t page_stride = (size_t)Hkv * PPG * HD, head_off = (size_t)kvh * PPG * HD;
+  const bf16_t *kA = (const bf16_t *)a.k_prefix, *vA = (const bf16_t *)a.v_prefix;
+  const bf16_t *kB = (const bf16_t *)a.k_suffix, *vB = (const bf16_t *)a.v_suffix;
+  v4u sk[3][TL::CPT], sv[3][TL::CPT];
+  // same number of loads whether or not the page exists (see the decode kernel)
+  auto issue = [&](int stage, int pi) __attribute__((always_inline)) {
+    const bool real = pi < n_pages;
+    const int p = real ? pi : 0;
+    const bool in_a = p < nPA;
+    const int page = in_a ? p : (pids_in_lds ? pids[p - nPA] : table[p - nPA]);
+    const bf16_t *kp = (in_a ? kA : kB) + (size_t)page * page_stride + head_off;
+    const bf16_t *vp = (in_a ? vA : vB) + (size_t)page * page_stride + head_off;
+    const size_t lane_off = real ? (size_t)tid * 8 : 0, step = real ? 256 * 8 : 0;
+#pragma unroll
+    for (int i = 0; i < TL::CPT; ++i) {
+      sk[stage][i] = *(const v4u *)(kp + lane_off + step * i);
+      sv[stage][i] = *(const v4u *)(vp + lane_off + step * i);
+    }
+  };
+  auto commit = [&](int stage, int buf) __attribute__((always_inline)) {
+    bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
+#pragma unroll
+    for (int i = 0; i < TL::CPT; ++i) {
+      const int ci = tid + 256 * i;
+      *(v4u *)(kt + (ci / (HD / 8)) * TL::KLD + (ci % (HD / 8)) * 8) = sk[stage][i];
+      *(v4u *)(vt + (ci / (PPG / 8)) * TL::VLD + (ci % (PPG / 8)) * 8) = sv[stage][i];
+    }
+  };
+  // one 32-key block whose key 0 sits at absolute position abs0; n_valid keys exist
+  auto process = [&](int buf, int blk, int n_valid, int abs0) __attribute__((always_inline)) {
+    const bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
+    const int kb = blk * 32;
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int c = 0; c < HD / 16; ++c) {
+      const v4u kf = *(const v4u *)(kt + (kb + col) * TL::KLD + 16 * c + 8 * h);
+      s = mfma32p(kf, qf[c], s);
+    }
+    // key of register r: 8 (r / 4) + 4 h + r % 4; it is masked if it does not exist or lies
+    // after this lane's query position
+    if (n_valid < 32 || abs0 + 31 > pos_start) {
+      const int lim = min(n_valid, my_pos - abs0 + 1);      // keys [0, lim) are visible
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (8 * (r >> 2) + 4 * h + (r & 3) >= lim) s[r] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+#pragma unroll
+    for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    constexpr float kTau = 8.0f;
+    const float mx2 = mx * scale2;                // -inf for a column that sees no key here
+    if (__any(mx2 > m + kTau)) {
+      const float m_new = fmaxf(m, mx2);
+      const float corr = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
+      l *= corr;
+      m = m_new;
+#pragma unroll
+      for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= corr;
+    }
+    // a column with no visible key so far keeps m = -inf: use 0 as reference, all its p are 0
+    const float mref = (m == -INFINITY) ? 0.f : m;
+    float rs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -mref));
+      rs += s[r];
+    }
+    rs += __shfl_xor(rs, 32, 64);
+    l += rs;
+    v4u pb[2];
+    pb[0] = v4u{pack2p_bf16(s[0], s[1]), pack2p_bf16(s[2], s[3]), pack2p_bf16(s[4], s[5]), pack2p_bf16(s[6], s[7])};
+    pb[1] = v4u{pack2p_bf16(s[8], s[9]), pack2p_bf16(s[10], s[11]), pack2p_bf16(s[12], s[13]), pack2p_bf16(s[14], s[15])};
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+      for (int sl = 0; sl < 2; ++sl) {
+        const bf16_t *vrow = vt + (dt * 32 + col) * TL::VLD + kb + 16 * sl + 4 * h;
+        const v2u lo = *(const v2u *)vrow, hi = *(const v2u *)(vrow + 8);
+        o[dt] = mfma32p(v4u{lo.x, lo.y, hi.x, hi.y}, pb[sl], o[dt]);
+      }
+  };
+  auto consume = [&](int pi) __attribute__((always_inline)) {
+    if (!wave_active) return;
+    const bool in_a = pi < nPA;
+    const int abs_page = in_a ? pi * PPG : a.prefix_len + (pi - nPA) * PPG;
+    const int keys_here = in_a ? min(PPG, nA - pi * PPG) : min(PPG, nB - (pi - nPA) * PPG);
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk) {
+      const int nv = min(32, keys_here - 32 * blk);
+      if (nv > 0) process(pi & 1, blk, nv, abs_page + 32 * blk);
+    }
+  };
+
+#pragma unroll
+  for (int st = 0; st < 3; ++st) issue(st, st);
+  for (int i = 0; i < n_pages; i += 3) {
+#pragma unroll
+    for (int st = 0; st < 3; ++st) {
+      const int pi = i + st;
+      commit(st, pi & 1);
+      __syncthreads();
+      issue(st, pi + 3);
+      if (pi < n_pages) consume(pi);
+    }
+  }
+
+  if (wave_active && col_valid) {
+    const float inv = 1.0f / l;                  // l > 0: every row sees at least its own key
+    bf16_t *out = (bf16_t *)a.out;
+    const int row = row_start + col;
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int d = dt * 32 + 8 * r4 + 4 * h;
+        const size_t at = a.out_tiled ? tiled_offset(row, head * HD + d, Hq * HD)
+                                      : ((size_t)row * Hq + head) * HD + d;
+        v2u pk = {pack2p_bf16(o[dt][4 * r4] * inv, o[dt][4 * r4 + 1] * inv),
+                  pack2p_bf16(o[dt][4 * r4 + 2] * inv, o[dt][4 * r4 + 3] * inv)};
+        *(v2u *)(out + at) = pk;
+      }
+  }
+}
+
+bool prefill_attention_mfma_supported(int page_tokens, int head_dim, int Hq, int Hkv) {
+  return page_tokens == PPG && (head_dim == 64 || head_dim == 128) && Hq % Hkv == 0;
+}
+
+template <int HD>
+static int launch_prefill_t(hipStream_t st, const PrefillAttnArgs &a) {
+  using TL = PTile<HD>;
+  const int G = a.n_q_heads / a.n_kv_heads, HG = (G + 3) / 4;
+  const size_t lds = TL::LDS_BYTES + kPrefillMaxPids * sizeof(int);
+  static bool attr_set = false;
+  if (!attr_set) {
+    MC_HIP(hipFuncSetAttribute((const void *)prefill_attention_kernel<HD>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024));
+    attr_set = true;
+  }
+  const unsigned grid = (unsigned)a.n_items * a.n_kv_heads * HG;
+  prefill_attention_kernel<HD><<<grid, 256, lds, st>>>(a);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
+int launch_attention_prefill_mfma(hipStream_t st, const PrefillAttnArgs &a) {
+  if (a.n_items <= 0) return MC_OK;
+  if (!prefill_attention_mfma_supported(a.page_tokens, a.head_dim, a.n_q_heads, a.n_kv_heads))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "prefill attention: shape not covered");
+  return a.head_dim == 128 ? launch_prefill_t<128>(st, a) : launch_prefill_t<64>(st, a);
+}
+
+}  // namespace mc

@@ -203,6 +203,28 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   return launch_attention_decode((hipStream_t)stream, dtype, a);
 }
 
+extern "C" int mc_op_attention_prefill(void *stream, int32_t n_items, const int32_t *items,
+                                       int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                       int32_t page_tokens, int32_t prefix_len, const void *q,
+                                       const void *k_prefix, const void *v_prefix,
+                                       const void *k_suffix, const void *v_suffix,
+                                       const int32_t *page_table, int32_t table_stride, void *out,
+                                       int32_t out_tiled) {
+  if (n_items < 0 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || prefix_len < 1)
+    MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!items || !q || !k_prefix || !v_prefix || !out) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  MC_TRY(check_tiled(MC_BF16, out_tiled, n_q_heads * head_dim));
+  if (!prefill_attention_mfma_supported(page_tokens, head_dim, n_q_heads, n_kv_heads))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "prefill attention: bf16, 64-token pages, head_dim 64 or 128 only");
+  PrefillAttnArgs a;
+  a.q = q; a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.k_suffix = k_suffix; a.v_suffix = v_suffix;
+  a.items = (const int4 *)items; a.n_items = n_items; a.page_table = page_table;
+  a.table_stride = table_stride; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads;
+  a.head_dim = head_dim; a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.out = out;
+  a.out_tiled = out_tiled;
+  return launch_attention_prefill_mfma((hipStream_t)stream, a);
+}
+
 extern "C" int mc_op_sample(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
                             size_t row_stride, float temperature, int32_t top_k,
                             const float *uniforms, int32_t *out_tokens, int32_t *out_topk) {

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "common.h"
+#include "kernels_mfma.h"
 
 namespace mc {
 
@@ -232,7 +233,7 @@ constexpr int kProfCap = 8192;
 struct SessionLayout {
   size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
       hlast, attn_ws, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
-      score_table, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
+      score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
   size_t total;
   // derived sizes
   int rows_cap, n_prefix_pages, n_pool_pages, pages_per_cand, n_score_pages;
@@ -297,6 +298,7 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.last_idx = at((size_t)p.max_cands * 4);
   o.page_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
   o.score_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
+  o.items = at((R / 32 + p.max_cands + 2) * 16);
   o.samp_tok = at((size_t)p.max_cands * 4);
   o.samp_u = at((size_t)p.max_cands * 4);
   o.topk = at((size_t)p.max_cands * MC_MAX_TOP_K * 4);
@@ -406,7 +408,7 @@ enum { PASS_PREFIX = 0, PASS_DECODE = 1, PASS_SCORE = 2 };
 // Run all layers on `rows` rows whose metadata (token, position, KV slot, table row) is on the
 // device already.  prefix_visible: number of prefix keys that exist (for PASS_PREFIX: the end of
 // this chunk).  Leaves the last down-projection's partial sums in `part` (n returned in *tail).
-static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int *tail_splits) {
+static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int n_items, int *tail_splits) {
   const mc_model *m = s->m;
   const mc_config &c = m->cfg;
   const SessionLayout &L = s->lay;
@@ -465,6 +467,18 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       ProfScope ps(s, MC_K_ATTN_DECODE);
       MC_TRY(launch_attention_decode(st, dt, a));
     } else {
+      if (tl && prefill_attention_mfma_supported(s->p.page_tokens, c.head_dim, c.n_q_heads, c.n_kv_heads)) {
+        PrefillAttnArgs pa;
+        pa.q = q; pa.k_prefix = kl; pa.v_prefix = vl; pa.k_suffix = kdst; pa.v_suffix = vdst;
+        pa.items = s->ptr<int4>(L.items); pa.n_items = n_items;
+        pa.page_table = (pass == PASS_SCORE) ? s->ptr<int32_t>(L.score_table) : nullptr;
+        pa.table_stride = L.pages_per_cand;
+        pa.n_q_heads = c.n_q_heads; pa.n_kv_heads = c.n_kv_heads; pa.head_dim = c.head_dim;
+        pa.page_tokens = s->p.page_tokens; pa.prefix_len = prefix_visible; pa.out = ao;
+        pa.out_tiled = tl;
+        ProfScope ps(s, MC_K_ATTN_PREFILL);
+        MC_TRY(launch_attention_prefill_mfma(st, pa));
+      } else {
       AttnArgs a;
       a.q = q; a.k_prefix = kl; a.v_prefix = vl; a.k_suffix = kdst; a.v_suffix = vdst;
       a.row_pos = row_pos; a.row_tab = row_tab;
@@ -475,6 +489,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       a.out = ao; a.out_tiled = tl;
       ProfScope ps(s, MC_K_ATTN_PREFILL);
       MC_TRY(launch_attention_generic(st, dt, a));
+      }
     }
     const int s2 = splits_for(d, qd);
     {
@@ -622,7 +637,7 @@ extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n
   // the old prefix and candidates are gone from here on
   s->prefix_len = 0;
   mc_session_reset_candidates(s);
-  std::vector<int32_t> meta;
+  std::vector<int32_t> meta, items;
   int tail = 0, rows = 0;
   for (int p0 = 0; p0 < n_tokens; p0 += s->chunk_rows) {
     rows = std::min(s->chunk_rows, n_tokens - p0);
@@ -638,7 +653,13 @@ extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n
     MC_TRY(upload(s, s->ptr<void>(L.row_pos), meta.data() + rows, (size_t)rows * 4));
     MC_TRY(upload(s, s->ptr<void>(L.row_page), meta.data() + 2 * rows, (size_t)rows * 4));
     MC_TRY(upload(s, s->ptr<void>(L.row_off), meta.data() + 3 * rows, (size_t)rows * 4));
-    MC_TRY(run_layers(s, rows, PASS_PREFIX, p0 + rows, &tail));
+    // attention work items: 32 consecutive positions each
+    items.clear();
+    for (int r = 0; r < rows; r += 32) {
+      items.push_back(r); items.push_back(std::min(32, rows - r)); items.push_back(p0 + r); items.push_back(-1);
+    }
+    MC_TRY(upload(s, s->ptr<void>(L.items), items.data(), items.size() * 4));
+    MC_TRY(run_layers(s, rows, PASS_PREFIX, p0 + rows, (int)items.size() / 4, &tail));
   }
   // logits of the last position only
   {
@@ -686,7 +707,7 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   int tail = 0;
   const int saved_n = s->n_cands;
   s->n_cands = n_cands;
-  int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, &tail);
+  int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, 0, &tail);
   if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
   if (rc != MC_OK) { s->n_cands = saved_n; return rc; }
   if (t % pg == 0)
@@ -769,7 +790,7 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
   const int pg = s->p.page_tokens;
   MC_TRY(upload(s, s->ptr<void>(L.rw_ids), reward_ids, (size_t)n_reward * 4));
   MC_TRY(upload(s, s->ptr<void>(L.rw_vals), reward_values, (size_t)n_reward * 4));
-  std::vector<int32_t> tok, pos, page, off, tab, last, table;
+  std::vector<int32_t> tok, pos, page, off, tab, last, table, items;
   int b0 = 0;
   while (b0 < n_cands) {
     // a chunk holds whole candidates, at most chunk_rows rows
@@ -780,8 +801,13 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
     last.resize(nc);
     table.assign((size_t)nc * L.pages_per_cand, 0);
     int r = 0, next_page = 0;
+    items.clear();
     for (int b = b0; b < b1; ++b) {
       const int len = suffix_lens[b];
+      for (int j = 0; j < len; j += 32) {
+        items.push_back(r + j); items.push_back(std::min(32, len - j));
+        items.push_back(s->prefix_len + j); items.push_back(b - b0);
+      }
       for (int j = 0; j < len; ++j, ++r) {
         if (j % pg == 0) table[(size_t)(b - b0) * L.pages_per_cand + j / pg] = next_page++;
         tok[r] = suffix_tokens[(size_t)b * max_len + j];
@@ -802,7 +828,8 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
     MC_HIP(hipMemcpyAsync(s->ptr<void>(L.score_table), table.data(), table.size() * 4, hipMemcpyHostToDevice, s->stream));
     MC_HIP(hipStreamSynchronize(s->stream));   // `table` is pageable host memory reused below
     int tail = 0;
-    MC_TRY(run_layers(s, rows, PASS_SCORE, s->prefix_len, &tail));
+    MC_TRY(upload(s, s->ptr<void>(L.items), items.data(), items.size() * 4));
+    MC_TRY(run_layers(s, rows, PASS_SCORE, s->prefix_len, (int)items.size() / 4, &tail));
     MC_TRY(lm_head(s, rows, tail, nc, true, s->ptr<float>(L.logits) + (size_t)b0 * c.vocab));
     b0 = b1;
   }

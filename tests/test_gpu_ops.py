@@ -280,3 +280,67 @@ def test_tiled_outputs_of_rmsnorm_and_attention():
     o_plain = binding.op_attention_decode(qd, kpd, vpd, ksd, vsd, table, P, t, pg)
     o_tiled = binding.op_attention_decode(qd, kpd, vpd, ksd, vsd, table, P, t, pg, out_tiled=True)
     assert torch.equal(binding.tiled_to_rowmajor(o_tiled.cpu(), B, Hq * hd), o_plain.cpu().reshape(B, Hq * hd))
+
+
+# ---------------------------------------------------------------- MFMA prefill / scoring attention
+def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False):
+    """seqs: list of (pos_start, n_rows); pos_start < P means a prefix chunk (keys = prefix
+    only, P grows to cover it), pos_start >= P a scored suffix starting at P."""
+    import torch
+    pg = 64
+    scoring = any(p0 >= P for p0, _ in seqs)
+    n_pre = -(-P // pg)
+    kpd, vpd, kpv, vpv = make_pools("bf16", n_pre, Hkv, pg, hd, seed)
+    per = max(-(-max(n for _, n in seqs) // pg), 1)
+    ksd, vsd, ksv, vsv = make_pools("bf16", len(seqs) * per, Hkv, pg, hd, seed + 2)
+    table = np.random.default_rng(seed).permutation(len(seqs) * per).astype(np.int32).reshape(len(seqs), per)
+    rows = sum(n for _, n in seqs)
+    q = rnd(seed + 4, (rows, Hq, hd)); qd, qv = to_dev(q, "bf16")
+    items, r0 = [], 0
+    for si, (p0, n) in enumerate(seqs):
+        for j in range(0, n, 32):
+            items.append([r0 + j, min(32, n - j), p0 + j, si if scoring else -1])
+        r0 += n
+    it = torch.tensor(items, dtype=torch.int32, device="cuda")
+    print("case: prefill attention", Hq, Hkv, hd, P, seqs, flush=True)
+    out = binding.op_attention_prefill(qd, it, kpd, vpd, ksd if scoring else None, vsd if scoring else None,
+                                       torch.from_numpy(table).cuda() if scoring else None, P, pg, out_tiled)
+    if out_tiled:
+        out = binding.tiled_to_rowmajor(out.cpu(), rows, Hq * hd).reshape(rows, Hq, hd)
+    out = out.float().cpu().numpy()
+    G, worst, r0 = Hq // Hkv, 0.0, 0
+    for si, (p0, n) in enumerate(seqs):
+        for j in range(n):
+            pos = p0 + j
+            for a in range(Hq):
+                if ((r0 + j) * Hq + a) % stride:
+                    continue
+                c = a // G
+                keys = [kpv[:, c].reshape(-1, hd)[:min(P, pos + 1)]]
+                vals = [vpv[:, c].reshape(-1, hd)[:min(P, pos + 1)]]
+                if pos >= P:
+                    keys.append(ksv[table[si], c].reshape(-1, hd)[:pos - P + 1])
+                    vals.append(vsv[table[si], c].reshape(-1, hd)[:pos - P + 1])
+                want = otf.attention_one(qv[r0 + j, a], np.concatenate(keys), np.concatenate(vals))
+                worst = max(worst, np.abs(out[r0 + j, a] - want).max())
+        r0 += n
+    return worst
+
+
+@pytest.mark.parametrize("Hq,Hkv,hd,P,seqs,stride", [
+    (8, 2, 128, 200, [(0, 200)], 1),                       # first prefill chunk, causal from position 0
+    (8, 2, 64, 330, [(130, 200)], 1),                      # later chunk: earlier keys + own diagonal
+    (32, 8, 128, 4096, [(2048, 2048)], 211),               # 8B shape, second half of the 4096 prefix
+    (8, 2, 128, 150, [(150, 70), (150, 33), (150, 1)], 1),  # scoring: ragged suffixes on a shared prefix
+    (40, 8, 128, 1000, [(1000, 100), (1000, 64)], 7),      # 5 query heads per KV head (two head groups)
+    (32, 8, 128, 4096, [(4096, 1024)] * 3, 1531),          # reranking shape: 1024-token suffixes
+    (4, 4, 64, 1, [(1, 65)], 1),
+])
+def test_attention_prefill_mfma(Hq, Hkv, hd, P, seqs, stride):
+    worst = prefill_case(Hq, Hkv, hd, P, seqs, stride)
+    assert worst < 1.5e-2, worst
+
+
+def test_attention_prefill_tiled_output_matches():
+    a = prefill_case(8, 2, 128, 100, [(100, 40), (100, 9)], out_tiled=True)
+    assert a < 1.5e-2, a
