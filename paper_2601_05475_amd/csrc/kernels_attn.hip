@@ -17,6 +17,8 @@
 // O^T += V^T P^T once V's key order follows the accumulator layout (see kmap below).
 #include "kernels_mfma.h"
 
+#include <stdlib.h>
+
 #include <algorithm>
 
 namespace mc {
@@ -53,17 +55,20 @@ template <int HD> struct AttnTile {
   static constexpr int CPT = CHUNKS / 256;              // chunks per thread per page per tensor
 };
 
+constexpr int kStages = 1;                   // register stages of the page pipeline
+constexpr int kMaxSuffixSplits = 8;
 constexpr int kMaxPids = 512;                // suffix page ids kept in LDS (longer suffixes read them from memory)
 
 struct AttnItems {
   int n_prefix_items, n_suffix_items;
   int splits, row_blocks, pages_per_split;   // prefix
+  int suffix_splits, suffix_pps;             // suffix: key splits per (candidate, kv head), pages per split
   int n_prefix_pages, rows;                  // rows = B * G
   int pid_offset;                            // byte offset of the page-id array in LDS
 };
 
 template <int HD>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(256, 2)
 void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
                                                                float *__restrict__ part_o,
                                                                float *__restrict__ part_ml) {
@@ -94,13 +99,14 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
     b_of_col = col_valid ? rho / G : 0;
     g_of_col = col_valid ? rho % G : 0;
   } else {
-    const int id = blockIdx.x - it.n_prefix_items;
+    int id = blockIdx.x - it.n_prefix_items;
+    const int ss = id % it.suffix_splits; id /= it.suffix_splits;
     kvh = id % Hkv;
     const int b = id / Hkv;
-    part = (a.prefix_len > 0) ? it.splits : 0;
-    first_page = 0;
-    n_pages = (a.suffix_len + PG - 1) / PG;
-    n_keys = a.suffix_len;
+    part = ((a.prefix_len > 0) ? it.splits : 0) + ss;
+    first_page = ss * it.suffix_pps;
+    n_pages = min(it.suffix_pps, (a.suffix_len + PG - 1) / PG - first_page);
+    n_keys = min(a.suffix_len - first_page * PG, n_pages * PG);
     kpool = (const bf16_t *)a.k_suffix; vpool = (const bf16_t *)a.v_suffix;
     table = a.page_table + (size_t)b * a.table_stride;
     col_valid = col < G;
@@ -128,18 +134,20 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
   // ---- staging: thread t carries chunks t + 256 i of the K and of the V page in flight
   const size_t page_stride = (size_t)Hkv * PG * HD;           // elements per page (all kv heads)
   const size_t head_off = (size_t)kvh * PG * HD;
-  // three register stages: pages i + 1, i + 2, i + 3 are in flight while page i is consumed
-  v4u sk[3][TL::CPT], sv[3][TL::CPT];
+  // kStages register stages: that many pages are in flight while one is consumed.  Two stages
+  // keep the kernel within 256 registers, so two workgroups share a CU and overlap each other's
+  // load, softmax and MFMA phases.
+  v4u sk[kStages][TL::CPT], sv[kStages][TL::CPT];
   // A suffix item's page ids are copied to LDS once: fetching one from global memory inside the
   // loop would put a full memory round trip in front of every prefetch.
   int *pids = (int *)(lds_raw + it.pid_offset);
   const bool pids_in_lds = table != nullptr && n_pages <= kMaxPids;
   if (pids_in_lds) {
-    for (int i = tid; i < n_pages; i += 256) pids[i] = table[i];
+    for (int i = tid; i < n_pages; i += 256) pids[i] = table[first_page + i];
     __syncthreads();
   }
   auto page_id = [&](int pi) __attribute__((always_inline)) -> int {
-    return table ? (pids_in_lds ? pids[pi] : table[pi]) : pi;
+    return table ? (pids_in_lds ? pids[pi - first_page] : table[pi]) : pi;
   };
   // Every call issues the same number of loads, whether or not page pi exists: past the end all
   // lanes re-read one 16-byte piece of the item's first page (the data is never used).  With no
@@ -233,7 +241,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
     const int buf = i & 1;
     const int key0 = i * PG;         // first key of this page, relative to the item's first page
     if (is_prefix) {
-#pragma unroll
+#pragma unroll 1
       for (int blk = 0; blk < 2; ++blk) {
         const int nv = min(32, n_keys - (key0 + 32 * blk));
         if (nv > 0) process(buf, blk, nv);
@@ -248,14 +256,14 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it,
   // arrives at the barrier of page pi - 1.  Stages past the last page run as no-ops on dummy
   // data (n_pages >= 1 for every item).
 #pragma unroll
-  for (int st = 0; st < 3; ++st) issue(st, st);
-  for (int i = 0; i < n_pages; i += 3) {
+  for (int st = 0; st < kStages; ++st) issue(st, st);
+  for (int i = 0; i < n_pages; i += kStages) {
 #pragma unroll
-    for (int st = 0; st < 3; ++st) {
+    for (int st = 0; st < kStages; ++st) {
       const int pi = i + st;
       commit(st, pi & 1);
       __syncthreads();
-      issue(st, pi + 3);
+      issue(st, pi + kStages);
       if (pi < n_pages) consume(pi);
     }
   }
@@ -383,7 +391,27 @@ static AttnItems plan_items(const DecodeAttnArgs &a) {
   }
   it.splits = splits;
   it.n_prefix_items = a.n_kv_heads * splits * it.row_blocks;
-  it.n_suffix_items = (a.suffix_len > 0) ? a.n_cands * a.n_kv_heads : 0;
+  // suffix: split a candidate's pages when that fills idle workgroup slots (two per CU); the
+  // partial state of a suffix item is small (G rows), so splitting costs little
+  const int s_pages = (a.suffix_len + PG - 1) / PG;
+  int ssplits = 1;
+  if (s_pages > 0) {
+    const char *env = getenv("MC_ATTN_SUFFIX_SPLITS");         // measurement override
+    if (env && atoi(env) > 0) ssplits = atoi(env);
+    else {
+      const int base_items = a.n_cands * a.n_kv_heads;
+      while (ssplits < kMaxSuffixSplits && base_items * ssplits * 2 + it.n_prefix_items <= 640 &&
+             (s_pages + ssplits * 2 - 1) / (ssplits * 2) >= 2)
+        ssplits *= 2;
+    }
+    ssplits = std::max(1, std::min(std::min(ssplits, kMaxSuffixSplits), s_pages));
+    it.suffix_pps = (s_pages + ssplits - 1) / ssplits;
+    ssplits = (s_pages + it.suffix_pps - 1) / it.suffix_pps;
+  } else {
+    it.suffix_pps = 0;
+  }
+  it.suffix_splits = ssplits;
+  it.n_suffix_items = (a.suffix_len > 0) ? a.n_cands * a.n_kv_heads * ssplits : 0;
   return it;
 }
 
@@ -399,14 +427,14 @@ size_t decode_attention_mfma_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int 
   (void)Hkv; (void)suffix_len;
   if (page_tokens != PG) return 0;
   const int pairs = ((prefix_len + PG - 1) / PG + 1) / 2;
-  const size_t parts = (size_t)pairs + 1;
+  const size_t parts = (size_t)pairs + kMaxSuffixSplits;
   return parts * n_cands * Hq * (size_t)(hd + 2) * sizeof(float) + 512;
 }
 
 template <int HD>
 static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, const AttnItems &it_in) {
   using TL = AttnTile<HD>;
-  const int n_parts = (a.prefix_len > 0 ? it_in.splits : 0) + (a.suffix_len > 0 ? 1 : 0);
+  const int n_parts = (a.prefix_len > 0 ? it_in.splits : 0) + (a.suffix_len > 0 ? it_in.suffix_splits : 0);
   const size_t rows = (size_t)a.n_cands * a.n_q_heads;
   const size_t need = (size_t)n_parts * rows * (HD + 2) * sizeof(float);
   if (a.workspace_bytes < need) MC_FAIL(MC_ERR_INVALID, "attention workspace has %zu bytes, %zu needed", a.workspace_bytes, need);
