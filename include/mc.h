@@ -220,8 +220,16 @@ int mc_op_linear_swiglu(void *stream, int32_t dtype, int32_t M, int32_t N, int32
 
 /* Sum the n_splits partial QKV rows, rotate q and k of row r by position row_pos[r],
  * store q as (T)[rows][Hq][hd] and write k, v of row r into KV page row_page[r] at
- * offset row_off[r].  K pages are (T)[Hkv][page_tokens][hd]; V pages are stored
- * transposed, (T)[Hkv][hd][page_tokens].  qkv: fp32 [n_splits][rows][(Hq+2Hkv)*hd]. */
+ * offset row_off[r].  qkv: fp32 [n_splits][rows][(Hq+2Hkv)*hd].
+ *
+ * KV page layout (all attention entry points read what this one writes).  A K page and a V
+ * page each hold Hkv regions of page_tokens * hd elements, one per KV head.  If page_tokens
+ * or hd is not a multiple of 32 a region is plain: K as [key][hd], V transposed as [hd][key].
+ * Otherwise it is a sequence of 32-key blocks of 32 * hd elements, each block a run of
+ * 1 KB fragments in the order one 32x32x16 MFMA reads its A operand; fragment f keeps, for
+ * lane l = 0..63, eight elements at (f * 64 + l) * 8:
+ *   K fragment c:          key l % 32, coordinates 16c + 8 (l / 32) + 0..7;
+ *   V fragment 2 dt + sl:  coordinate 32 dt + l % 32, keys 16 sl + 4 (l / 32) + {0,1,2,3,8,9,10,11}. */
 int mc_op_rope_kv_write(void *stream, int32_t dtype, int32_t rows, int32_t n_q_heads,
                         int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens,
                         float rope_base, const float *qkv, int32_t n_splits,

@@ -320,6 +320,49 @@ def tiled_to_rowmajor(flat, rows: int, K: int):
     return v.permute(0, 4, 1, 3, 2, 5).reshape(rp, K)[:rows]
 
 
+def kv_page_offsets(page_tokens: int, head_dim: int):
+    """Element offsets (k_off[key, d], v_off[key, d]) inside one KV head's region of a page, as
+    the library lays pages out: plain ([key][hd] and [hd][key]) unless both sizes are multiples
+    of 32, then blocks of 32 keys in the order the 32x32x16 MFMA reads its A operand."""
+    pg, hd = page_tokens, head_dim
+    key = np.arange(pg, dtype=np.int64)[:, None]
+    d = np.arange(hd, dtype=np.int64)[None, :]
+    if pg % 32 or hd % 32:
+        return key * hd + d, d * pg + key
+    blk = (key >> 5) * 32 * hd
+    k_off = blk + ((d >> 4) * 64 + (key & 31) + 32 * ((d >> 3) & 1)) * 8 + (d & 7)
+    k16, sl = key & 15, (key >> 4) & 1
+    v_off = blk + (((d >> 5) * 2 + sl) * 64 + (d & 31) + 32 * ((k16 >> 2) & 1)) * 8 + 4 * (k16 >> 3) + (k16 & 3)
+    return k_off, v_off
+
+
+def kv_pages_pack(k, v):
+    """k, v: [n_pages, Hkv, pg, hd] tensors -> (K pool, V pool) in the library's page layout,
+    each [n_pages, Hkv, pg * hd] (torch indexing only)."""
+    import torch
+    n, Hkv, pg, hd = k.shape
+    k_off, v_off = kv_page_offsets(pg, hd)
+    ko = torch.from_numpy(k_off.reshape(-1)).to(k.device)
+    vo = torch.from_numpy(v_off.reshape(-1)).to(k.device)
+    kp = torch.empty((n, Hkv, pg * hd), dtype=k.dtype, device=k.device)
+    vp = torch.empty_like(kp)
+    kp[:, :, ko] = k.reshape(n, Hkv, pg * hd)
+    vp[:, :, vo] = v.reshape(n, Hkv, pg * hd)
+    return kp, vp
+
+
+def kv_pages_unpack(kp, vp, page_tokens: int, head_dim: int):
+    """Inverse of kv_pages_pack: pools -> (k, v), each [n_pages, Hkv, pg, hd]."""
+    import torch
+    n, Hkv = kp.shape[0], kp.shape[1]
+    k_off, v_off = kv_page_offsets(page_tokens, head_dim)
+    ko = torch.from_numpy(k_off.reshape(-1)).to(kp.device)
+    vo = torch.from_numpy(v_off.reshape(-1)).to(kp.device)
+    k = kp.reshape(n, Hkv, -1)[:, :, ko].reshape(n, Hkv, page_tokens, head_dim)
+    v = vp.reshape(n, Hkv, -1)[:, :, vo].reshape(n, Hkv, page_tokens, head_dim)
+    return k, v
+
+
 def op_add_rmsnorm(x, partials, gain, eps: float, tiled: bool = False):
     """x: fp32 [rows, d] (updated in place); partials: fp32 [S, rows, d] or None.  Returns h
     ([rows, d], or the flat tiled buffer when tiled)."""
@@ -386,7 +429,7 @@ def op_rope_kv_write(qkv, row_pos, row_page, row_off, n_q_heads, n_kv_heads, hea
 
 def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, prefix_len,
                         suffix_len, page_tokens, prefix_splits: int = 0, out_tiled: bool = False):
-    """q: [B, Hq, hd]; pools: [n_pages, Hkv, pg, hd] (K) and [n_pages, Hkv, hd, pg] (V);
+    """q: [B, Hq, hd]; pools: [n_pages, Hkv, pg * hd] in the page layout (kv_pages_pack);
     page_table: int32 [B, stride].  Returns out [B, Hq, hd] (or the flat tiled [B, Hq*hd])."""
     import torch
     lib = load_library()

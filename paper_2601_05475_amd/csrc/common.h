@@ -56,10 +56,36 @@ void set_error(const char *fmt, ...);
   } while (0)
 
 // ---- geometry of one KV page ---------------------------------------------------------
-// K page: [Hkv][page_tokens][hd]; V page: [Hkv][hd][page_tokens] (transposed so that the
-// probability-times-value contraction reads keys contiguously).  Both have this many elements.
+// A page holds page_tokens keys of every KV head; head kvh owns elements
+// [kvh * page_tokens * hd, (kvh + 1) * page_tokens * hd) of the K page and of the V page.
 inline size_t page_elems(int n_kv_heads, int head_dim, int page_tokens) {
   return (size_t)n_kv_heads * head_dim * page_tokens;
+}
+// Inside a head's region there are two layouts.
+//   plain (page_tokens % 32 != 0 or hd % 32 != 0): K as [key][hd], V transposed as [hd][key].
+//   fragment order (otherwise): blocks of 32 keys, 32 * hd elements each.  A block is a run of
+//     1 KB fragments, fragment f holding for lane l = 0..63 eight consecutive elements at
+//     (f * 64 + l) * 8, exactly what one 32x32x16 MFMA reads as its A operand:
+//       K fragment c (d = 16c..16c+15): lane l has key l % 32, d = 16c + 8 (l / 32) + 0..7;
+//       V fragment 2 dt + sl: lane l has d = 32 dt + l % 32 and the eight keys
+//         16 sl + 4 (l / 32) + {0,1,2,3, 8,9,10,11}, the order in which the transposed score
+//         accumulator of the same MFMA holds its keys.
+//     A wave then loads an operand with one fully coalesced 16-byte-per-lane instruction.
+__host__ __device__ inline bool kv_fragment_layout(int page_tokens, int hd) {
+  return page_tokens % 32 == 0 && hd % 32 == 0;
+}
+// element offset of K[key][d] / V[key][d] inside one head's region of a page
+__host__ __device__ inline size_t k_elem_offset(int key, int d, int page_tokens, int hd) {
+  if (!kv_fragment_layout(page_tokens, hd)) return (size_t)key * hd + d;
+  const int lane = (key & 31) + 32 * ((d >> 3) & 1);
+  return (size_t)(key >> 5) * 32 * hd + (size_t)((d >> 4) * 64 + lane) * 8 + (d & 7);
+}
+__host__ __device__ inline size_t v_elem_offset(int key, int d, int page_tokens, int hd) {
+  if (!kv_fragment_layout(page_tokens, hd)) return (size_t)d * page_tokens + key;
+  const int k16 = key & 15, sl = (key >> 4) & 1;
+  const int lane = (d & 31) + 32 * ((k16 >> 2) & 1);
+  const int j = 4 * (k16 >> 3) + (k16 & 3);
+  return (size_t)(key >> 5) * 32 * hd + (size_t)(((d >> 5) * 2 + sl) * 64 + lane) * 8 + j;
 }
 
 // ---- tiled operand layout of the bf16 MFMA kernels --------------------------------------

@@ -292,12 +292,10 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(
   const size_t pelems = (size_t)Hkv * hd * pg;
   if (h < Hq + Hkv) {
     const double pos = (double)row_pos[r];
-    T *dst;
-    if (h < Hq) {
-      dst = q_out + ((size_t)r * Hq + h) * hd;
-    } else {
-      dst = k_pages + (size_t)row_page[r] * pelems + ((size_t)(h - Hq) * pg + row_off[r]) * hd;
-    }
+    // queries go out row-major; a key goes to its slot of the page, in the page's layout
+    T *dst = (h < Hq) ? q_out + ((size_t)r * Hq + h) * hd
+                      : k_pages + (size_t)row_page[r] * pelems + (size_t)(h - Hq) * pg * hd;
+    const int key = row_off[r];
     for (int i = threadIdx.x; i < half; i += 64) {
       float lo = 0.f, hi = 0.f;
       for (int s = 0; s < n_splits; ++s) {
@@ -306,16 +304,19 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(
       }
       double sn, cs;
       sincos(pos * pow(rope_base, -2.0 * (double)i / (double)hd), &sn, &cs);
-      dst[i] = Cvt<T>::from_f32((float)((double)lo * cs - (double)hi * sn));
-      dst[i + half] = Cvt<T>::from_f32((float)((double)hi * cs + (double)lo * sn));
+      const size_t at_lo = (h < Hq) ? (size_t)i : k_elem_offset(key, i, pg, hd);
+      const size_t at_hi = (h < Hq) ? (size_t)(i + half) : k_elem_offset(key, i + half, pg, hd);
+      dst[at_lo] = Cvt<T>::from_f32((float)((double)lo * cs - (double)hi * sn));
+      dst[at_hi] = Cvt<T>::from_f32((float)((double)hi * cs + (double)lo * sn));
     }
   } else {
     const int kvh = h - Hq - Hkv;
-    T *dst = v_pages + (size_t)row_page[r] * pelems + (size_t)kvh * hd * pg + row_off[r];
+    T *dst = v_pages + (size_t)row_page[r] * pelems + (size_t)kvh * hd * pg;
+    const int key = row_off[r];
     for (int i = threadIdx.x; i < hd; i += 64) {
       float v = 0.f;
       for (int s = 0; s < n_splits; ++s) v += src[s * sstride + i];
-      dst[(size_t)i * pg] = Cvt<T>::from_f32(v);
+      dst[v_elem_offset(key, i, pg, hd)] = Cvt<T>::from_f32(v);
     }
   }
 }
@@ -381,9 +382,18 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(AttnArgs a) {
         in_prefix = false;
       }
       base = (long long)((size_t)page * pelems + (size_t)kvh * hd * pg);
-      const T *kp = (const T *)(in_prefix ? a.k_prefix : a.k_suffix) + base + (size_t)off * hd;
+      const T *kp = (const T *)(in_prefix ? a.k_prefix : a.k_suffix) + base;
       float dot = 0.f;
-      for (int i = 0; i < hd; ++i) dot += qs[i] * Cvt<T>::to_f32(kp[i]);
+      if (kv_fragment_layout(pg, hd)) {
+        for (int i = 0; i < hd; i += 8) {
+          const T *k8 = kp + k_elem_offset(off, i, pg, hd);      // 8 consecutive d are contiguous
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dot += qs[i + j] * Cvt<T>::to_f32(k8[j]);
+        }
+      } else {
+        kp += (size_t)off * hd;
+        for (int i = 0; i < hd; ++i) dot += qs[i] * Cvt<T>::to_f32(kp[i]);
+      }
       s = dot * scale;
     }
     // bit 62 marks "suffix pool" so that the value pass picks the right pool
@@ -405,7 +415,7 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(AttnArgs a) {
         for (int t = 0; t < nblk; ++t) {
           const long long kb = kbase[t];
           const T *vp = (const T *)((kb >> 62) & 1 ? a.v_suffix : a.v_prefix) +
-                        (kb & ~(1ll << 62)) + (size_t)d * pg + koff[t];
+                        (kb & ~(1ll << 62)) + v_elem_offset(koff[t], d, pg, hd);
           acc += ps[t] * Cvt<T>::to_f32(*vp);
         }
         o[c] = acc;

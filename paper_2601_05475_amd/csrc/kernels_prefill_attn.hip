@@ -4,10 +4,11 @@
 // query heads: wave w owns head 4 * hg + w of the group, the 32 positions are its MFMA columns.
 // Keys are streamed page by page (64 keys) through LDS and shared by the four waves: first the
 // shared-prefix pages that are visible to the block, then (scoring) the sequence's own suffix
-// pages.  Each item sees all keys of its rows, so it normalises and writes bf16 itself.
-// Tile layout, operand mapping and the softmax scheme are those of the decode kernel
-// (transposed scores, lazy base-2 reference maximum); the addition is the causal mask, applied
-// only to blocks that reach past the first position of the item.
+// pages.  Pages are stored in MFMA fragment order, so a page is copied to LDS as it is and an
+// operand is one conflict-free 16-byte read per lane.  Each item sees all keys of its rows, so
+// it normalises and writes bf16 itself.  Operand mapping and the softmax scheme are those of
+// the decode kernel (transposed scores, lazy base-2 reference maximum); the addition is the
+// causal mask, applied only to blocks that reach past the first position of the item.
 #include "kernels_mfma.h"
 
 #include <algorithm>
@@ -32,8 +33,8 @@ __device__ inline uint32_t pack2p_bf16(float a, float b) {
 constexpr int PPG = 64;                       // keys per page
 
 template <int HD> struct PTile {
-  static constexpr int KLD = HD + 8, VLD = PPG + 8;
-  static constexpr int K_ELEMS = PPG * KLD, V_ELEMS = HD * VLD, PAGE_ELEMS = K_ELEMS + V_ELEMS;
+  static constexpr int K_ELEMS = PPG * HD, V_ELEMS = PPG * HD, PAGE_ELEMS = K_ELEMS + V_ELEMS;
+  static constexpr int NF = HD / 16;          // 1 KB fragments per 32-key block (K and V alike)
   static constexpr int LDS_BYTES = 2 * PAGE_ELEMS * 2;
   static constexpr int CPT = PPG * HD / 8 / 256;
 };
@@ -111,20 +112,20 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
 #pragma unroll
     for (int i = 0; i < TL::CPT; ++i) {
       const int ci = tid + 256 * i;
-      *(v4u *)(kt + (ci / (HD / 8)) * TL::KLD + (ci % (HD / 8)) * 8) = sk[stage][i];
-      *(v4u *)(vt + (ci / (PPG / 8)) * TL::VLD + (ci % (PPG / 8)) * 8) = sv[stage][i];
+      *(v4u *)(kt + ci * 8) = sk[stage][i];
+      *(v4u *)(vt + ci * 8) = sv[stage][i];
     }
   };
   // one 32-key block whose key 0 sits at absolute position abs0; n_valid keys exist
   auto process = [&](int buf, int blk, int n_valid, int abs0) __attribute__((always_inline)) {
     const bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
-    const int kb = blk * 32;
+    const bf16_t *kblk = kt + (blk * TL::NF * 64 + lane) * 8, *vblk = vt + (blk * TL::NF * 64 + lane) * 8;
     f32x16 s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int c = 0; c < HD / 16; ++c) {
-      const v4u kf = *(const v4u *)(kt + (kb + col) * TL::KLD + 16 * c + 8 * h);
+      const v4u kf = *(const v4u *)(kblk + c * 512);
       s = mfma32p(kf, qf[c], s);
     }
     // key of register r: 8 (r / 4) + 4 h + r % 4; it is masked if it does not exist or lies
@@ -168,9 +169,8 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
     for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
       for (int sl = 0; sl < 2; ++sl) {
-        const bf16_t *vrow = vt + (dt * 32 + col) * TL::VLD + kb + 16 * sl + 4 * h;
-        const v2u lo = *(const v2u *)vrow, hi = *(const v2u *)(vrow + 8);
-        o[dt] = mfma32p(v4u{lo.x, lo.y, hi.x, hi.y}, pb[sl], o[dt]);
+        const v4u vf = *(const v4u *)(vblk + (dt * 2 + sl) * 512);
+        o[dt] = mfma32p(vf, pb[sl], o[dt]);
       }
   };
   auto consume = [&](int pi) __attribute__((always_inline)) {

@@ -68,26 +68,27 @@ def test_linear_swiglu(dtype, M, N, K):
 
 
 def make_pools(dtype, n_pages, Hkv, pg, hd, seed):
-    """Random K / V page pools in the library's layout; returns device tensors and fp32 views
-    k[page, kvh, j, :], v[page, kvh, j, :] (v un-transposed for the oracle)."""
+    """Random K / V page pools in the library's page layout; returns device tensors and fp32
+    views k[page, kvh, j, :], v[page, kvh, j, :] for the oracle."""
     k = rnd(seed, (n_pages, Hkv, pg, hd)); v = rnd(seed + 1, (n_pages, Hkv, pg, hd))
     kd, kv = to_dev(k, dtype)
-    vd, vv = to_dev(np.ascontiguousarray(v.transpose(0, 1, 3, 2)), dtype)
-    return kd, vd, kv, vv.transpose(0, 1, 3, 2)
+    vd, vv = to_dev(v, dtype)
+    kp, vp = binding.kv_pages_pack(kd, vd)
+    return kp, vp, kv, vv
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_rope_kv_write(dtype):
+@pytest.mark.parametrize("dtype,pg", [("f32", 8), ("bf16", 8), ("f32", 32), ("bf16", 64)])
+def test_rope_kv_write(dtype, pg):
     import torch
-    rows, Hq, Hkv, hd, pg, S, base = 7, 4, 2, 64, 8, 2, 10000.0
+    rows, Hq, Hkv, hd, S, base = 7, 4, 2, 64, 2, 10000.0
     nq = (Hq + 2 * Hkv) * hd
     qkv = rnd(10, (S, rows, nq))
     pos = np.array([0, 1, 5, 130, 4095, 17000, 3], np.int32)
     page = np.array([3, 0, 2, 2, 1, 4, 0], np.int32)
     off = np.array([0, 7, 1, 2, 5, 6, 3], np.int32)
     tdt = torch.float32 if dtype == "f32" else torch.bfloat16
-    kp = torch.zeros((5, Hkv, pg, hd), dtype=tdt, device="cuda")
-    vp = torch.zeros((5, Hkv, hd, pg), dtype=tdt, device="cuda")
+    kp = torch.zeros((5, Hkv, pg * hd), dtype=tdt, device="cuda")
+    vp = torch.zeros((5, Hkv, pg * hd), dtype=tdt, device="cuda")
     q = binding.op_rope_kv_write(torch.from_numpy(qkv).cuda(), torch.from_numpy(pos).cuda(),
                                  torch.from_numpy(page).cuda(), torch.from_numpy(off).cuda(),
                                  Hq, Hkv, hd, pg, base, kp, vp)
@@ -97,10 +98,11 @@ def test_rope_kv_write(dtype):
     wv = full[:, Hq + Hkv:]
     tol = 1e-5 if dtype == "f32" else 2e-2
     np.testing.assert_allclose(q.float().cpu().numpy(), wq, rtol=0, atol=tol)
-    kh, vh = kp.float().cpu().numpy(), vp.float().cpu().numpy()
+    ku, vu = binding.kv_pages_unpack(kp, vp, pg, hd)
+    kh, vh = ku.float().cpu().numpy(), vu.float().cpu().numpy()
     for r in range(rows):
         np.testing.assert_allclose(kh[page[r], :, off[r], :], wk[r], rtol=0, atol=tol)
-        np.testing.assert_allclose(vh[page[r], :, :, off[r]], wv[r], rtol=0, atol=tol)
+        np.testing.assert_allclose(vh[page[r], :, off[r], :], wv[r], rtol=0, atol=tol)
     written = np.zeros((5, pg), bool); written[page, off] = True
     assert np.all(kh[~written[:, None, :, None].repeat(Hkv, 1).repeat(hd, 3)] == 0)
 
