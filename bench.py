@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--workload", default="8b", choices=["8b", "1b"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (diagnosis only; marks the line invalid)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain elementwise copy of 256 MiB (a kernel of known traffic "
+                         "that hardware-counter readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
@@ -131,6 +134,12 @@ def main():
     run_steps(W)
     sess.sync()
     sess.reset_candidates()
+    if args.calibration_copy:
+        src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")      # 256 MiB read, 256 MiB written
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # timed region; every 4th gate/up launch is bracketed by HIP events on the session stream
     stride = max(1, (s.n_layers * K + 8191) // 8192)

@@ -18,6 +18,12 @@ bool gemm_supported(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                      const void *w2, float *out, void *out_t);
 
+// The same for shapes that fill 256-row tiles (N % 256 == 0, or N % 128 == 0 in the SwiGLU form):
+// 256 x 256 output tile per workgroup, double-buffered LDS, XCD-aware tile order.
+bool gemm256_supported(int M, int N, int K, bool swiglu);
+int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const void *w,
+                   const void *w2, float *out, void *out_t);
+
 // Causal attention over many rows.  items[i] = (first row, rows <= 32, position of the first
 // row, page-table row or -1): 32 consecutive positions of one sequence.  Keys at positions
 // < prefix_len come from the prefix pages, later ones from the sequence's suffix pages.

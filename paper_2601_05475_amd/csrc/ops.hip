@@ -21,6 +21,14 @@ bool tiled_shapes_ok(int M, int N, int K) {
   return N % 128 == 0 && K % 256 == 0;
 }
 
+// The 256-row-tile GEMM pays off once its tiles cover most of the 256 CUs; smaller products
+// keep the 128-row-tile kernel, which has four times as many workgroups.
+static bool use_gemm256(int M, int N, int K, bool swiglu) {
+  if (!gemm256_supported(M, N, K, swiglu)) return false;
+  const long tiles = (long)((M + 255) / 256) * (N / (swiglu ? 128 : 256));
+  return tiles >= 192;
+}
+
 int linear_auto_splits(int dtype, int M, int N, int K, int tiled) {
   if (tiled) return (dtype == MC_BF16 && M <= 64) ? skinny_linear_splits(M, N, K) : 1;
   if (M > 64) return 1;
@@ -38,6 +46,7 @@ int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a,
     MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
   if (M <= 64) return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits);
   if (n_splits != 1) MC_FAIL(MC_ERR_UNSUPPORTED, "the many-row GEMM does not split K");
+  if (use_gemm256(M, N, K, false)) return launch_gemm256(st, M, N, K, a, w, nullptr, out, nullptr);
   return launch_gemm_mfma(st, M, N, K, a, w, nullptr, out, nullptr);
 }
 
@@ -47,6 +56,7 @@ int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const v
   if (dtype != MC_BF16 || !tiled_shapes_ok(M, N, K))
     MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
   if (M <= 64) return launch_linear_skinny(st, M, N, K, a, wg, wu, nullptr, out, 1);
+  if (use_gemm256(M, N, K, true)) return launch_gemm256(st, M, N, K, a, wg, wu, nullptr, out);
   return launch_gemm_mfma(st, M, N, K, a, wg, wu, nullptr, out);
 }
 

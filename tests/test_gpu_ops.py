@@ -240,6 +240,8 @@ def test_pack_tiled_roundtrip():
     (32, 256, 512, 1), (32, 256, 512, 2), (16, 3072, 2048, 0), (1, 128, 256, 1), (33, 128, 1024, 2),
     (64, 384, 768, 1), (5, 6144, 4096, 0), (32, 4096, 14336, 0),
     (65, 128, 256, 1), (200, 256, 512, 1), (130, 384, 1024, 1), (4096, 128, 256, 1),
+    # 256-row-tile GEMM: ragged last row tile, a last band of fewer than 8 row tiles, padding ids
+    (3000, 4096, 256, 1), (2300, 5632, 512, 1),
 ])
 def test_linear_tiled(M, N, K, S):
     a = rnd(60, (M, K)); w = rnd(61, (N, K), 0.05)
@@ -253,7 +255,8 @@ def test_linear_tiled(M, N, K, S):
     np.testing.assert_allclose(out, want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
 
 
-@pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512)])
+@pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512),
+                                   (3000, 2048, 512), (2070, 2944, 256)])
 def test_linear_swiglu_tiled(M, N, K):
     a = rnd(62, (M, K)); wg = rnd(63, (N, K), 0.05); wu = rnd(64, (N, K), 0.05)
     ad, av = to_dev(a, "bf16"); gd, gv = to_dev(wg, "bf16"); ud, uv = to_dev(wu, "bf16")
