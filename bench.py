@@ -28,6 +28,31 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 
 
+# HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
+# dispatch, scaled by what the same counters read for a plain copy of known size; see
+# profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
+TRAFFIC_GATE_UP = {"fetch_kib": 115741.7, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+                   "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
+                   "sha256": "df563474358ed6287cd7a9963434fede956b4b7c1d55239e9f2879309d19b580"}
+
+
+def measured_traffic_bytes(workload):
+    """Counter-derived HBM bytes per gate/up launch, or None if the kernel source has changed
+    since the counters were taken (or the workload is not the one they were taken on)."""
+    import hashlib
+    if workload != "8b":
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), TRAFFIC_GATE_UP["source"])
+    try:
+        with open(path, "rb") as f:
+            if hashlib.sha256(f.read()).hexdigest() != TRAFFIC_GATE_UP["sha256"]:
+                return None
+    except OSError:
+        return None
+    t = TRAFFIC_GATE_UP
+    return (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0
+
+
 def gate_up_bytes(s, n_cands):
     """Algorithmic bytes of one gate/up launch: both weight matrices once, the activations in
     and the SwiGLU product out (bf16)."""
@@ -173,7 +198,8 @@ def main():
                    "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens},
         "roofline": {"bound": "hbm", "kernel": "skinny_linear_kernel (gate/up + SwiGLU)",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "launches_timed": n_gu, "avg_us": gu_us},
+                     "traffic": measured_traffic_bytes(args.workload), "algorithmic_bytes": gate_up_bytes(s, B),
+                     "launches_timed": n_gu, "avg_us": gu_us},
         "roofline_attn": {"bound": "hbm", "kernel": "decode attention (all launches of one layer-step)",
                           "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
                           "traffic": None, "launches_timed": n_at, "avg_us": at_us},
