@@ -475,9 +475,79 @@ __device__ inline unsigned long long block_max_u64(unsigned long long v, unsigne
   return t;
 }
 
-// One block of 1024 threads per candidate.  Exact top-k by radix selection on the 64-bit key
-// (11/11/10-bit digits), a bitonic sort of the k survivors in LDS, then the softmax and the
+__device__ inline unsigned int block_reduce_u32(unsigned int v, bool take_max, unsigned int *scratch) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned int t = __shfl_xor(v, o, 64);
+    v = take_max ? max(v, t) : min(v, t);
+  }
+  __syncthreads();
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  unsigned int t = scratch[0];
+  for (int w = 1; w < nw; ++w) t = take_max ? max(t, scratch[w]) : min(t, scratch[w]);
+  return t;
+}
+
+// Slot in a shared list for every lane with `want` set: one atomic per wave, not per lane.
+__device__ inline unsigned int wave_claim(bool want, unsigned int *counter) {
+  const unsigned long long m = __ballot(want);
+  if (m == 0) return 0;
+  const int leader = __ffsll((long long)m) - 1;
+  unsigned int base = 0;
+  if ((int)(threadIdx.x & 63) == leader) base = atomicAdd(counter, (unsigned int)__popcll(m));
+  base = __shfl(base, leader, 64);
+  return base + (unsigned int)__popcll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
+}
+
+// Walk one row with all 1024 threads: f(valid, logit, index) is called the same number of times
+// by every thread (so f may use wave-wide operations).  Loads go out in batches of eight 16-byte
+// vectors per thread; a loop of single dependent-looking loads would pay the memory latency
+// once per element.
+template <typename F>
+__device__ inline void scan_row(const float *row, int V, F f) {
+  constexpr int NB = 8;
+  const int tid = threadIdx.x;
+  const int V4 = (((uintptr_t)row & 15) == 0) ? V / 4 : 0;
+  const float4 *row4 = (const float4 *)row;
+  for (int g0 = 0; g0 < V4; g0 += NB * 1024) {
+    float4 z[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int g = g0 + j * 1024 + tid;
+      z[j] = (g < V4) ? row4[g] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int g = g0 + j * 1024 + tid;
+      const bool ok = g < V4;
+      f(ok, z[j].x, 4 * g);
+      f(ok, z[j].y, 4 * g + 1);
+      f(ok, z[j].z, 4 * g + 2);
+      f(ok, z[j].w, 4 * g + 3);
+    }
+  }
+  for (int v0 = 4 * V4; v0 < V; v0 += 1024) {
+    const int v = v0 + tid;
+    const bool ok = v < V;
+    f(ok, ok ? row[v] : 0.f, v);
+  }
+}
+
+// One block of 1024 threads per candidate: exact top-k of z / T under the order (value
+// descending, id ascending), a bitonic sort of the survivors in LDS, then the softmax and the
 // cumulative walk done left to right by one thread, as the rule demands.
+//
+// Selection, fast path (k <= 1024, V >= 4096): pass 1 takes every thread's largest value; the
+// threads form n_g >= k groups (n_g the next power of two), and the smallest of the n_g group
+// maxima, L, is a lower bound of the k-th largest value (n_g >= k distinct elements are >= L);
+// M is the row maximum.  Pass 2 looks only at elements >= L (a fraction of a percent of the row
+// for k = 50): they are kept in an LDS list and counted in a histogram over (M - value) in
+// order-preserving integer units, 2047 bins.  The bin B in which the count reaches k bounds the
+// top k from below, the list is cut down to bins <= B (k plus a few) and sorted.  Two passes over
+// the row and hardly any contended atomics.  If the list or the cut overflows (many equal
+// values), or k > 1024, the radix selection below does the job: up to six passes on the 64-bit
+// key (11/11/10-bit digits), exact for any input.
 __global__ __launch_bounds__(1024) void sample_kernel(
     int V, const float *__restrict__ logits, size_t row_stride, float temperature, int top_k,
     const float *__restrict__ uniforms, int32_t *__restrict__ out_tokens,
@@ -486,7 +556,8 @@ __global__ __launch_bounds__(1024) void sample_kernel(
   __shared__ float ev[MC_MAX_TOP_K];
   __shared__ unsigned int hist[2048];
   __shared__ unsigned long long scratch64[16];
-  __shared__ unsigned int s_bin, s_above, s_cnt;
+  __shared__ unsigned int scratch32[16];
+  __shared__ unsigned int s_bin, s_above, s_cnt, s_cnt2;
   const int b = blockIdx.x, tid = threadIdx.x;
   const float *row = logits + (size_t)b * row_stride;
 
@@ -505,71 +576,167 @@ __global__ __launch_bounds__(1024) void sample_kernel(
     return;
   }
   const int k = (top_k <= 0 || top_k >= V) ? V : top_k;
+  int n_sel = 0;                                   // keys in sel[] (>= k; the top k are among them)
 
-  // ---- radix selection of the k-th largest key
-  unsigned long long prefix = 0, pmask = 0;
-  unsigned int need = (unsigned int)k;
-  const int shifts[6] = {53, 42, 32, 21, 10, 0};
-  const int nbits[6] = {11, 11, 10, 11, 11, 10};
-  for (int pass = 0; pass < 6; ++pass) {
-    const int shift = shifts[pass];
-    const unsigned int bmask = (1u << nbits[pass]) - 1u;
-    for (int i = tid; i < 2048; i += 1024) hist[i] = 0;
+  // ---- fast path
+  if (k <= 1024 && V >= 4096) {
+    // Division by T > 0, correctly rounded, never reverses an order, so maxima are taken on the
+    // logits themselves and only they are divided.
+    unsigned int mine = 0;
+    scan_row(row, V, [&](bool ok, float z, int) {
+      if (ok) mine = max(mine, float_order_bits(z));
+    });
+    const unsigned int M = float_order_bits(
+        __fdiv_rn(float_from_order_bits(block_reduce_u32(mine, true, scratch32)), temperature));
+    // group maxima: n_g groups of 1024 / n_g consecutive threads (V >= 4096: every thread has
+    // seen elements, and different threads see different elements)
+    int n_g = 1;
+    while (n_g < k) n_g <<= 1;
+    hist[tid] = mine;
     __syncthreads();
-    for (int v = tid; v < V; v += 1024) {
-      const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
-      if ((key & pmask) == prefix) atomicAdd(&hist[(unsigned int)(key >> shift) & bmask], 1u);
+    unsigned int gmax = 0xFFFFFFFFu;
+    if (tid < n_g) {
+      const int per = 1024 / n_g;
+      gmax = 0;
+      for (int i = 0; i < per; ++i) gmax = max(gmax, hist[tid * per + i]);
     }
+    const float z_l = float_from_order_bits(block_reduce_u32(gmax, false, scratch32));
+    const unsigned int L = float_order_bits(__fdiv_rn(z_l, temperature));
+    // a logit below z_low cannot reach L after the division (its quotient is smaller by dozens
+    // of ulps): a cheap test that spares the division for nearly every element
+    const float z_low = z_l - fabsf(z_l) * 3.8147e-06f - 1e-30f;
+    const unsigned int range = M - L;
+    int shift = 0;
+    while ((range >> shift) > 2046u) ++shift;
+    for (int i = tid; i < 2048; i += 1024) hist[i] = 0;
+    if (tid == 0) { s_cnt = 0; s_cnt2 = 0; }
     __syncthreads();
+    scan_row(row, V, [&](bool ok, float z, int v) {
+      const bool maybe = ok && z >= z_low;
+      if (__ballot(maybe) == 0) return;             // wave-uniform: most batches hold no candidate
+      const unsigned int ob = maybe ? float_order_bits(__fdiv_rn(z, temperature)) : 0u;
+      const bool keep = maybe && ob >= L;
+      const unsigned int slot = wave_claim(keep, &s_cnt);
+      if (keep) {
+        atomicAdd(&hist[(M - ob) >> shift], 1u);
+        if (slot < MC_MAX_TOP_K) sel[slot] = ((unsigned long long)ob << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)v);
+      }
+    });
+    __syncthreads();
+    const unsigned int n_cand = s_cnt;
     if (tid < 64) {
-      // lane L owns bins [2048-32(L+1), 2048-32L): walk from the top bin down
-      const int hi = 2048 - 32 * tid;
-      unsigned int mine = 0;
-      for (int i = 1; i <= 32; ++i) mine += hist[hi - i];
-      unsigned int incl = mine;                   // inclusive scan over lanes 0..L
+      // lane L owns bins [32L, 32L + 32): find the bin in which the running count reaches k
+      unsigned int own = 0;
+      for (int i = 0; i < 32; ++i) own += hist[32 * tid + i];
+      unsigned int incl = own;
       for (int o = 1; o < 64; o <<= 1) {
         const unsigned int t = __shfl_up(incl, o, 64);
         if (tid >= o) incl += t;
       }
-      const unsigned int excl = incl - mine;
-      if (excl < need && incl >= need) {          // exactly one lane
-        unsigned int above = excl;
-        for (int i = 1; i <= 32; ++i) {
-          const unsigned int c = hist[hi - i];
-          if (above + c >= need) {
-            s_bin = (unsigned int)(hi - i);
-            s_above = above;
-            s_cnt = c;
+      const unsigned int excl = incl - own;
+      if (excl < (unsigned int)k && incl >= (unsigned int)k) {   // exactly one lane (count >= 1024 >= k)
+        unsigned int run = excl;
+        for (int i = 0; i < 32; ++i) {
+          run += hist[32 * tid + i];
+          if (run >= (unsigned int)k) {
+            s_bin = (unsigned int)(32 * tid + i);
+            s_above = run;                          // elements in bins <= s_bin
             break;
           }
-          above += c;
         }
       }
     }
     __syncthreads();
-    prefix |= (unsigned long long)s_bin << shift;
-    pmask |= (unsigned long long)bmask << shift;
-    need -= s_above;
-    const bool done = (s_cnt == need);            // the whole bin belongs to the top k
-    __syncthreads();
-    if (done) break;
-  }
-  // every key >= prefix (low bits zero) is selected: exactly k of them
-  if (tid == 0) s_cnt = 0;
-  __syncthreads();
-  for (int v = tid; v < V; v += 1024) {
-    const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
-    if (key >= prefix) {
-      const unsigned int slot = atomicAdd(&s_cnt, 1u);
-      if (slot < MC_MAX_TOP_K) sel[slot] = key;
+    const unsigned int B = s_bin, G = s_above;
+    if (n_cand <= MC_MAX_TOP_K && G <= MC_MAX_TOP_K) {
+      // cut the list down to bins <= B: read everything, then write the survivors back
+      unsigned long long mykeys[MC_MAX_TOP_K / 1024];
+#pragma unroll
+      for (int j = 0; j < MC_MAX_TOP_K / 1024; ++j) {
+        const unsigned int i = tid + 1024 * j;
+        mykeys[j] = (i < n_cand) ? sel[i] : 0ull;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < MC_MAX_TOP_K / 1024; ++j) {
+        const unsigned int i = tid + 1024 * j;
+        const bool keep = i < n_cand && ((M - (unsigned int)(mykeys[j] >> 32)) >> shift) <= B;
+        const unsigned int slot = wave_claim(keep, &s_cnt2);
+        if (keep) sel[slot] = mykeys[j];
+      }
+      __syncthreads();
+      n_sel = (int)s_cnt2;                           // == G
     }
+    __syncthreads();
+  }
+
+  // ---- general path: radix selection of the k-th largest key
+  if (n_sel == 0) {
+    unsigned long long prefix = 0, pmask = 0;
+    unsigned int need = (unsigned int)k;
+    const int shifts[6] = {53, 42, 32, 21, 10, 0};
+    const int nbits[6] = {11, 11, 10, 11, 11, 10};
+    for (int pass = 0; pass < 6; ++pass) {
+      const int shift = shifts[pass];
+      const unsigned int bmask = (1u << nbits[pass]) - 1u;
+      for (int i = tid; i < 2048; i += 1024) hist[i] = 0;
+      __syncthreads();
+      for (int v = tid; v < V; v += 1024) {
+        const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
+        if ((key & pmask) == prefix) atomicAdd(&hist[(unsigned int)(key >> shift) & bmask], 1u);
+      }
+      __syncthreads();
+      if (tid < 64) {
+        // lane L owns bins [2048-32(L+1), 2048-32L): walk from the top bin down
+        const int hi = 2048 - 32 * tid;
+        unsigned int mine = 0;
+        for (int i = 1; i <= 32; ++i) mine += hist[hi - i];
+        unsigned int incl = mine;                   // inclusive scan over lanes 0..L
+        for (int o = 1; o < 64; o <<= 1) {
+          const unsigned int t = __shfl_up(incl, o, 64);
+          if (tid >= o) incl += t;
+        }
+        const unsigned int excl = incl - mine;
+        if (excl < need && incl >= need) {          // exactly one lane
+          unsigned int above = excl;
+          for (int i = 1; i <= 32; ++i) {
+            const unsigned int c = hist[hi - i];
+            if (above + c >= need) {
+              s_bin = (unsigned int)(hi - i);
+              s_above = above;
+              s_cnt = c;
+              break;
+            }
+            above += c;
+          }
+        }
+      }
+      __syncthreads();
+      prefix |= (unsigned long long)s_bin << shift;
+      pmask |= (unsigned long long)bmask << shift;
+      need -= s_above;
+      const bool done = (s_cnt == need);            // the whole bin belongs to the top k
+      __syncthreads();
+      if (done) break;
+    }
+    // every key >= prefix (low bits zero) is selected: exactly k of them
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    for (int v = tid; v < V; v += 1024) {
+      const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
+      if (key >= prefix) {
+        const unsigned int slot = atomicAdd(&s_cnt, 1u);
+        if (slot < MC_MAX_TOP_K) sel[slot] = key;
+      }
+    }
+    n_sel = k;
   }
   int kp = 1;
-  while (kp < k) kp <<= 1;
+  while (kp < n_sel) kp <<= 1;
   __syncthreads();
-  for (int i = k + tid; i < kp; i += 1024) sel[i] = 0ull;
+  for (int i = n_sel + tid; i < kp; i += 1024) sel[i] = 0ull;
   __syncthreads();
-  // ---- bitonic sort, descending
+  // ---- bitonic sort, descending; the first k entries are the top k in order
   for (int size = 2; size <= kp; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
       for (int i = tid; i < kp; i += 1024) {

@@ -202,6 +202,30 @@ def test_sample_op_cases():
     assert k5.shape == (2, 7) and int(t5.cpu()[0]) == int(k5.cpu()[0, -1]) and int(t5.cpu()[1]) == int(k5.cpu()[1, 0])
 
 
+@pytest.mark.parametrize("V,k,T,scale", [
+    (128256, 1, 0.7, 1.28),        # k = 1 with T > 0: argmax path
+    (128256, 2, 0.6, 1.28), (128256, 50, 0.6, 1.28), (128256, 64, 1.0, 0.01), (128256, 65, 0.7, 30.0),
+    (128256, 400, 0.7, 1.28),      # 512 thread groups: the candidate list is near its capacity
+    (128256, 1000, 0.7, 1.28),     # the list overflows: radix selection
+    (128256, 4096, 1.3, 1.28),     # k above the fast path
+    (4096, 50, 0.7, 1.0), (4100, 50, 0.7, 1.0), (4095, 50, 0.7, 1.0), (1000, 200, 0.7, 1.0),
+])
+def test_sample_selection_paths(V, k, T, scale):
+    """Top-k ids bit-exact on both selection paths (threshold selection and radix selection),
+    including rows quantised to few distinct values (many ties at the cut)."""
+    import torch
+    B = 3
+    lg = rnd(33 + k, (B, V), scale)
+    lg[1] = np.round(lg[1] * 4) / 4 if scale >= 1 else np.round(lg[1] * 400) / 400     # heavy ties
+    lg[2, : V // 2] = lg[2, V // 2: 2 * (V // 2)]                                         # every value twice
+    us = synth.uniforms(34, 1, (B,))
+    print("case: sample paths", V, k, T, scale, flush=True)
+    toks, topk = binding.op_sample(torch.from_numpy(lg).cuda(), T, k, torch.from_numpy(us).cuda(), want_topk=True)
+    toks, topk = toks.cpu().numpy(), topk.cpu().numpy()
+    for b in range(B):
+        check_sampler_on_logits(lg[b], T, k, us[b], toks[b], topk[b])
+
+
 def test_reward_score_op():
     import torch
     V, B, R = 128256, 64, 8
