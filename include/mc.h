@@ -116,6 +116,19 @@ int mc_session_sync(mc_session *s);
  *    last prefix position on the device for mc_sample.  Asynchronous. */
 int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens);
 
+/* 1b. Grow the shared context in place (Sec. 3: the state of step i+1 is the state of step i
+ *    plus the chosen candidate, its feedback and the critique, so the prompt of the next depth
+ *    extends the prompt of this one).  mc_extend_shared appends n_tokens host tokens at positions
+ *    prefix_len .. of the shared sequence: only the new tokens are run, attending to the
+ *    prefix KV already there, and the logits of the last new position are left for mc_sample.
+ *    n_tokens in [1, max_prefix - prefix_len].  mc_promote_candidate appends the tokens candidate
+ *    cand has decoded so far (its suffix KV, copied on the device; nothing is recomputed) and
+ *    makes that candidate's pending logits the prefix logits.  Both drop all candidates.
+ *    Errors: MC_ERR_STATE without a prefix / without a decoded token, MC_ERR_OOM or
+ *    MC_ERR_INVALID when max_prefix would be exceeded.  Asynchronous. */
+int mc_extend_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens);
+int mc_promote_candidate(mc_session *s, int32_t cand);
+
 /* 2. One new token per candidate: appends its K/V to the candidate's current page
  *    and leaves logits [n_cands][vocab] on the device.  tokens: host [n_cands], or
  *    NULL to consume the tokens drawn by the latest mc_sample without leaving the

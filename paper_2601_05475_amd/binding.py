@@ -67,6 +67,8 @@ SIGNATURES = {
     "mc_session_reset_candidates": (C.c_int, [_vp]),
     "mc_session_sync": (C.c_int, [_vp]),
     "mc_prefill_shared": (C.c_int, [_vp, _vp, _i32]),
+    "mc_extend_shared": (C.c_int, [_vp, _vp, _i32]),
+    "mc_promote_candidate": (C.c_int, [_vp, _i32]),
     "mc_decode_step": (C.c_int, [_vp, _vp, _i32]),
     "mc_sample": (C.c_int, [_vp, _i32, _f32, _i32, _vp, _vp, _vp]),
     "mc_score_candidates": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
@@ -212,6 +214,13 @@ class Session:
     def prefill_shared(self, tokens: np.ndarray):
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         _check(load_library().mc_prefill_shared(self.handle, t.ctypes.data, t.shape[0]))
+
+    def extend_shared(self, tokens: np.ndarray):
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        _check(load_library().mc_extend_shared(self.handle, t.ctypes.data, t.shape[0]))
+
+    def promote_candidate(self, cand: int):
+        _check(load_library().mc_promote_candidate(self.handle, int(cand)))
 
     def decode_step(self, tokens: Optional[np.ndarray], n_cands: Optional[int] = None):
         if tokens is None:

@@ -625,28 +625,23 @@ extern "C" int mc_session_reset_candidates(mc_session *s) {
   return MC_OK;
 }
 
-extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens) {
-  if (!s || !tokens) MC_FAIL(MC_ERR_INVALID, "session / tokens is NULL");
-  if (n_tokens < 1 || n_tokens > s->p.max_prefix)
-    MC_FAIL(MC_ERR_INVALID, "n_tokens %d outside [1, %d]", n_tokens, s->p.max_prefix);
-  const mc_config &c = s->m->cfg;
-  MC_TRY(check_tokens(c, tokens, n_tokens));
-  MC_HIP(hipSetDevice(s->m->device));
+// Run n_tokens tokens at positions start .. start + n_tokens - 1 of the shared sequence (the
+// positions below start are in the prefix pages already), write their keys and values into the
+// prefix pages and leave the logits of the last one in prefix_logits.
+static int prefill_range(mc_session *s, const int32_t *tokens, int n_tokens, int start) {
   const SessionLayout &L = s->lay;
   const int pg = s->p.page_tokens;
-  // the old prefix and candidates are gone from here on
-  s->prefix_len = 0;
-  mc_session_reset_candidates(s);
   std::vector<int32_t> meta, items;
   int tail = 0, rows = 0;
   for (int p0 = 0; p0 < n_tokens; p0 += s->chunk_rows) {
     rows = std::min(s->chunk_rows, n_tokens - p0);
     meta.resize((size_t)rows * 4);
     for (int r = 0; r < rows; ++r) {
+      const int pos = start + p0 + r;
       meta[r] = tokens[p0 + r];
-      meta[rows + r] = p0 + r;
-      meta[2 * rows + r] = (p0 + r) / pg;
-      meta[3 * rows + r] = (p0 + r) % pg;
+      meta[rows + r] = pos;
+      meta[2 * rows + r] = pos / pg;
+      meta[3 * rows + r] = pos % pg;
     }
     // the four blocks land in row_tok, row_pos, row_page, row_off
     MC_TRY(upload(s, s->ptr<void>(L.row_tok), meta.data(), (size_t)rows * 4));
@@ -656,20 +651,108 @@ extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n
     // attention work items: 32 consecutive positions each
     items.clear();
     for (int r = 0; r < rows; r += 32) {
-      items.push_back(r); items.push_back(std::min(32, rows - r)); items.push_back(p0 + r); items.push_back(-1);
+      items.push_back(r); items.push_back(std::min(32, rows - r)); items.push_back(start + p0 + r); items.push_back(-1);
     }
     MC_TRY(upload(s, s->ptr<void>(L.items), items.data(), items.size() * 4));
-    MC_TRY(run_layers(s, rows, PASS_PREFIX, p0 + rows, (int)items.size() / 4, &tail));
+    MC_TRY(run_layers(s, rows, PASS_PREFIX, start + p0 + rows, (int)items.size() / 4, &tail));
   }
   // logits of the last position only
-  {
-    const int32_t last = rows - 1;
-    MC_TRY(upload(s, s->ptr<void>(L.last_idx), &last, 4));
-    MC_TRY(lm_head(s, rows, tail, 1, true, s->ptr<float>(L.prefix_logits)));
-  }
+  const int32_t last = rows - 1;
+  MC_TRY(upload(s, s->ptr<void>(L.last_idx), &last, 4));
+  MC_TRY(lm_head(s, rows, tail, 1, true, s->ptr<float>(L.prefix_logits)));
+  return MC_OK;
+}
+
+extern "C" int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens) {
+  if (!s || !tokens) MC_FAIL(MC_ERR_INVALID, "session / tokens is NULL");
+  if (n_tokens < 1 || n_tokens > s->p.max_prefix)
+    MC_FAIL(MC_ERR_INVALID, "n_tokens %d outside [1, %d]", n_tokens, s->p.max_prefix);
+  MC_TRY(check_tokens(s->m->cfg, tokens, n_tokens));
+  MC_HIP(hipSetDevice(s->m->device));
+  // the old prefix and candidates are gone from here on
+  s->prefix_len = 0;
+  mc_session_reset_candidates(s);
+  MC_TRY(prefill_range(s, tokens, n_tokens, 0));
   s->prefix_len = n_tokens;
   s->logits_state = LOGITS_PREFIX;
   s->logits_rows = 1;
+  return MC_OK;
+}
+
+extern "C" int mc_extend_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens) {
+  if (!s || !tokens) MC_FAIL(MC_ERR_INVALID, "session / tokens is NULL");
+  if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_extend_shared before mc_prefill_shared");
+  if (n_tokens < 1 || n_tokens > s->p.max_prefix - s->prefix_len)
+    MC_FAIL(MC_ERR_INVALID, "n_tokens %d outside [1, %d] (prefix holds %d of %d)", n_tokens,
+            s->p.max_prefix - s->prefix_len, s->prefix_len, s->p.max_prefix);
+  MC_TRY(check_tokens(s->m->cfg, tokens, n_tokens));
+  MC_HIP(hipSetDevice(s->m->device));
+  const int start = s->prefix_len;
+  // candidates were conditioned on the shorter prefix: they are gone; a failure below leaves
+  // the old prefix intact (pages past it may have been written, which nothing reads)
+  mc_session_reset_candidates(s);
+  s->logits_state = LOGITS_NONE;
+  s->logits_rows = 0;
+  MC_TRY(prefill_range(s, tokens, n_tokens, start));
+  s->prefix_len = start + n_tokens;
+  s->logits_state = LOGITS_PREFIX;
+  s->logits_rows = 1;
+  return MC_OK;
+}
+
+namespace mc {
+// Copy the keys and values of suffix tokens 0 .. t-1 of one candidate (pages table_row[.] of the
+// pool) to prefix positions P .. P + t - 1, element by element: the two sides may sit at
+// different offsets inside their pages.  One block per (token, layer).
+template <typename T>
+__global__ __launch_bounds__(256) void kv_promote_kernel(
+    char *kbase, char *vbase, size_t layer_bytes, int n_prefix_pages, const int32_t *__restrict__ table_row,
+    int Hkv, int hd, int pg, int P) {
+  const int j = blockIdx.x, l = blockIdx.y;
+  const size_t pelems = (size_t)Hkv * hd * pg;
+  T *k = (T *)(kbase + (size_t)l * layer_bytes), *v = (T *)(vbase + (size_t)l * layer_bytes);
+  const size_t src = (size_t)(n_prefix_pages + table_row[j / pg]) * pelems;
+  const size_t dst = (size_t)((P + j) / pg) * pelems;
+  const int so = j % pg, dof = (P + j) % pg;
+  for (int e = threadIdx.x; e < Hkv * hd; e += 256) {
+    const int kvh = e / hd, d = e % hd;
+    const size_t head = (size_t)kvh * pg * hd;
+    k[dst + head + k_elem_offset(dof, d, pg, hd)] = k[src + head + k_elem_offset(so, d, pg, hd)];
+    v[dst + head + v_elem_offset(dof, d, pg, hd)] = v[src + head + v_elem_offset(so, d, pg, hd)];
+  }
+}
+}  // namespace mc
+
+extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
+  if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
+  if (s->n_cands < 1 || s->suffix_len < 1) MC_FAIL(MC_ERR_STATE, "mc_promote_candidate: no candidate has decoded a token");
+  if (cand < 0 || cand >= s->n_cands) MC_FAIL(MC_ERR_INVALID, "candidate %d outside [0, %d)", cand, s->n_cands);
+  const int t = s->suffix_len, P = s->prefix_len;
+  if (t > s->p.max_prefix - P)
+    MC_FAIL(MC_ERR_OOM, "prefix of %d + suffix of %d tokens exceeds max_prefix %d", P, t, s->p.max_prefix);
+  MC_HIP(hipSetDevice(s->m->device));
+  const mc_config &c = s->m->cfg;
+  const SessionLayout &L = s->lay;
+  const int32_t *row = s->ptr<int32_t>(L.page_table) + (size_t)cand * L.pages_per_cand;
+  dim3 grid(t, c.n_layers);
+  if (c.dtype == MC_F32)
+    kv_promote_kernel<float><<<grid, 256, 0, s->stream>>>(s->k_layer(0), s->v_layer(0), s->layer_pool_bytes(),
+                                                          L.n_prefix_pages, row, c.n_kv_heads, c.head_dim, s->p.page_tokens, P);
+  else
+    kv_promote_kernel<bf16_t><<<grid, 256, 0, s->stream>>>(s->k_layer(0), s->v_layer(0), s->layer_pool_bytes(),
+                                                           L.n_prefix_pages, row, c.n_kv_heads, c.head_dim, s->p.page_tokens, P);
+  MC_HIP(hipGetLastError());
+  // the candidate's last logits become the logits of the last prefix position
+  const bool have_logits = s->logits_state == LOGITS_CANDS && s->logits_rows == s->n_cands;
+  if (have_logits)
+    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.prefix_logits), s->ptr<float>(L.logits) + (size_t)cand * c.vocab,
+                          (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, s->stream));
+  s->prefix_len = P + t;
+  mc_session_reset_candidates(s);
+  if (!have_logits) {
+    s->logits_state = LOGITS_NONE;
+    s->logits_rows = 0;
+  }
   return MC_OK;
 }
 

@@ -221,3 +221,88 @@ def test_1b_shape_two_layer_twin():
     toks, topk = sess.sample(16, wl.temperature, wl.top_k, us, want_topk=True)
     for b in range(16):
         check_sampler_on_logits(steps[-1][b], wl.temperature, wl.top_k, us[b], toks[b], topk[b])
+
+
+# ---------------------------------------------------------------- growing the shared prefix
+def _decode_all(sess, suffix):
+    out = []
+    for t in range(suffix.shape[1]):
+        sess.decode_step(suffix[:, t])
+        out.append(sess.logits(suffix.shape[0]))
+    return np.stack(out)
+
+
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4, cut=101, chunk=32), "f32"),
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=8, cut=1, chunk=0), "bf16"),
+    # tiled bf16 path: MFMA prefill attention over prefix pages written by two calls, 64-token pages
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64, cut=70, chunk=64), "bf16"),
+    (dict(L=2, d=256, Hq=8, Hkv=2, hd=128, F=512, V=1024, pg=64, cut=128, chunk=0), "bf16"),
+])
+def test_extend_shared_equals_one_prefill(kw, dtype):
+    """Prefix written by prefill + two extensions: the logits after it and the decode steps on
+    top of it are those of the oracle on the whole sequence (and of a single prefill)."""
+    s = small_shape("ext", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 78)
+    P, B, N = 170, 3, 4
+    prefix = synth.tokens(6, 1, (P,), s.vocab)
+    suffix = synth.tokens(6, 2, (B, N), s.vocab)
+    print("case: extend shared", kw, dtype, flush=True)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P, B, N, kw["pg"], kw["chunk"])
+    cut = kw["cut"]
+    sess.prefill_shared(prefix[:cut])
+    sess.decode_step(suffix[:, 0])                  # candidates that the extension must drop
+    sess.extend_shared(prefix[cut:cut + 37])
+    sess.extend_shared(prefix[cut + 37:])
+    pl = sess.logits(1)[0]
+    steps = _decode_all(sess, suffix)
+    check_against_oracle(s, w, prefix, suffix, pl, steps)
+    one = binding.Session(model, P, B, N, kw["pg"], kw["chunk"])
+    one.prefill_shared(prefix)
+    tol = 1e-5 if dtype == "f32" else 3e-2          # chunk boundaries differ: not bit-identical
+    np.testing.assert_allclose(one.logits(1)[0], pl, rtol=0, atol=tol * np.abs(pl).max())
+    with pytest.raises(binding.McError) as e:       # the prefix is full
+        sess.extend_shared(prefix[:1])
+    assert e.value.code == -1
+
+
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4, P=50), "f32"),
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64, P=100), "bf16"),
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64, P=64), "f32"),
+])
+def test_promote_candidate_then_extend(kw, dtype):
+    """Decode, promote one candidate's suffix into the prefix (a copy of its KV), extend with more
+    tokens, decode again: everything equals the oracle on the concatenated sequence."""
+    s = small_shape("pro", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 79)
+    P, B, N1, E, N2, keep = kw["P"], 4, 70, 9, 3, 2
+    prefix = synth.tokens(7, 1, (P,), s.vocab)
+    suf1 = synth.tokens(7, 2, (B, N1), s.vocab)
+    extra = synth.tokens(7, 3, (E,), s.vocab)
+    suf2 = synth.tokens(7, 4, (B, N2), s.vocab)
+    print("case: promote", kw, dtype, flush=True)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P + N1 + E, B, N1, kw["pg"], 64)
+    with pytest.raises(binding.McError) as e:
+        sess.extend_shared(extra)
+    assert e.value.code == -2
+    sess.prefill_shared(prefix)
+    with pytest.raises(binding.McError) as e:
+        sess.promote_candidate(0)
+    assert e.value.code == -2
+    steps1 = _decode_all(sess, suf1)
+    sess.promote_candidate(keep)
+    np.testing.assert_array_equal(sess.logits(1)[0], steps1[-1][keep])
+    grown = np.concatenate([prefix, suf1[keep]])
+    # decoding straight on the promoted prefix (no extension)
+    d0 = _decode_all(sess, suf2[:, :1])
+    want_pl, want = oracle_shared(s, w, grown, suf2[:, :1])
+    fl = oracle_shared(s, w, grown, suf2[:, :1], exact=False)[1] if dtype == "bf16" else None
+    assert_logits_close(d0, want, dtype, "decode on the promoted prefix", fl)
+    # then the feedback / critique tokens, and a new round of candidates
+    sess.extend_shared(extra)
+    pl = sess.logits(1)[0]
+    steps2 = _decode_all(sess, suf2)
+    check_against_oracle(s, w, np.concatenate([grown, extra]), suf2, pl, steps2)
