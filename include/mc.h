@@ -129,6 +129,16 @@ int mc_prefill_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens);
 int mc_extend_shared(mc_session *s, const int32_t *tokens, int32_t n_tokens);
 int mc_promote_candidate(mc_session *s, int32_t cand);
 
+/* 1c. Several new tokens per candidate in one pass (the critic of Sec. 3.3 reads, per candidate,
+ *    the candidate and its execution feedback after the shared trajectory, then writes its
+ *    critique token by token).  suffix_tokens: host [n_cands][len]; every candidate gets len
+ *    tokens at suffix positions suffix_len .. suffix_len + len - 1, attending causally to the
+ *    shared prefix and to its own suffix; their K/V go to the candidate's pages and stay, the
+ *    logits of each candidate's last new token are left for mc_sample / mc_decode_step to go on
+ *    from.  Candidates stay in lock-step (one common len).  Errors: MC_ERR_STATE without a
+ *    prefix, MC_ERR_OOM beyond max_suffix, MC_ERR_INVALID for a changed n_cands.  Asynchronous. */
+int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len);
+
 /* 2. One new token per candidate: appends its K/V to the candidate's current page
  *    and leaves logits [n_cands][vocab] on the device.  tokens: host [n_cands], or
  *    NULL to consume the tokens drawn by the latest mc_sample without leaving the

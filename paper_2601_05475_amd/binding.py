@@ -69,6 +69,7 @@ SIGNATURES = {
     "mc_prefill_shared": (C.c_int, [_vp, _vp, _i32]),
     "mc_extend_shared": (C.c_int, [_vp, _vp, _i32]),
     "mc_promote_candidate": (C.c_int, [_vp, _i32]),
+    "mc_prefill_suffix": (C.c_int, [_vp, _vp, _i32, _i32]),
     "mc_decode_step": (C.c_int, [_vp, _vp, _i32]),
     "mc_sample": (C.c_int, [_vp, _i32, _f32, _i32, _vp, _vp, _vp]),
     "mc_score_candidates": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
@@ -221,6 +222,11 @@ class Session:
 
     def promote_candidate(self, cand: int):
         _check(load_library().mc_promote_candidate(self.handle, int(cand)))
+
+    def prefill_suffix(self, suffix_tokens: np.ndarray):
+        """suffix_tokens: [n_cands, len] appended to every candidate in one pass."""
+        t = np.ascontiguousarray(suffix_tokens, dtype=np.int32)
+        _check(load_library().mc_prefill_suffix(self.handle, t.ctypes.data, t.shape[0], t.shape[1]))
 
     def decode_step(self, tokens: Optional[np.ndarray], n_cands: Optional[int] = None):
         if tokens is None:

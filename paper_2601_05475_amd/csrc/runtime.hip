@@ -403,7 +403,7 @@ __global__ void copy_row_kernel(int n, const float *__restrict__ src, float *__r
   if (i < n) dst[i] = src[i];
 }
 
-enum { PASS_PREFIX = 0, PASS_DECODE = 1, PASS_SCORE = 2 };
+enum { PASS_PREFIX = 0, PASS_DECODE = 1, PASS_SCORE = 2, PASS_SUFFIX = 3 };
 
 // Run all layers on `rows` rows whose metadata (token, position, KV slot, table row) is on the
 // device already.  prefix_visible: number of prefix keys that exist (for PASS_PREFIX: the end of
@@ -447,7 +447,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
     char *kl = s->k_layer(l), *vl = s->v_layer(l);
     void *kdst, *vdst;
     if (pass == PASS_PREFIX) { kdst = kl; vdst = vl; }
-    else if (pass == PASS_DECODE) { kdst = kl + prefix_bytes; vdst = vl + prefix_bytes; }
+    else if (pass == PASS_DECODE || pass == PASS_SUFFIX) { kdst = kl + prefix_bytes; vdst = vl + prefix_bytes; }
     else { kdst = s->ptr<void>(L.kscr); vdst = s->ptr<void>(L.vscr); }
     {
       ProfScope ps(s, MC_K_ROPE_KV);
@@ -471,7 +471,8 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
         PrefillAttnArgs pa;
         pa.q = q; pa.k_prefix = kl; pa.v_prefix = vl; pa.k_suffix = kdst; pa.v_suffix = vdst;
         pa.items = s->ptr<int4>(L.items); pa.n_items = n_items;
-        pa.page_table = (pass == PASS_SCORE) ? s->ptr<int32_t>(L.score_table) : nullptr;
+        pa.page_table = (pass == PASS_SCORE) ? s->ptr<int32_t>(L.score_table)
+                        : (pass == PASS_SUFFIX) ? s->ptr<int32_t>(L.page_table) : nullptr;
         pa.table_stride = L.pages_per_cand;
         pa.n_q_heads = c.n_q_heads; pa.n_kv_heads = c.n_kv_heads; pa.head_dim = c.head_dim;
         pa.page_tokens = s->p.page_tokens; pa.prefix_len = prefix_visible; pa.out = ao;
@@ -482,7 +483,8 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       AttnArgs a;
       a.q = q; a.k_prefix = kl; a.v_prefix = vl; a.k_suffix = kdst; a.v_suffix = vdst;
       a.row_pos = row_pos; a.row_tab = row_tab;
-      a.page_table = (pass == PASS_SCORE) ? s->ptr<int32_t>(L.score_table) : nullptr;
+      a.page_table = (pass == PASS_SCORE) ? s->ptr<int32_t>(L.score_table)
+                     : (pass == PASS_SUFFIX) ? s->ptr<int32_t>(L.page_table) : nullptr;
       a.table_stride = L.pages_per_cand;
       a.rows = rows; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
       a.head_dim = c.head_dim; a.page_tokens = s->p.page_tokens; a.prefix_len = prefix_visible;
@@ -756,6 +758,21 @@ extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
   return MC_OK;
 }
 
+// Page ids are a pure function of (candidate, page slot) under the lock-step rule: at the
+// boundary t = p * page_tokens candidates take pages in ascending order from the list head.
+// The whole table goes to the device once per set of candidates.
+static int ensure_page_table(mc_session *s, int n_cands) {
+  if (s->table_ready) return MC_OK;
+  const SessionLayout &L = s->lay;
+  std::vector<int32_t> full((size_t)s->p.max_cands * L.pages_per_cand, 0);
+  for (int p = 0; p < L.pages_per_cand; ++p)
+    for (int b = 0; b < n_cands; ++b) full[(size_t)b * L.pages_per_cand + p] = s->free_list[(size_t)p * n_cands + b];
+  MC_HIP(hipMemcpyAsync(s->ptr<void>(L.page_table), full.data(), full.size() * 4, hipMemcpyHostToDevice, s->stream));
+  MC_HIP(hipStreamSynchronize(s->stream));
+  s->table_ready = true;
+  return MC_OK;
+}
+
 extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_cands) {
   if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
   if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_decode_step before mc_prefill_shared");
@@ -770,16 +787,7 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   MC_HIP(hipSetDevice(s->m->device));
   const SessionLayout &L = s->lay;
   const int pg = s->p.page_tokens, t = s->suffix_len;
-  if (!s->table_ready) {
-    // Page ids are a pure function of (candidate, page slot) under the lock-step rule: at the
-    // boundary t = p * page_tokens candidates take pages in ascending order from the list head.
-    std::vector<int32_t> full((size_t)s->p.max_cands * L.pages_per_cand, 0);
-    for (int p = 0; p < L.pages_per_cand; ++p)
-      for (int b = 0; b < n_cands; ++b) full[(size_t)b * L.pages_per_cand + p] = s->free_list[(size_t)p * n_cands + b];
-    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.page_table), full.data(), full.size() * 4, hipMemcpyHostToDevice, s->stream));
-    MC_HIP(hipStreamSynchronize(s->stream));
-    s->table_ready = true;
-  }
+  MC_TRY(ensure_page_table(s, n_cands));
   if (tokens) MC_TRY(upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4));
   else MC_HIP(hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4, hipMemcpyDeviceToDevice, s->stream));
   decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
@@ -930,6 +938,69 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
   // scoring overwrote the candidates' logits buffer: sampling must be preceded by a new step
   s->logits_state = LOGITS_SCORE;
   s->logits_rows = n_cands;
+  return MC_OK;
+}
+
+extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len) {
+  if (!s || !suffix_tokens) MC_FAIL(MC_ERR_INVALID, "session / suffix_tokens is NULL");
+  if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_prefill_suffix before mc_prefill_shared");
+  if (n_cands < 1 || n_cands > s->p.max_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
+  if (s->n_cands && n_cands != s->n_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d differs from the %d fixed earlier", n_cands, s->n_cands);
+  const int t = s->suffix_len;
+  if (len < 1) MC_FAIL(MC_ERR_INVALID, "len %d < 1", len);
+  if (len > s->p.max_suffix - t)
+    MC_FAIL(MC_ERR_OOM, "suffix of %d + %d tokens exceeds max_suffix %d: page pool exhausted", t, len, s->p.max_suffix);
+  const mc_config &c = s->m->cfg;
+  MC_TRY(check_tokens(c, suffix_tokens, (size_t)n_cands * len));
+  MC_HIP(hipSetDevice(s->m->device));
+  const SessionLayout &L = s->lay;
+  const int pg = s->p.page_tokens;
+  MC_TRY(ensure_page_table(s, n_cands));
+  auto page_of = [&](int b, int slot) { return s->free_list[(size_t)slot * n_cands + b]; };
+  std::vector<int32_t> tok, pos, page, off, tab, last, items;
+  const int per_chunk = std::max(1, s->chunk_rows / len);          // whole candidates per chunk
+  const int saved_n = s->n_cands;
+  s->n_cands = n_cands;
+  for (int b0 = 0; b0 < n_cands; b0 += per_chunk) {
+    const int nc = std::min(per_chunk, n_cands - b0), rows = nc * len;
+    tok.resize(rows); pos.resize(rows); page.resize(rows); off.resize(rows); tab.resize(rows);
+    last.resize(nc);
+    items.clear();
+    int r = 0;
+    for (int b = b0; b < b0 + nc; ++b) {
+      for (int j = 0; j < len; j += 32) {
+        items.push_back(r + j); items.push_back(std::min(32, len - j));
+        items.push_back(s->prefix_len + t + j); items.push_back(b);
+      }
+      for (int j = 0; j < len; ++j, ++r) {
+        tok[r] = suffix_tokens[(size_t)b * len + j];
+        pos[r] = s->prefix_len + t + j;
+        page[r] = page_of(b, (t + j) / pg);
+        off[r] = (t + j) % pg;
+        tab[r] = b;
+      }
+      last[b - b0] = r - 1;
+    }
+    int rc = upload(s, s->ptr<void>(L.row_tok), tok.data(), (size_t)rows * 4);
+    if (rc == MC_OK) rc = upload(s, s->ptr<void>(L.row_pos), pos.data(), (size_t)rows * 4);
+    if (rc == MC_OK) rc = upload(s, s->ptr<void>(L.row_page), page.data(), (size_t)rows * 4);
+    if (rc == MC_OK) rc = upload(s, s->ptr<void>(L.row_off), off.data(), (size_t)rows * 4);
+    if (rc == MC_OK) rc = upload(s, s->ptr<void>(L.row_tab), tab.data(), (size_t)rows * 4);
+    if (rc == MC_OK) rc = upload(s, s->ptr<void>(L.last_idx), last.data(), (size_t)nc * 4);
+    if (rc == MC_OK) rc = upload(s, s->ptr<void>(L.items), items.data(), items.size() * 4);
+    int tail = 0;
+    if (rc == MC_OK) rc = run_layers(s, rows, PASS_SUFFIX, s->prefix_len, (int)items.size() / 4, &tail);
+    if (rc == MC_OK) rc = lm_head(s, rows, tail, nc, true, s->ptr<float>(L.logits) + (size_t)b0 * c.vocab);
+    if (rc != MC_OK) { s->n_cands = saved_n; return rc; }
+  }
+  for (int slot = t / pg; slot <= (t + len - 1) / pg; ++slot)
+    for (int b = 0; b < n_cands; ++b) s->host_table[(size_t)b * L.pages_per_cand + slot] = page_of(b, slot);
+  s->suffix_len = t + len;
+  s->logits_state = LOGITS_CANDS;
+  s->logits_rows = n_cands;
+  s->sampled_on_device = false;
   return MC_OK;
 }
 

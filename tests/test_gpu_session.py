@@ -306,3 +306,51 @@ def test_promote_candidate_then_extend(kw, dtype):
     pl = sess.logits(1)[0]
     steps2 = _decode_all(sess, suf2)
     check_against_oracle(s, w, np.concatenate([grown, extra]), suf2, pl, steps2)
+
+
+# ---------------------------------------------------------------- critic workload: suffix prefill
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4, P=50, B=3, chunk=0), "f32"),
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=8, P=9, B=5, chunk=32), "bf16"),
+    # tiled bf16: MFMA attention over prefix pages + the candidate's own pages, chunks of 2 candidates
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64, P=100, B=5, chunk=160), "bf16"),
+    (dict(L=2, d=256, Hq=8, Hkv=2, hd=128, F=512, V=1024, pg=64, P=64, B=2, chunk=0), "bf16"),
+])
+def test_prefill_suffix_then_decode(kw, dtype):
+    """Per-candidate suffix written in bulk (after two ordinary decode steps, then 70 tokens at
+    once, crossing page boundaries), then token-by-token decoding on top: every logit row equals
+    the oracle's for the same sequences."""
+    s = small_shape("crit", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 80)
+    P, B = kw["P"], kw["B"]
+    n0, n1, n2 = 2, 70, 3
+    prefix = synth.tokens(8, 1, (P,), s.vocab)
+    suffix = synth.tokens(8, 2, (B, n0 + n1 + n2), s.vocab)
+    print("case: prefill suffix", kw, dtype, flush=True)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P, B, n0 + n1 + n2, kw["pg"], kw["chunk"])
+    with pytest.raises(binding.McError) as e:
+        sess.prefill_suffix(suffix[:, :4])
+    assert e.value.code == -2
+    sess.prefill_shared(prefix)
+    pl = sess.logits(1)[0]
+    got = [None] * (n0 + n1 + n2)
+    for t in range(n0):
+        sess.decode_step(suffix[:, t])
+        got[t] = sess.logits(B)
+    sess.prefill_suffix(suffix[:, n0:n0 + n1])
+    got[n0 + n1 - 1] = sess.logits(B)
+    for t in range(n0 + n1, n0 + n1 + n2):
+        sess.decode_step(suffix[:, t])
+        got[t] = sess.logits(B)
+    with pytest.raises(binding.McError) as e:       # the candidates' pages are full
+        sess.prefill_suffix(suffix[:, :1])
+    assert e.value.code == -3
+    want_pl, want = oracle_shared(s, w, prefix, suffix)
+    fl = oracle_shared(s, w, prefix, suffix, exact=False)[1] if dtype == "bf16" else None
+    idx = [t for t in range(len(got)) if got[t] is not None]
+    assert_logits_close(np.stack([got[t] for t in idx]), want[idx], dtype, "suffix prefill + decode",
+                        None if fl is None else fl[idx])
+    tab, n = sess.page_table()
+    ref = opaging.page_tables(B, n0 + n1 + n2, kw["pg"], range(sess.pool_pages()))
+    np.testing.assert_array_equal(tab[:, :ref.shape[1]], ref)
