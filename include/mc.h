@@ -177,6 +177,36 @@ int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
 #define MC_MAX_TOP_K 4096
 #define MC_MAX_REWARD 64
 
+/* ---- host-side bookkeeping of the search loop (no device work) -------------------- */
+
+/* Categorical reward f_r (Sec. 3.3, "Categorical Reward Formulation"): 0 if the candidate is
+ * incorrect or its speedup is <= 100 %, else 1..4 by the thresholds (s1, s2, s3) in percent
+ * (intervals closed on the right).  thresholds: host, 3 values, 100 <= s1 <= s2 <= s3.
+ * Returns the bin, or a negative mc_status. */
+int32_t mc_reward_bin(double speedup_percent, int32_t correct, const double *thresholds);
+
+/* Best discounted reward so far (Sec. 3.2): u_out[i] = max_{j <= i} gamma^depths[j] * rewards[j].
+ * All arrays host, n >= 1, gamma in (0, 1]. */
+int mc_best_so_far(const double *rewards, const int32_t *depths, int32_t n, double gamma, double *u_out);
+
+/* Training targets of the value model along one trajectory (Sec. 3.3): with rewards[t] =
+ * f_r(e_{t+1}), t = 0..n-1,  u_out[t] = max_{k <= t} gamma^k rewards[k]  and
+ * v_out[t] = max(u_out[t] / gamma, max_{k >= t} gamma^(k-t) rewards[k]). */
+int mc_value_targets(const double *rewards, int32_t n, double gamma, double *u_out, double *v_out);
+
+/* Beam step of the CUDA-LLM search (Sec. 3.2): the index of the largest speedup ratio if any is
+ * > 1 (lowest index on ties), else MC_SELECT_NONE (no candidate is correct and faster). */
+#define MC_SELECT_NONE (-100)
+int32_t mc_select_candidate(const double *speedups, int32_t n);
+
+/* Evaluation statistics (Sec. 4, "Evaluation Metrics").  mc_median_of_max: speedups holds the
+ * generations of problem 0, then of problem 1, ... (counts[p] >= 1 each); *out = the median over
+ * problems of the per-problem maximum (mean of the two middle values for an even count).
+ * mc_average_rank: max_speedup is [n_methods][n_problems]; avg_rank[m] = mean over problems of
+ * 1 + the number of methods strictly better on that problem. */
+int mc_median_of_max(const double *speedups, const int32_t *counts, int32_t n_problems, double *out);
+int mc_average_rank(const double *max_speedup, int32_t n_methods, int32_t n_problems, double *avg_rank);
+
 /* ---- inspection hooks (tests and tools; not on the fast path) -------------------- */
 /* Copy the pending logits to host as fp32: n_rows rows of vocab floats (1 row after
  * a prefill, n_cands after a decode step, n_cands after scoring). */

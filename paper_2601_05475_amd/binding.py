@@ -70,6 +70,12 @@ SIGNATURES = {
     "mc_extend_shared": (C.c_int, [_vp, _vp, _i32]),
     "mc_promote_candidate": (C.c_int, [_vp, _i32]),
     "mc_prefill_suffix": (C.c_int, [_vp, _vp, _i32, _i32]),
+    "mc_reward_bin": (_i32, [C.c_double, _i32, _vp]),
+    "mc_best_so_far": (C.c_int, [_vp, _vp, _i32, C.c_double, _vp]),
+    "mc_value_targets": (C.c_int, [_vp, _i32, C.c_double, _vp, _vp]),
+    "mc_select_candidate": (_i32, [_vp, _i32]),
+    "mc_median_of_max": (C.c_int, [_vp, _vp, _i32, _vp]),
+    "mc_average_rank": (C.c_int, [_vp, _i32, _i32, _vp]),
     "mc_decode_step": (C.c_int, [_vp, _vp, _i32]),
     "mc_sample": (C.c_int, [_vp, _i32, _f32, _i32, _vp, _vp, _vp]),
     "mc_score_candidates": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
@@ -304,6 +310,61 @@ class Session:
 
 
 # ---- single operations on torch CUDA tensors -------------------------------------------
+
+# ---- host-side bookkeeping of the search loop (argument marshalling only)
+MC_SELECT_NONE = -100
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def reward_bin(speedup_percent: float, correct: bool, thresholds) -> int:
+    th = _f64(thresholds)
+    r = load_library().mc_reward_bin(float(speedup_percent), int(bool(correct)), th.ctypes.data)
+    if r < 0:
+        _check(r)
+    return r
+
+
+def best_so_far(rewards, depths, gamma: float) -> np.ndarray:
+    r = _f64(rewards); d = np.ascontiguousarray(depths, dtype=np.int32)
+    out = np.empty(r.shape[0], np.float64)
+    _check(load_library().mc_best_so_far(r.ctypes.data, d.ctypes.data, r.shape[0], float(gamma), out.ctypes.data))
+    return out
+
+
+def value_targets(rewards, gamma: float):
+    r = _f64(rewards)
+    u = np.empty(r.shape[0], np.float64); v = np.empty(r.shape[0], np.float64)
+    _check(load_library().mc_value_targets(r.ctypes.data, r.shape[0], float(gamma), u.ctypes.data, v.ctypes.data))
+    return u, v
+
+
+def select_candidate(speedups):
+    f = _f64(speedups)
+    r = load_library().mc_select_candidate(f.ctypes.data, f.shape[0])
+    if r == MC_SELECT_NONE:
+        return None
+    if r < 0:
+        _check(r)
+    return r
+
+
+def median_of_max(speedups_per_problem) -> float:
+    counts = np.array([len(g) for g in speedups_per_problem], np.int32)
+    flat = _f64(np.concatenate([np.asarray(g, np.float64) for g in speedups_per_problem]))
+    out = C.c_double(0.0)
+    _check(load_library().mc_median_of_max(flat.ctypes.data, counts.ctypes.data, counts.shape[0], C.addressof(out)))
+    return out.value
+
+
+def average_rank(max_speedup) -> np.ndarray:
+    t = _f64(max_speedup)
+    out = np.empty(t.shape[0], np.float64)
+    _check(load_library().mc_average_rank(t.ctypes.data, t.shape[0], t.shape[1], out.ctypes.data))
+    return out
+
 
 def _stream():
     import torch

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 _CSRC = os.path.join(_HERE, "csrc")
 HIP_SOURCES = ["runtime.hip", "ops.hip", "kernels_basic.hip", "kernels_mfma.hip", "kernels_gemm.hip", "kernels_attn.hip",
-               "kernels_prefill_attn.hip"]
+               "kernels_prefill_attn.hip", "search_host.hip"]
 LIB = os.path.join(_HERE, "libmaxcode_mi355x.so")
 
 

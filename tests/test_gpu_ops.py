@@ -263,6 +263,7 @@ def test_pack_tiled_roundtrip():
 @pytest.mark.parametrize("M,N,K,S", [
     (32, 256, 512, 1), (32, 256, 512, 2), (16, 3072, 2048, 0), (1, 128, 256, 1), (33, 128, 1024, 2),
     (64, 384, 768, 1), (5, 6144, 4096, 0), (32, 4096, 14336, 0),
+    (32, 128256, 4096, 0),         # the LM head of the 8B shape
     (65, 128, 256, 1), (200, 256, 512, 1), (130, 384, 1024, 1), (4096, 128, 256, 1),
     # 256-row-tile GEMM: ragged last row tile, a last band of fewer than 8 row tiles, padding ids
     (3000, 4096, 256, 1), (2300, 5632, 512, 1),

@@ -8,7 +8,8 @@ from paper_2601_05475_amd import binding, synth
 
 from gpu_common import (SAMPLE_MARGIN, assert_logits_close, check_against_oracle,
                         check_sampler_on_logits, oracle_shared, teacher_forced_gpu)
-from helpers import small_shape
+from helpers import oracle_config, small_shape
+from oracle import transformer as otf
 
 pytestmark = pytest.mark.gpu
 
@@ -221,6 +222,40 @@ def test_1b_shape_two_layer_twin():
     toks, topk = sess.sample(16, wl.temperature, wl.top_k, us, want_topk=True)
     for b in range(16):
         check_sampler_on_logits(steps[-1][b], wl.temperature, wl.top_k, us[b], toks[b], topk[b])
+
+
+def _as_f64(w):
+    if isinstance(w, dict):
+        return {k: _as_f64(v) for k, v in w.items()}
+    if isinstance(w, (list, tuple)):
+        return [_as_f64(v) for v in w]
+    return np.asarray(w, np.float64)
+
+
+@pytest.mark.timeout(1500)
+def test_8b_shape_layer_at_the_benchmark_launch_configuration():
+    """One layer of the 8B shape at full width (4096 wide, 32/8 heads of 128, FFN 14336) in the
+    configuration the benchmark times: 4096-token shared prefix, 32 candidates, 64-token pages,
+    2048-row prefill chunks, automatic key splits.  The vocabulary is cut to 32000 to keep the
+    oracle's float64 copies small (the LM-head shape itself is covered by an operation test).
+    Decode steps 1 and 2 for all candidates against the oracle."""
+    wl = synth.WORKLOADS["8b"]
+    base = wl.shape
+    s = synth.Shape("8b-L1-V32000", 1, base.d_model, base.n_q_heads, base.n_kv_heads, base.head_dim,
+                    base.d_ffn, 32000, base.rope_base, base.dtype, base.rms_eps)
+    w = synth.make_weights(s, wl.seed_weights)
+    prefix = synth.tokens(9, 1, (wl.prefix_len,), s.vocab)
+    suffix = synth.tokens(9, 2, (wl.n_cands, 2), s.vocab)
+    print("case: 8b layer twin", s, flush=True)
+    pl, steps, sess, _ = teacher_forced_gpu(s, w, prefix, suffix, wl.page_tokens, chunk_rows=2048,
+                                            max_suffix=wl.n_steps)
+    w64 = _as_f64(synth.weights_as_f32(w))          # converted once: the oracle would redo it per call
+    print("oracle: exact", flush=True)
+    want_pl, want = otf.forward_shared(oracle_config(s, exact=True), w64, prefix, suffix)
+    print("oracle: bf16 tensors", flush=True)
+    fl_pl, fl = otf.forward_shared(oracle_config(s, exact=False), w64, prefix, suffix)
+    assert_logits_close(pl[None], want_pl[None], "bf16", "prefix logits", fl_pl[None])
+    assert_logits_close(steps, want.transpose(1, 0, 2), "bf16", "decode logits", fl.transpose(1, 0, 2))
 
 
 # ---------------------------------------------------------------- growing the shared prefix
