@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 
 
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
@@ -108,13 +109,137 @@ def cpu_baseline(wl, weights, n_layers_sample=2, n_cands_sample=4):
                       f"{t_head:.1f} s head measured)"}
 
 
+def measured_copy_gbs(torch):
+    """Read + write rate of a plain device copy of 1 GiB (an elementwise kernel), GB/s."""
+    src = torch.zeros(256 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        torch.add(src, 1, out=dst)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        torch.add(src, 1, out=dst)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    del src, dst
+    return 2 * (1 << 30) / (ms * 1e-3) / 1e9
+
+
+def cpu_baseline_rerank(wl, weights, n_layers_sample=1, rows_sample=64):
+    """The oracle on a bounded sample of the scoring workload: the last `rows_sample` positions of
+    ONE candidate suffix (attending to random prefix + suffix keys of the real length) through
+    `n_layers_sample` layers; scaled linearly to all rows, candidates and layers.  The LM head is
+    needed for one row per candidate only and is left out."""
+    from oracle import transformer as otf
+    from paper_2601_05475_amd import synth
+    s = wl.shape
+    cfg = otf.Config(s.n_layers, s.d_model, s.n_q_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab,
+                     s.rope_base, s.rms_eps, "bf16")
+    P, Ls, B = wl.prefix_len, wl.n_steps, wl.n_cands
+    n_keys = P + Ls - rows_sample
+    layers = [{k: synth.bf16_bits_to_f32(v) for k, v in weights["layers"][l].items()} for l in range(n_layers_sample)]
+    kv = [(synth.bf16_bits_to_f32(synth.normal(7, 50 + l, (n_keys, s.n_kv_heads, s.head_dim), 0.0, 1.0, "bf16")).astype(np.float64),
+           synth.bf16_bits_to_f32(synth.normal(7, 80 + l, (n_keys, s.n_kv_heads, s.head_dim), 0.0, 1.0, "bf16")).astype(np.float64))
+          for l in range(n_layers_sample)]
+    x = synth.bf16_bits_to_f32(weights["embed"][synth.suffix_tokens(wl, 1, rows_sample)[0]]).astype(np.float64)
+    t0 = time.perf_counter()
+    for l in range(n_layers_sample):
+        x, _, _ = otf.layer_forward(cfg, layers[l], x, np.arange(n_keys, n_keys + rows_sample), kv[l][0], kv[l][1])
+    t = time.perf_counter() - t0
+    total = t / n_layers_sample * s.n_layers * (Ls / rows_sample) * B
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": B / total, "unit": "scored candidates/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"the last {rows_sample} of {Ls} suffix positions of one of {B} candidates through "
+                      f"{n_layers_sample} of {s.n_layers} layers ({t:.1f} s measured), scaled linearly to all "
+                      f"positions, candidates and layers; LM head (one row per candidate) left out"}
+
+
+def bench_rerank(args, torch, binding, synth):
+    """Scoring workload: B candidate suffixes of Ls tokens on the shared prefix, expected value of
+    the categorical reward read at each suffix end.  A step = one mc_score_candidates call."""
+    wl = synth.WORKLOADS[args.workload]
+    s = wl.shape if not args.layers else wl.shape.with_layers(args.layers)
+    B, P, Ls = wl.n_cands, wl.prefix_len, wl.n_steps
+    K = args.steps if args.steps_given else 3
+    W = args.warmup if args.warmup_given else 1
+    chunk = args.chunk_rows or 8192
+    t0 = time.perf_counter()
+    weights = synth.make_weights(s, wl.seed_weights)
+    t_gen = time.perf_counter() - t0
+    model = binding.Model(s, weights)
+    sess = binding.Session(model, P, B, Ls, wl.page_tokens, chunk_rows=chunk)
+    torch.cuda.synchronize()
+    prefix = synth.prefix_tokens(wl)
+    suffix = synth.suffix_tokens(wl)
+    lens = np.full(B, Ls, np.int32)
+    R = 8
+    ids = synth.reward_token_ids(wl, R)
+    vals = np.arange(R, dtype=np.float32)
+    t0 = time.perf_counter()
+    sess.prefill_shared(prefix)
+    sess.sync()
+    t_prefill = time.perf_counter() - t0
+    for _ in range(W):
+        sess.score_candidates(suffix, lens, ids, vals, 1.0)
+    sess.profile_begin("linear_gate_up", 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        sess.score_candidates(suffix, lens, ids, vals, 1.0)     # returns after the scores are on the host
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_gu, ms_gu = sess.profile_end()
+    sess.profile_begin("attn_prefill", 1)
+    sess.score_candidates(suffix, lens, ids, vals, 1.0)
+    n_at, ms_at = sess.profile_end()
+    rows = B * Ls
+    n_chunks = -(-rows // (chunk // Ls * Ls))
+    m_chunk = rows / n_chunks
+    gu_flops = 2.0 * m_chunk * (2 * s.d_ffn) * s.d_model
+    gu_us = ms_gu * 1e3 / max(n_gu, 1)
+    layer_flops = 2.0 * rows * s.d_model * ((s.n_q_heads + 2 * s.n_kv_heads) * s.head_dim + s.n_q_heads * s.head_dim + 3 * s.d_ffn)
+    attn_flops = 4.0 * s.n_q_heads * s.head_dim * B * Ls * (P + Ls / 2.0)          # per layer, causal
+    out = {
+        "metric": "scored candidates/s (8B-shape reranking: expected categorical reward at each suffix end)",
+        "value": B * K / elapsed, "unit": "candidates/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {s.n_layers} layers of the 8B shape; {B} suffixes of {Ls} tokens on a "
+                               f"shared prefix of {P}; {R} reward tokens; chunks of {chunk} rows",
+                   "n_cands": B, "prefix_len": P, "suffix_len": Ls, "page_tokens": wl.page_tokens},
+        "roofline": {"bound": "mfma", "kernel": "gemm256_kernel<true> (gate/up + SwiGLU)",
+                     "achieved": gu_flops / gu_us / 1e6, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gu_flops / gu_us / 1e6 / MFMA_PEAK_TFLOPS, "traffic": None,
+                     "launches_timed": n_gu, "avg_us": gu_us, "rows_per_launch": m_chunk},
+        "whole_pass": {"linear_flops": layer_flops * s.n_layers, "attention_flops": attn_flops * s.n_layers,
+                       "achieved_tflops": (layer_flops + attn_flops) * s.n_layers / (elapsed / K) / 1e12,
+                       "attention_ms_per_pass": ms_at, "attention_tflops": attn_flops * s.n_layers / (ms_at * 1e-3) / 1e12},
+        "prefill_s": t_prefill, "setup_s": {"generate_weights": t_gen},
+        "measured_copy_gbs": measured_copy_gbs(torch),
+    }
+    if args.layers:
+        out["invalid"] = "layer count overridden"
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_rerank(wl, weights)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=512)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="8b", choices=["8b", "1b"])
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="8b", choices=["8b", "1b", "32b", "8b-rerank"],
+                    help="8b (default): the headline decode workload; 1b, 32b: the same loop on the other "
+                         "decode configurations; 8b-rerank: the scoring workload")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (diagnosis only; marks the line invalid)")
+    ap.add_argument("--chunk-rows", type=int, default=0, help="rows per prefill / scoring chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (a kernel of known traffic "
@@ -123,11 +248,18 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
+    args.steps_given, args.warmup_given = args.steps is not None, args.warmup is not None
 
     import torch
     from paper_2601_05475_amd import binding, synth
     binding.load_library()                      # raises if the HIP library is not built
+    if args.workload == "8b-rerank":
+        return bench_rerank(args, torch, binding, synth)
     wl = synth.WORKLOADS[args.workload]
+    if args.steps is None:
+        args.steps = wl.n_steps
+    if args.warmup is None:
+        args.warmup = 8
     s = wl.shape if not args.layers else wl.shape.with_layers(args.layers)
     B, P = wl.n_cands, wl.prefix_len
     K, W = args.steps, args.warmup
@@ -140,7 +272,7 @@ def main():
     t_gen = time.perf_counter() - t0
     t0 = time.perf_counter()
     model = binding.Model(s, weights)
-    sess = binding.Session(model, P, B, wl.n_steps, wl.page_tokens, chunk_rows=2048)
+    sess = binding.Session(model, P, B, wl.n_steps, wl.page_tokens, chunk_rows=args.chunk_rows or 2048)
     torch.cuda.synchronize()
     t_upload = time.perf_counter() - t0
 
@@ -179,7 +311,17 @@ def main():
     # second pass (untimed): the decode-attention kernel, averaged over the same K steps
     sess.reset_candidates()
     sess.profile_begin("attn_decode", stride)
-    run_steps(K)
+    step_ms = {}
+    marks = sorted({1, K // 2, K} - {0})
+    for t in range(K):
+        if t + 1 in marks:                       # wall time of this one step, bracketed by syncs
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        sess.sample(B, wl.temperature, wl.top_k, us[t], want_tokens=False)
+        sess.decode_step(None, B)
+        if t + 1 in marks:
+            torch.cuda.synchronize()
+            step_ms[str(t + 1)] = (time.perf_counter() - t1) * 1e3
     n_at, ms_at = sess.profile_end()
     at_bytes = float(np.mean([attention_bytes(s, B, P, t + 1) for t in range(K)]))
 
@@ -188,7 +330,7 @@ def main():
     gu_gbs = gate_up_bytes(s, B) / gu_us / 1e3
     at_gbs = at_bytes / at_us / 1e3
     out = {
-        "metric": "generated tokens/s at B candidates (8B-shape decode); % HBM roofline attn",
+        "metric": f"generated tokens/s at B candidates ({args.workload.upper()}-shape decode); % HBM roofline attn",
         "value": B * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -203,7 +345,9 @@ def main():
         "roofline_attn": {"bound": "hbm", "kernel": "decode attention (all launches of one layer-step)",
                           "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
                           "traffic": None, "launches_timed": n_at, "avg_us": at_us},
+        "step_ms_at_suffix_len": step_ms,
         "prefill_s": t_prefill, "setup_s": {"generate_weights": t_gen, "upload_and_pack": t_upload},
+        "measured_copy_gbs": measured_copy_gbs(torch),
     }
     if args.layers:
         out["invalid"] = "layer count overridden"
