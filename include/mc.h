@@ -307,8 +307,8 @@ int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t
                            size_t workspace_bytes, void *out, int32_t out_tiled);
 
 /* Causal attention for many query rows (prefix prefill, candidate scoring); bf16, 64-token
- * pages, head_dim 64 or 128.  items: device int32 [n_items][4] = (first row, rows <= 32,
- * position of the first row, page-table row or -1): 32 consecutive positions of one sequence.
+ * pages, head_dim 64 or 128.  items: device int32 [n_items][4] = (first row, rows <= 64,
+ * position of the first row, page-table row or -1): up to 64 consecutive positions of one sequence.
  * A row at position p attends to keys 0..p: positions < prefix_len from the prefix pages (in
  * order), later ones from pages page_table[row][.] of the suffix pool.  q: [rows][Hq][hd];
  * out: [rows][Hq*hd], row-major or tiled (out_tiled = 1). */

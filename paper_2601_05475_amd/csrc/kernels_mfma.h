@@ -24,8 +24,8 @@ bool gemm256_supported(int M, int N, int K, bool swiglu);
 int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                    const void *w2, float *out, void *out_t);
 
-// Causal attention over many rows.  items[i] = (first row, rows <= 32, position of the first
-// row, page-table row or -1): 32 consecutive positions of one sequence.  Keys at positions
+// Causal attention over many rows.  items[i] = (first row, rows <= 64, position of the first
+// row, page-table row or -1): up to 64 consecutive positions of one sequence.  Keys at positions
 // < prefix_len come from the prefix pages, later ones from the sequence's suffix pages.
 struct PrefillAttnArgs {
   const void *q;                 // bf16 [rows][Hq][hd]

@@ -1,7 +1,10 @@
 // Causal attention for many query rows (prefix prefill and candidate scoring), bf16, gfx950 MFMA.
 //
-// A work item is 32 consecutive positions of one sequence, one KV head and up to four of its
-// query heads: wave w owns head 4 * hg + w of the group, the 32 positions are its MFMA columns.
+// A work item is up to 64 consecutive positions of one sequence, one KV head and up to four of
+// its query heads.  The workgroup has 8 waves: wave w owns head 4 * hg + w % 4 of the group and
+// positions 32 (w / 4) .. + 31 of the item, which are its MFMA columns.  Two waves per SIMD let
+// one wave's softmax run under the other's MFMAs, and the LDS only reaches its full read rate
+// with eight waves per CU.
 // Keys are streamed page by page (64 keys) through LDS and shared by the four waves: first the
 // shared-prefix pages that are visible to the block, then (scoring) the sequence's own suffix
 // pages.  Pages are stored in MFMA fragment order, so a page is copied to LDS as it is and an
@@ -36,47 +39,55 @@ template <int HD> struct PTile {
   static constexpr int K_ELEMS = PPG * HD, V_ELEMS = PPG * HD, PAGE_ELEMS = K_ELEMS + V_ELEMS;
   static constexpr int NF = HD / 16;          // 1 KB fragments per 32-key block (K and V alike)
   static constexpr int LDS_BYTES = 2 * PAGE_ELEMS * 2;
-  static constexpr int CPT = PPG * HD / 8 / 256;
+  static constexpr int CPT = PPG * HD / 8 / 512;
 };
 
 constexpr int kPrefillMaxPids = 1024;
 
 template <int HD>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(512)
 void prefill_attention_kernel(PrefillAttnArgs a) {
   using TL = PTile<HD>;
   extern __shared__ __attribute__((aligned(16))) unsigned char plds_raw[];
   bf16_t *lds = (bf16_t *)plds_raw;
   int *pids = (int *)(plds_raw + TL::LDS_BYTES);
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, h = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hw = wave & 3, half = wave >> 2;    // head within the group, half of the item's rows
   const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, G = Hq / Hkv, HG = (G + 3) / 4;
 
   int id = blockIdx.x;
   const int hg = id % HG; id /= HG;
   const int kvh = id % Hkv; id /= Hkv;
-  const int4 item = a.items[id];               // row_start, n_rows (<= 32), pos_start, table row
-  const int row_start = item.x, n_rows = item.y, pos_start = item.z, tab = item.w;
-  const int g = 4 * hg + wave;
-  const bool wave_active = g < G;               // uniform per wave
-  const int head = kvh * G + (wave_active ? g : 0);
-  const bool col_valid = col < n_rows;
+  const int4 item = a.items[id];               // row_start, n_rows (<= 64), pos_start, table row
+  const int n_rows = item.y, tab = item.w;
+  const int row_start = item.x + 32 * half;     // this wave's rows and their first position
+  const int pos_start = item.z + 32 * half;
+  const int my_rows = min(32, n_rows - 32 * half);
+  const int g = 4 * hg + hw;
+  const bool wave_active = g < G && my_rows > 0;   // uniform per wave
+  const int head = kvh * G + (g < G ? g : 0);
+  const bool col_valid = col < my_rows;
   const int my_pos = pos_start + (col_valid ? col : 0);
+  const int my_last = pos_start + my_rows - 1;     // last position of this wave's rows
 
   // visible keys: prefix [0, nA), then own suffix [0, nB) at absolute positions prefix_len + j
-  const int last_pos = pos_start + n_rows - 1;
+  const int last_pos = item.z + n_rows - 1;        // of the whole item: pages every wave helps to stage
   const int nA = min(a.prefix_len, last_pos + 1);
   const int nB = (tab >= 0 && last_pos >= a.prefix_len) ? last_pos - a.prefix_len + 1 : 0;
   const int nPA = (nA + PPG - 1) / PPG, nPB = (nB + PPG - 1) / PPG, n_pages = nPA + nPB;
   const int32_t *table = (nPB > 0) ? a.page_table + (size_t)tab * a.table_stride : nullptr;
   const bool pids_in_lds = nPB <= kPrefillMaxPids;
   if (nPB > 0 && pids_in_lds) {
-    for (int i = tid; i < nPB; i += 256) pids[i] = table[i];
+    for (int i = tid; i < nPB; i += 512) pids[i] = table[i];
     __syncthreads();
   }
 
   v4u qf[HD / 16];
   {
-    const bf16_t *qrow = (const bf16_t *)a.q + ((size_t)(row_start + (col_valid ? col : 0)) * Hq + head) * HD + 8 * h;
+    // a wave without rows reads the item's first row (its result is never stored)
+    const int qr = wave_active ? row_start + (col_valid ? col : 0) : item.x;
+    const bf16_t *qrow = (const bf16_t *)a.q + ((size_t)qr * Hq + head) * HD + 8 * h;
 #pragma unroll
     for (int c = 0; c < HD / 16; ++c) qf[c] = *(const v4u *)(qrow + 16 * c);
   }
@@ -100,7 +111,7 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
     const int page = in_a ? p : (pids_in_lds ? pids[p - nPA] : table[p - nPA]);
     const bf16_t *kp = (in_a ? kA : kB) + (size_t)page * page_stride + head_off;
     const bf16_t *vp = (in_a ? vA : vB) + (size_t)page * page_stride + head_off;
-    const size_t lane_off = real ? (size_t)tid * 8 : 0, step = real ? 256 * 8 : 0;
+    const size_t lane_off = real ? (size_t)tid * 8 : 0, step = real ? 512 * 8 : 0;
 #pragma unroll
     for (int i = 0; i < TL::CPT; ++i) {
       sk[stage][i] = *(const v4u *)(kp + lane_off + step * i);
@@ -111,7 +122,7 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
     bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
 #pragma unroll
     for (int i = 0; i < TL::CPT; ++i) {
-      const int ci = tid + 256 * i;
+      const int ci = tid + 512 * i;
       *(v4u *)(kt + ci * 8) = sk[stage][i];
       *(v4u *)(vt + ci * 8) = sv[stage][i];
     }
@@ -181,7 +192,7 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int nv = min(32, keys_here - 32 * blk);
-      if (nv > 0) process(pi & 1, blk, nv, abs_page + 32 * blk);
+      if (nv > 0 && abs_page + 32 * blk <= my_last) process(pi & 1, blk, nv, abs_page + 32 * blk);   // else all masked
     }
   };
 
@@ -232,7 +243,7 @@ static int launch_prefill_t(hipStream_t st, const PrefillAttnArgs &a) {
     attr_set = true;
   }
   const unsigned grid = (unsigned)a.n_items * a.n_kv_heads * HG;
-  prefill_attention_kernel<HD><<<grid, 256, lds, st>>>(a);
+  prefill_attention_kernel<HD><<<grid, 512, lds, st>>>(a);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }

@@ -650,10 +650,10 @@ static int prefill_range(mc_session *s, const int32_t *tokens, int n_tokens, int
     MC_TRY(upload(s, s->ptr<void>(L.row_pos), meta.data() + rows, (size_t)rows * 4));
     MC_TRY(upload(s, s->ptr<void>(L.row_page), meta.data() + 2 * rows, (size_t)rows * 4));
     MC_TRY(upload(s, s->ptr<void>(L.row_off), meta.data() + 3 * rows, (size_t)rows * 4));
-    // attention work items: 32 consecutive positions each
+    // attention work items: 64 consecutive positions each
     items.clear();
-    for (int r = 0; r < rows; r += 32) {
-      items.push_back(r); items.push_back(std::min(32, rows - r)); items.push_back(start + p0 + r); items.push_back(-1);
+    for (int r = 0; r < rows; r += 64) {
+      items.push_back(r); items.push_back(std::min(64, rows - r)); items.push_back(start + p0 + r); items.push_back(-1);
     }
     MC_TRY(upload(s, s->ptr<void>(L.items), items.data(), items.size() * 4));
     MC_TRY(run_layers(s, rows, PASS_PREFIX, start + p0 + rows, (int)items.size() / 4, &tail));
@@ -895,8 +895,8 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
     items.clear();
     for (int b = b0; b < b1; ++b) {
       const int len = suffix_lens[b];
-      for (int j = 0; j < len; j += 32) {
-        items.push_back(r + j); items.push_back(std::min(32, len - j));
+      for (int j = 0; j < len; j += 64) {
+        items.push_back(r + j); items.push_back(std::min(64, len - j));
         items.push_back(s->prefix_len + j); items.push_back(b - b0);
       }
       for (int j = 0; j < len; ++j, ++r) {
@@ -970,8 +970,8 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
     items.clear();
     int r = 0;
     for (int b = b0; b < b0 + nc; ++b) {
-      for (int j = 0; j < len; j += 32) {
-        items.push_back(r + j); items.push_back(std::min(32, len - j));
+      for (int j = 0; j < len; j += 64) {
+        items.push_back(r + j); items.push_back(std::min(64, len - j));
         items.push_back(s->prefix_len + t + j); items.push_back(b);
       }
       for (int j = 0; j < len; ++j, ++r) {

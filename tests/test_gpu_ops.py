@@ -313,7 +313,7 @@ def test_tiled_outputs_of_rmsnorm_and_attention():
 
 
 # ---------------------------------------------------------------- MFMA prefill / scoring attention
-def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False):
+def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False, item_rows=64):
     """seqs: list of (pos_start, n_rows); pos_start < P means a prefix chunk (keys = prefix
     only, P grows to cover it), pos_start >= P a scored suffix starting at P."""
     import torch
@@ -328,8 +328,8 @@ def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False):
     q = rnd(seed + 4, (rows, Hq, hd)); qd, qv = to_dev(q, "bf16")
     items, r0 = [], 0
     for si, (p0, n) in enumerate(seqs):
-        for j in range(0, n, 32):
-            items.append([r0 + j, min(32, n - j), p0 + j, si if scoring else -1])
+        for j in range(0, n, item_rows):
+            items.append([r0 + j, min(item_rows, n - j), p0 + j, si if scoring else -1])
         r0 += n
     it = torch.tensor(items, dtype=torch.int32, device="cuda")
     print("case: prefill attention", Hq, Hkv, hd, P, seqs, flush=True)
@@ -368,6 +368,15 @@ def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False):
 ])
 def test_attention_prefill_mfma(Hq, Hkv, hd, P, seqs, stride):
     worst = prefill_case(Hq, Hkv, hd, P, seqs, stride)
+    assert worst < 1.5e-2, worst
+
+
+@pytest.mark.parametrize("item_rows", [32, 48, 17])
+def test_attention_prefill_item_sizes(item_rows):
+    """Items shorter than 64 positions: the second half of the workgroup has fewer rows or none."""
+    worst = prefill_case(8, 2, 128, 150, [(150, 130), (150, 33)], item_rows=item_rows)
+    assert worst < 1.5e-2, worst
+    worst = prefill_case(8, 2, 64, 200, [(0, 200)], item_rows=item_rows)
     assert worst < 1.5e-2, worst
 
 
