@@ -139,6 +139,17 @@ int mc_promote_candidate(mc_session *s, int32_t cand);
  *    prefix, MC_ERR_OOM beyond max_suffix, MC_ERR_INVALID for a changed n_cands.  Asynchronous. */
 int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len);
 
+/* 1d. Candidates end at different lengths, and a value-guided search keeps only the promising
+ *    ones (Sec. 3.3).  mc_drop_candidates removes the n candidates cands[.] (ids as numbered when
+ *    the candidates were started, each still decoding, at least one other must stay): they take
+ *    no further part in mc_decode_step / mc_sample / mc_prefill_suffix, whose work (rows, KV
+ *    traffic) shrinks accordingly, and their pages count as released.  From then on those calls
+ *    are given the number of candidates still decoding, and every per-candidate array (tokens,
+ *    uniforms, sampled ids, logits rows) lists the survivors in ascending id order; results that
+ *    were pending for the survivors (logits, sampled tokens) stay valid.
+ *    mc_session_reset_candidates starts over with all candidates. */
+int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n);
+
 /* 2. One new token per candidate: appends its K/V to the candidate's current page
  *    and leaves logits [n_cands][vocab] on the device.  tokens: host [n_cands], or
  *    NULL to consume the tokens drawn by the latest mc_sample without leaving the

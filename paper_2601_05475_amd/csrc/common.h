@@ -119,6 +119,7 @@ struct DecodeAttnArgs {
   const void *k_prefix, *v_prefix, *k_suffix, *v_suffix;
   const int32_t *page_table;
   int32_t table_stride;
+  const int32_t *row_cand = nullptr;   // device: page-table row of each candidate row (nullptr: row r uses table row r)
   int32_t n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens;
   int32_t prefix_len, suffix_len;
   int32_t prefix_splits;         // 0 = automatic

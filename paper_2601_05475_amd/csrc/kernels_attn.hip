@@ -101,7 +101,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     blk_end = min(first_blk + it.suffix_bps, it.n_suffix_blocks);
     len = a.suffix_len;
     kpool = (const bf16_t *)a.k_suffix; vpool = (const bf16_t *)a.v_suffix;
-    table = a.page_table + (size_t)b_item * a.table_stride;
+    table = a.page_table + (size_t)(a.row_cand ? a.row_cand[b_item] : b_item) * a.table_stride;
     col0 = 0;
     n_cols = G;
   }

@@ -61,11 +61,12 @@ int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const v
 }
 
 // ---- decode attention: MFMA split-K kernel when the shape allows, else the generic kernel ---
-__global__ void fill_decode_rows_kernel(int B, int pos, int32_t *row_pos, int32_t *row_tab) {
+__global__ void fill_decode_rows_kernel(int B, int pos, const int32_t *__restrict__ row_cand,
+                                        int32_t *row_pos, int32_t *row_tab) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b < B) {
     row_pos[b] = pos;
-    row_tab[b] = b;
+    row_tab[b] = row_cand ? row_cand[b] : b;
   }
 }
 
@@ -84,7 +85,7 @@ int launch_attention_decode(hipStream_t st, int dtype, const DecodeAttnArgs &a) 
     MC_FAIL(MC_ERR_INVALID, "attention workspace too small");
   int32_t *row_pos = (int32_t *)a.workspace, *row_tab = row_pos + a.n_cands;
   fill_decode_rows_kernel<<<(a.n_cands + 63) / 64, 64, 0, st>>>(
-      a.n_cands, a.prefix_len + a.suffix_len - 1, row_pos, row_tab);
+      a.n_cands, a.prefix_len + a.suffix_len - 1, a.row_cand, row_pos, row_tab);
   MC_HIP(hipGetLastError());
   AttnArgs g;
   g.q = a.q; g.k_prefix = a.k_prefix; g.v_prefix = a.v_prefix; g.k_suffix = a.k_suffix;

@@ -232,7 +232,7 @@ constexpr int kProfCap = 8192;
 
 struct SessionLayout {
   size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
-      hlast, attn_ws, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
+      hlast, attn_ws, alive, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
       score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
   size_t total;
   // derived sizes
@@ -290,6 +290,7 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.attn_ws_bytes = decode_attention_ws_bytes(p.max_cands, c.n_q_heads, c.n_kv_heads, c.head_dim,
                                               p.max_prefix, p.max_suffix, pg);
   o.attn_ws = at(o.attn_ws_bytes);
+  o.alive = at((size_t)p.max_cands * 4);
   o.row_tok = at(R * 4);
   o.row_pos = at(R * 4);
   o.row_page = at(R * 4);
@@ -329,6 +330,10 @@ struct mc_session {
   // state
   int prefix_len = 0, n_cands = 0, suffix_len = 0, logits_state = LOGITS_NONE, logits_rows = 0;
   bool sampled_on_device = false, table_ready = false;
+  // candidates still decoding, ascending ids (all of 0..n_cands-1 until some are dropped); row r
+  // of every per-candidate buffer belongs to candidate alive[r]
+  std::vector<int32_t> alive;
+  bool dropped_any = false;
   int prefix_splits = 0;
   std::vector<int32_t> free_list;           // initial order of the pool
   std::vector<int32_t> host_table;          // [max_cands][pages_per_cand], pool-relative ids
@@ -388,14 +393,25 @@ static int download(mc_session *s, void *dst_host, const void *src_dev, size_t b
 }
 
 __global__ void decode_rows_kernel(int B, int pos, int page_slot, int off, int table_stride,
-                                   const int32_t *__restrict__ table, int32_t *row_pos,
-                                   int32_t *row_page, int32_t *row_off, int32_t *row_tab) {
+                                   const int32_t *__restrict__ table, const int32_t *__restrict__ alive,
+                                   int32_t *row_pos, int32_t *row_page, int32_t *row_off, int32_t *row_tab) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  const int cand = alive ? alive[b] : b;
   row_pos[b] = pos;
-  row_page[b] = table[(size_t)b * table_stride + page_slot];
+  row_page[b] = table[(size_t)cand * table_stride + page_slot];
   row_off[b] = off;
-  row_tab[b] = b;
+  row_tab[b] = cand;
+}
+
+// dst[r] = src[idx[r]] for r < n (idx ascending, so in place is safe when done by one thread each
+// after all reads: the kernel reads everything first)
+__global__ void compact_i32_kernel(int n, const int32_t *__restrict__ idx, int32_t *data) {
+  __shared__ int32_t tmp[1024];
+  const int r = threadIdx.x;
+  if (r < n) tmp[r] = data[idx[r]];
+  __syncthreads();
+  if (r < n) data[r] = tmp[r];
 }
 
 __global__ void copy_row_kernel(int n, const float *__restrict__ src, float *__restrict__ dst) {
@@ -462,6 +478,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       a.head_dim = c.head_dim; a.page_tokens = s->p.page_tokens;
       a.prefix_len = s->prefix_len; a.suffix_len = s->suffix_len + 1;
       a.prefix_splits = s->prefix_splits;
+      a.row_cand = s->dropped_any ? row_tab : nullptr;
       a.workspace = s->ptr<void>(L.attn_ws); a.workspace_bytes = L.attn_ws_bytes; a.out = ao;
       a.out_tiled = tl;
       ProfScope ps(s, MC_K_ATTN_DECODE);
@@ -616,6 +633,8 @@ extern "C" int mc_session_reset_candidates(mc_session *s) {
   s->suffix_len = 0;
   s->sampled_on_device = false;
   s->table_ready = false;
+  s->alive.clear();
+  s->dropped_any = false;
   std::fill(s->host_table.begin(), s->host_table.end(), -1);
   if (s->prefix_len > 0) {
     s->logits_state = LOGITS_PREFIX;
@@ -729,6 +748,8 @@ extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
   if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
   if (s->n_cands < 1 || s->suffix_len < 1) MC_FAIL(MC_ERR_STATE, "mc_promote_candidate: no candidate has decoded a token");
   if (cand < 0 || cand >= s->n_cands) MC_FAIL(MC_ERR_INVALID, "candidate %d outside [0, %d)", cand, s->n_cands);
+  const int ri = (int)(std::find(s->alive.begin(), s->alive.end(), cand) - s->alive.begin());
+  if (ri >= (int)s->alive.size()) MC_FAIL(MC_ERR_INVALID, "candidate %d was dropped", cand);
   const int t = s->suffix_len, P = s->prefix_len;
   if (t > s->p.max_prefix - P)
     MC_FAIL(MC_ERR_OOM, "prefix of %d + suffix of %d tokens exceeds max_prefix %d", P, t, s->p.max_prefix);
@@ -745,9 +766,9 @@ extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
                                                            L.n_prefix_pages, row, c.n_kv_heads, c.head_dim, s->p.page_tokens, P);
   MC_HIP(hipGetLastError());
   // the candidate's last logits become the logits of the last prefix position
-  const bool have_logits = s->logits_state == LOGITS_CANDS && s->logits_rows == s->n_cands;
+  const bool have_logits = s->logits_state == LOGITS_CANDS && s->logits_rows == (int)s->alive.size();
   if (have_logits)
-    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.prefix_logits), s->ptr<float>(L.logits) + (size_t)cand * c.vocab,
+    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.prefix_logits), s->ptr<float>(L.logits) + (size_t)ri * c.vocab,
                           (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, s->stream));
   s->prefix_len = P + t;
   mc_session_reset_candidates(s);
@@ -756,6 +777,26 @@ extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
     s->logits_rows = 0;
   }
   return MC_OK;
+}
+
+// The number of candidates is fixed by the first call that names it; from then on calls name the
+// number still decoding.
+static int check_cand_count(mc_session *s, int n_cands) {
+  if (n_cands < 1 || n_cands > s->p.max_cands)
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
+  if (s->n_cands && n_cands != (int)s->alive.size())
+    MC_FAIL(MC_ERR_INVALID, "n_cands %d, but %d candidates are decoding (%d were started)", n_cands,
+            (int)s->alive.size(), s->n_cands);
+  return MC_OK;
+}
+static void fix_cands(mc_session *s, int n_cands) {
+  if (s->n_cands) return;
+  s->n_cands = n_cands;
+  s->alive.resize(n_cands);
+  for (int b = 0; b < n_cands; ++b) s->alive[b] = b;
+}
+static void unfix_cands(mc_session *s, int saved_total) {
+  if (saved_total == 0) { s->n_cands = 0; s->alive.clear(); }
 }
 
 // Page ids are a pure function of (candidate, page slot) under the lock-step rule: at the
@@ -776,10 +817,7 @@ static int ensure_page_table(mc_session *s, int n_cands) {
 extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_cands) {
   if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
   if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_decode_step before mc_prefill_shared");
-  if (n_cands < 1 || n_cands > s->p.max_cands)
-    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
-  if (s->n_cands && n_cands != s->n_cands)
-    MC_FAIL(MC_ERR_INVALID, "n_cands %d differs from the %d fixed earlier", n_cands, s->n_cands);
+  MC_TRY(check_cand_count(s, n_cands));
   if (s->suffix_len >= s->p.max_suffix) MC_FAIL(MC_ERR_OOM, "suffix is full (%d tokens): page pool exhausted", s->suffix_len);
   const mc_config &c = s->m->cfg;
   if (tokens) MC_TRY(check_tokens(c, tokens, n_cands));
@@ -787,23 +825,23 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   MC_HIP(hipSetDevice(s->m->device));
   const SessionLayout &L = s->lay;
   const int pg = s->p.page_tokens, t = s->suffix_len;
-  MC_TRY(ensure_page_table(s, n_cands));
+  const int saved_n = s->n_cands;
+  fix_cands(s, n_cands);
+  if (int rc0 = ensure_page_table(s, s->n_cands)) { unfix_cands(s, saved_n); return rc0; }
   if (tokens) MC_TRY(upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4));
   else MC_HIP(hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4, hipMemcpyDeviceToDevice, s->stream));
   decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
       n_cands, s->prefix_len + t, t / pg, t % pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
-      s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
+      s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
       s->ptr<int32_t>(L.row_tab));
   MC_HIP(hipGetLastError());
   int tail = 0;
-  const int saved_n = s->n_cands;
-  s->n_cands = n_cands;
   int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, 0, &tail);
   if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
-  if (rc != MC_OK) { s->n_cands = saved_n; return rc; }
+  if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
   if (t % pg == 0)
-    for (int b = 0; b < n_cands; ++b)
-      s->host_table[(size_t)b * L.pages_per_cand + t / pg] = s->free_list[(size_t)(t / pg) * n_cands + b];
+    for (int b : s->alive)
+      s->host_table[(size_t)b * L.pages_per_cand + t / pg] = s->free_list[(size_t)(t / pg) * s->n_cands + b];
   s->suffix_len = t + 1;
   s->logits_state = LOGITS_CANDS;
   s->logits_rows = n_cands;
@@ -816,10 +854,7 @@ extern "C" int mc_sample(mc_session *s, int32_t n_cands, float temperature, int3
   if (!s || !uniforms) MC_FAIL(MC_ERR_INVALID, "session / uniforms is NULL");
   if (s->logits_state != LOGITS_PREFIX && s->logits_state != LOGITS_CANDS)
     MC_FAIL(MC_ERR_STATE, "mc_sample without pending logits (call mc_prefill_shared or mc_decode_step first)");
-  if (n_cands < 1 || n_cands > s->p.max_cands)
-    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
-  if (s->n_cands && n_cands != s->n_cands)
-    MC_FAIL(MC_ERR_INVALID, "n_cands %d differs from the %d fixed earlier", n_cands, s->n_cands);
+  MC_TRY(check_cand_count(s, n_cands));
   if (!isfinite(temperature)) MC_FAIL(MC_ERR_INVALID, "temperature is not finite");
   for (int b = 0; b < n_cands; ++b)
     if (!(uniforms[b] >= 0.f && uniforms[b] < 1.f)) MC_FAIL(MC_ERR_INVALID, "uniforms[%d] = %g outside [0, 1)", b, uniforms[b]);
@@ -839,7 +874,7 @@ extern "C" int mc_sample(mc_session *s, int32_t n_cands, float temperature, int3
                          out_topk_ids ? s->ptr<int32_t>(L.topk) : nullptr));
   }
   s->sampled_on_device = true;
-  s->n_cands = n_cands;
+  fix_cands(s, n_cands);
   if (out_tokens || out_topk_ids) {
     if (out_tokens) MC_TRY(download(s, out_tokens, s->ptr<void>(L.samp_tok), (size_t)n_cands * 4));
     if (out_topk_ids) MC_TRY(download(s, out_topk_ids, s->ptr<void>(L.topk), (size_t)n_cands * k * 4));
@@ -941,13 +976,52 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
   return MC_OK;
 }
 
+extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n) {
+  if (!s || !cands) MC_FAIL(MC_ERR_INVALID, "session / cands is NULL");
+  if (s->n_cands < 1) MC_FAIL(MC_ERR_STATE, "mc_drop_candidates: no candidates");
+  const int old_n = (int)s->alive.size();
+  if (n < 1 || n >= old_n) MC_FAIL(MC_ERR_INVALID, "n %d outside [1, %d): at least one candidate must stay", n, old_n);
+  std::vector<char> gone(s->n_cands, 0);
+  for (int i = 0; i < n; ++i) {
+    const int b = cands[i];
+    if (b < 0 || b >= s->n_cands || gone[b] || std::find(s->alive.begin(), s->alive.end(), b) == s->alive.end())
+      MC_FAIL(MC_ERR_INVALID, "cands[%d] = %d is not a candidate that is still decoding (or is repeated)", i, b);
+    gone[b] = 1;
+  }
+  MC_HIP(hipSetDevice(s->m->device));
+  const mc_config &c = s->m->cfg;
+  const SessionLayout &L = s->lay;
+  std::vector<int32_t> keep_rows, new_alive;
+  for (int r = 0; r < old_n; ++r)
+    if (!gone[s->alive[r]]) { keep_rows.push_back(r); new_alive.push_back(s->alive[r]); }
+  const int new_n = (int)new_alive.size();
+  // pending per-candidate results move up to the rows of the survivors (ascending, so a row is
+  // never overwritten before it has been copied)
+  if (s->logits_state == LOGITS_CANDS && s->logits_rows == old_n)
+    for (int r = 0; r < new_n; ++r)
+      if (keep_rows[r] != r)
+        MC_HIP(hipMemcpyAsync(s->ptr<float>(L.logits) + (size_t)r * c.vocab, s->ptr<float>(L.logits) + (size_t)keep_rows[r] * c.vocab,
+                              (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, s->stream));
+  if (s->sampled_on_device) {
+    if (old_n > 1024) MC_FAIL(MC_ERR_UNSUPPORTED, "more than 1024 candidates");
+    MC_TRY(upload(s, s->ptr<void>(L.last_idx), keep_rows.data(), (size_t)new_n * 4));
+    compact_i32_kernel<<<1, 1024, 0, s->stream>>>(new_n, s->ptr<int32_t>(L.last_idx), s->ptr<int32_t>(L.samp_tok));
+    MC_HIP(hipGetLastError());
+  }
+  MC_TRY(upload(s, s->ptr<void>(L.alive), new_alive.data(), (size_t)new_n * 4));
+  for (int b = 0; b < s->n_cands; ++b)
+    if (gone[b])
+      for (int p = 0; p < L.pages_per_cand; ++p) s->host_table[(size_t)b * L.pages_per_cand + p] = -1;
+  s->alive = new_alive;
+  s->dropped_any = true;
+  if (s->logits_state == LOGITS_CANDS) s->logits_rows = new_n;
+  return MC_OK;
+}
+
 extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len) {
   if (!s || !suffix_tokens) MC_FAIL(MC_ERR_INVALID, "session / suffix_tokens is NULL");
   if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_prefill_suffix before mc_prefill_shared");
-  if (n_cands < 1 || n_cands > s->p.max_cands)
-    MC_FAIL(MC_ERR_INVALID, "n_cands %d outside [1, %d]", n_cands, s->p.max_cands);
-  if (s->n_cands && n_cands != s->n_cands)
-    MC_FAIL(MC_ERR_INVALID, "n_cands %d differs from the %d fixed earlier", n_cands, s->n_cands);
+  MC_TRY(check_cand_count(s, n_cands));
   const int t = s->suffix_len;
   if (len < 1) MC_FAIL(MC_ERR_INVALID, "len %d < 1", len);
   if (len > s->p.max_suffix - t)
@@ -957,29 +1031,31 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
   MC_HIP(hipSetDevice(s->m->device));
   const SessionLayout &L = s->lay;
   const int pg = s->p.page_tokens;
-  MC_TRY(ensure_page_table(s, n_cands));
-  auto page_of = [&](int b, int slot) { return s->free_list[(size_t)slot * n_cands + b]; };
+  const int saved_n = s->n_cands;
+  fix_cands(s, n_cands);
+  if (int rc0 = ensure_page_table(s, s->n_cands)) { unfix_cands(s, saved_n); return rc0; }
+  const int n_total = s->n_cands;
+  auto page_of = [&](int cand, int slot) { return s->free_list[(size_t)slot * n_total + cand]; };
   std::vector<int32_t> tok, pos, page, off, tab, last, items;
   const int per_chunk = std::max(1, s->chunk_rows / len);          // whole candidates per chunk
-  const int saved_n = s->n_cands;
-  s->n_cands = n_cands;
   for (int b0 = 0; b0 < n_cands; b0 += per_chunk) {
     const int nc = std::min(per_chunk, n_cands - b0), rows = nc * len;
     tok.resize(rows); pos.resize(rows); page.resize(rows); off.resize(rows); tab.resize(rows);
     last.resize(nc);
     items.clear();
     int r = 0;
-    for (int b = b0; b < b0 + nc; ++b) {
+    for (int b = b0; b < b0 + nc; ++b) {         // b: row among the candidates still decoding
+      const int cand = s->alive[b];
       for (int j = 0; j < len; j += 64) {
         items.push_back(r + j); items.push_back(std::min(64, len - j));
-        items.push_back(s->prefix_len + t + j); items.push_back(b);
+        items.push_back(s->prefix_len + t + j); items.push_back(cand);
       }
       for (int j = 0; j < len; ++j, ++r) {
         tok[r] = suffix_tokens[(size_t)b * len + j];
         pos[r] = s->prefix_len + t + j;
-        page[r] = page_of(b, (t + j) / pg);
+        page[r] = page_of(cand, (t + j) / pg);
         off[r] = (t + j) % pg;
-        tab[r] = b;
+        tab[r] = cand;
       }
       last[b - b0] = r - 1;
     }
@@ -993,10 +1069,10 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
     int tail = 0;
     if (rc == MC_OK) rc = run_layers(s, rows, PASS_SUFFIX, s->prefix_len, (int)items.size() / 4, &tail);
     if (rc == MC_OK) rc = lm_head(s, rows, tail, nc, true, s->ptr<float>(L.logits) + (size_t)b0 * c.vocab);
-    if (rc != MC_OK) { s->n_cands = saved_n; return rc; }
+    if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
   }
   for (int slot = t / pg; slot <= (t + len - 1) / pg; ++slot)
-    for (int b = 0; b < n_cands; ++b) s->host_table[(size_t)b * L.pages_per_cand + slot] = page_of(b, slot);
+    for (int b : s->alive) s->host_table[(size_t)b * L.pages_per_cand + slot] = page_of(b, slot);
   s->suffix_len = t + len;
   s->logits_state = LOGITS_CANDS;
   s->logits_rows = n_cands;
@@ -1021,9 +1097,10 @@ extern "C" int mc_debug_page_table(mc_session *s, int32_t *out, int32_t *n_pages
   const int held = (s->suffix_len + s->p.page_tokens - 1) / s->p.page_tokens;
   if (max_pages < held) MC_FAIL(MC_ERR_INVALID, "max_pages %d < %d pages held", max_pages, held);
   for (int b = 0; b < s->p.max_cands; ++b) {
-    n_pages[b] = b < s->n_cands ? held : 0;
+    const bool holds = std::find(s->alive.begin(), s->alive.end(), b) != s->alive.end();
+    n_pages[b] = holds ? held : 0;
     for (int p = 0; p < max_pages; ++p)
-      out[(size_t)b * max_pages + p] = (b < s->n_cands && p < held) ? s->host_table[(size_t)b * s->lay.pages_per_cand + p] : -1;
+      out[(size_t)b * max_pages + p] = (holds && p < held) ? s->host_table[(size_t)b * s->lay.pages_per_cand + p] : -1;
   }
   return MC_OK;
 }

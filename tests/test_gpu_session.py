@@ -389,3 +389,84 @@ def test_prefill_suffix_then_decode(kw, dtype):
     tab, n = sess.page_table()
     ref = opaging.page_tables(B, n0 + n1 + n2, kw["pg"], range(sess.pool_pages()))
     np.testing.assert_array_equal(tab[:, :ref.shape[1]], ref)
+
+
+# ---------------------------------------------------------------- candidates that stop early
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4), "f32"),
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64), "bf16"),
+    (dict(L=2, d=256, Hq=8, Hkv=2, hd=128, F=512, V=1024, pg=64), "bf16"),
+])
+def test_drop_candidates_midway(kw, dtype):
+    """Candidates are independent sequences: dropping some leaves the others' logits what they
+    were (the oracle's), while rows, page bookkeeping and pending sampled tokens follow the
+    survivors.  70 steps cross a 64-token page boundary after the first drop."""
+    s = small_shape("drop", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 82)
+    P, B, N = 90, 6, 70
+    prefix = synth.tokens(11, 1, (P,), s.vocab)
+    suffix = synth.tokens(11, 2, (B, N), s.vocab)
+    print("case: drop candidates", kw, dtype, flush=True)
+    model = binding.Model(s, w)
+    ref = binding.Session(model, P + N, B, N, kw["pg"])
+    ref.prefill_shared(prefix)
+    full = _decode_all(ref, suffix)                                  # [N, B, V]
+    sess = binding.Session(model, P + N, B, N, kw["pg"])
+    sess.prefill_shared(prefix)
+    alive = list(range(B))
+    drops = {3: [1, 4], 66: [0]}
+    tol = 0 if dtype == "f32" else 3e-2
+    for t in range(N):
+        if t in drops:
+            before = sess.logits(len(alive))
+            sess.drop_candidates(drops[t])
+            keep = [i for i, b in enumerate(alive) if b not in drops[t]]
+            alive = [b for b in alive if b not in drops[t]]
+            np.testing.assert_array_equal(sess.logits(len(alive)), before[keep])   # pending rows moved up
+            with pytest.raises(binding.McError):
+                sess.decode_step(suffix[:, t])                      # the old count is refused
+            with pytest.raises(binding.McError):
+                sess.drop_candidates(drops[t][:1])                  # already gone
+        sess.decode_step(suffix[alive, t])
+        got = sess.logits(len(alive))
+        np.testing.assert_allclose(got, full[t][alive], rtol=0, atol=tol * np.abs(full[t]).max() + 0.0)
+    want_pl, want = oracle_shared(s, w, prefix, suffix[alive][:, :N])
+    fl = oracle_shared(s, w, prefix, suffix[alive], exact=False)[1] if dtype == "bf16" else None
+    assert_logits_close(got[None], want[-1:], dtype, "survivors, last step", None if fl is None else fl[-1:])
+    tab, n = sess.page_table()
+    held = -(-N // kw["pg"])
+    assert [int(x) for x in n[:B]] == [held if b in alive else 0 for b in range(B)]
+    ref_tab = opaging.page_tables(B, N, kw["pg"], range(sess.pool_pages()))
+    for b in alive:
+        np.testing.assert_array_equal(tab[b, :held], ref_tab[b])
+    # a survivor can be promoted, a dropped candidate cannot
+    with pytest.raises(binding.McError):
+        sess.promote_candidate(1)
+    sess.promote_candidate(alive[-1])
+    np.testing.assert_array_equal(sess.logits(1)[0], got[-1])
+
+
+def test_drop_candidates_with_tokens_pending_on_the_device(tiny):
+    wl, w = tiny
+    s = wl.shape
+    prefix = synth.prefix_tokens(wl, 40)
+    model = binding.Model(s, w)
+    B = 4
+    us = synth.step_uniforms(wl, B, 2)
+    a = binding.Session(model, 40, B, 8, wl.page_tokens)
+    b = binding.Session(model, 40, B, 8, wl.page_tokens)
+    for sess in (a, b):
+        sess.prefill_shared(prefix)
+    toks = a.sample(B, wl.temperature, wl.top_k, us[0])
+    b.sample(B, wl.temperature, wl.top_k, us[0], want_tokens=False)   # ids stay on the device
+    a.decode_step(toks)
+    b.decode_step(None, B)
+    toks = a.sample(B, wl.temperature, wl.top_k, us[1])
+    b.sample(B, wl.temperature, wl.top_k, us[1], want_tokens=False)
+    a.drop_candidates([0, 2])
+    b.drop_candidates([0, 2])
+    a.decode_step(toks[[1, 3]])
+    b.decode_step(None, 2)
+    np.testing.assert_array_equal(a.logits(2), b.logits(2))
+    with pytest.raises(binding.McError):
+        a.drop_candidates([1, 3])                                     # one candidate must stay
