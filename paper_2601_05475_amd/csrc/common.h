@@ -140,12 +140,27 @@ int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a,
                   float *out, int n_splits, int tiled);
 int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
                          const void *wg, const void *wu, void *out, int tiled);
-int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst);
+// interleave_hd > 0: within every group of interleave_hd rows, destination row 2i takes source
+// row i and destination row 2i + 1 source row i + interleave_hd / 2 (the two members of a rotary
+// pair become neighbours)
+int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst, int interleave_hd = 0);
+
+// cos / sin of pos * base^(-2i/hd) in double for pos < n_pos, i < hd / 2: table[pos * hd/2 + i]
+int launch_rope_table(hipStream_t st, int n_pos, int hd, double rope_base, double2 *table);
+
+// Where the fused QKV layer puts its result (few-row bf16 path): rotated queries, and keys /
+// values straight into their page slots.
+struct RopeOut {
+  const int32_t *row_pos, *row_page, *row_off;   // device, per row
+  void *q_out, *k_pages, *v_pages;
+  const double2 *table;                          // launch_rope_table
+  int32_t Hq, Hkv, hd, pg;
+};
 bool tiled_shapes_ok(int M, int N, int K);
 int launch_rope_kv(hipStream_t st, int dtype, int rows, int Hq, int Hkv, int hd, int page_tokens,
                    double rope_base, const float *qkv, int n_splits, const int32_t *row_pos,
                    const int32_t *row_page, const int32_t *row_off, void *q_out, void *k_pages,
-                   void *v_pages);
+                   void *v_pages, const double2 *table = nullptr, int qk_interleaved = 0);
 int launch_attention_generic(hipStream_t st, int dtype, const AttnArgs &a);
 size_t decode_attention_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int prefix_len,
                                  int suffix_len, int page_tokens);

@@ -277,14 +277,34 @@ int launch_linear_swiglu_generic(hipStream_t st, int dtype, int M, int N, int K,
 }
 
 // ------------------------------------------------------------------ RoPE + KV page write
+__global__ void rope_table_kernel(int n_pos, int half, int hd, double rope_base, double2 *__restrict__ table) {
+  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= (size_t)n_pos * half) return;
+  const int pos = (int)(e / half), i = (int)(e % half);
+  double sn, cs;
+  sincos((double)pos * pow(rope_base, -2.0 * (double)i / (double)hd), &sn, &cs);
+  table[e] = make_double2(cs, sn);
+}
+
+int launch_rope_table(hipStream_t st, int n_pos, int hd, double rope_base, double2 *table) {
+  const size_t n = (size_t)n_pos * (hd / 2);
+  if (n == 0) return MC_OK;
+  rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(n_pos, hd / 2, hd, rope_base, table);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
 // One block per (row, head).  Heads 0..Hq-1 are queries, then Hkv key heads, then Hkv value
-// heads.  The angle pos * base^(-2i/hd) and its sine/cosine are taken in double.
+// heads.  The angle pos * base^(-2i/hd) and its sine/cosine are taken in double (from the table
+// of the same expressions when one is given).  qk_interleaved: coordinate i of a query / key head
+// sits at 2i and coordinate i + hd/2 at 2i + 1 of the input row (see launch_pack_tiled).
 template <typename T>
 __global__ __launch_bounds__(64) void rope_kv_kernel(
     int rows, int Hq, int Hkv, int hd, int pg, double rope_base,
     const float *__restrict__ qkv, int n_splits, const int32_t *__restrict__ row_pos,
     const int32_t *__restrict__ row_page, const int32_t *__restrict__ row_off,
-    T *__restrict__ q_out, T *__restrict__ k_pages, T *__restrict__ v_pages) {
+    T *__restrict__ q_out, T *__restrict__ k_pages, T *__restrict__ v_pages,
+    const double2 *__restrict__ table, int qk_interleaved) {
   const int r = blockIdx.x, h = blockIdx.y;
   const int nqkv = (Hq + 2 * Hkv) * hd, half = hd >> 1;
   const size_t sstride = (size_t)rows * nqkv;
@@ -298,12 +318,18 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(
     const int key = row_off[r];
     for (int i = threadIdx.x; i < half; i += 64) {
       float lo = 0.f, hi = 0.f;
+      const int at_l = qk_interleaved ? 2 * i : i, at_h = qk_interleaved ? 2 * i + 1 : i + half;
       for (int s = 0; s < n_splits; ++s) {
-        lo += src[s * sstride + i];
-        hi += src[s * sstride + i + half];
+        lo += src[s * sstride + at_l];
+        hi += src[s * sstride + at_h];
       }
       double sn, cs;
-      sincos(pos * pow(rope_base, -2.0 * (double)i / (double)hd), &sn, &cs);
+      if (table) {
+        const double2 t = table[(size_t)row_pos[r] * half + i];
+        cs = t.x; sn = t.y;
+      } else {
+        sincos(pos * pow(rope_base, -2.0 * (double)i / (double)hd), &sn, &cs);
+      }
       const size_t at_lo = (h < Hq) ? (size_t)i : k_elem_offset(key, i, pg, hd);
       const size_t at_hi = (h < Hq) ? (size_t)(i + half) : k_elem_offset(key, i + half, pg, hd);
       dst[at_lo] = Cvt<T>::from_f32((float)((double)lo * cs - (double)hi * sn));
@@ -324,18 +350,19 @@ __global__ __launch_bounds__(64) void rope_kv_kernel(
 int launch_rope_kv(hipStream_t st, int dtype, int rows, int Hq, int Hkv, int hd, int page_tokens,
                    double rope_base, const float *qkv, int n_splits, const int32_t *row_pos,
                    const int32_t *row_page, const int32_t *row_off, void *q_out, void *k_pages,
-                   void *v_pages) {
+                   void *v_pages, const double2 *table, int qk_interleaved) {
   if (rows <= 0) return MC_OK;
   dim3 grid(rows, Hq + 2 * Hkv);
   if (dtype == MC_F32)
     rope_kv_kernel<float><<<grid, 64, 0, st>>>(rows, Hq, Hkv, hd, page_tokens, rope_base, qkv,
                                                n_splits, row_pos, row_page, row_off,
-                                               (float *)q_out, (float *)k_pages, (float *)v_pages);
+                                               (float *)q_out, (float *)k_pages, (float *)v_pages,
+                                               table, qk_interleaved);
   else
     rope_kv_kernel<bf16_t><<<grid, 64, 0, st>>>(rows, Hq, Hkv, hd, page_tokens, rope_base, qkv,
                                                 n_splits, row_pos, row_page, row_off,
                                                 (bf16_t *)q_out, (bf16_t *)k_pages,
-                                                (bf16_t *)v_pages);
+                                                (bf16_t *)v_pages, table, qk_interleaved);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }

@@ -10,8 +10,11 @@ namespace mc {
 // w2 != nullptr selects the SwiGLU form (out_t = silu(a wg^T) * (a wu^T), bf16, tiled).
 bool skinny_linear_supported(int M, int N, int K);
 int skinny_linear_splits(int M, int N, int K);
+// rope != nullptr: the fused QKV layer (one K split): w has the rows of every query / key head
+// interleaved (launch_pack_tiled), and the result goes where *rope says instead of to `out`.
 int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                         const void *w2, float *out, void *out_t, int n_splits);
+                         const void *w2, float *out, void *out_t, int n_splits,
+                         const RopeOut *rope = nullptr);
 
 // Many-row GEMM: 1 split; fp32 out, or the SwiGLU form with bf16 out.
 bool gemm_supported(int M, int N, int K);

@@ -49,7 +49,7 @@ __device__ inline v4u load_stream(const bf16_t *p) {
 
 // ---- row-major -> tiled repack (one thread per 16-byte chunk of the destination) -----------
 __global__ void pack_tiled_kernel(int rows, int rows_pad, int K, const bf16_t *__restrict__ src,
-                                  bf16_t *__restrict__ dst) {
+                                  bf16_t *__restrict__ dst, int interleave_hd) {
   const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t total = (size_t)rows_pad * K / 8;
   if (chunk >= total) return;
@@ -58,17 +58,24 @@ __global__ void pack_tiled_kernel(int rows, int rows_pad, int K, const bf16_t *_
   const int U = K >> 6;
   const int rt = (int)(blk / U), u = (int)(blk % U);
   const int row = 32 * rt + (lane & 31), k = 64 * u + 32 * (lane >> 5) + 8 * c;
+  int srow = row;
+  if (interleave_hd > 0) {                      // destination row 2i <- i, 2i + 1 <- i + hd / 2
+    const int jp = row % interleave_hd;
+    srow = row - jp + (jp >> 1) + ((jp & 1) ? interleave_hd / 2 : 0);
+  }
   v4u v = make_v4u(0, 0, 0, 0);
-  if (row < rows) v = *(const v4u *)(src + (size_t)row * K + k);
+  if (row < rows) v = *(const v4u *)(src + (size_t)srow * K + k);
   *(v4u *)(dst + chunk * 8) = v;
 }
 
-int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst) {
+int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *dst, int interleave_hd) {
   if (rows <= 0) return MC_OK;
   if (K % 64) MC_FAIL(MC_ERR_UNSUPPORTED, "tiled layout needs K %% 64 == 0 (K = %d)", K);
+  if (interleave_hd < 0 || (interleave_hd > 0 && (interleave_hd % 2 || rows % interleave_hd)))
+    MC_FAIL(MC_ERR_INVALID, "row interleave of %d does not fit %d rows", interleave_hd, rows);
   const int rows_pad = (rows + 31) / 32 * 32;
   const size_t chunks = (size_t)rows_pad * K / 8;
-  pack_tiled_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(rows, rows_pad, K, (const bf16_t *)src, (bf16_t *)dst);
+  pack_tiled_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(rows, rows_pad, K, (const bf16_t *)src, (bf16_t *)dst, interleave_hd);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }
@@ -79,11 +86,15 @@ int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *ds
 // and meet in LDS.  Loads run two units (2 x 4 KB per operand) ahead of the MFMAs.
 // MB = number of 32-row tiles of the activations (M <= 32 MB).
 // =====================================================================================
-template <int MB, bool SWIGLU>
+// ROPE (the fused QKV layer, one K split): instead of storing the sums, rotate the query / key
+// coordinates by the row's position and write queries (bf16, row-major), keys and values (into
+// their page slots).  The weight rows of every query / key head are interleaved so that the two
+// members of a rotary pair are neighbours in a thread's four consecutive outputs.
+template <int MB, bool SWIGLU, bool ROPE>
 __global__ __launch_bounds__(256) void skinny_linear_kernel(
     int M, int N, int K, int units_per_wave, const bf16_t *__restrict__ a,
     const bf16_t *__restrict__ w, const bf16_t *__restrict__ w2, float *__restrict__ out,
-    bf16_t *__restrict__ out_t) {
+    bf16_t *__restrict__ out_t, RopeOut ro) {
   constexpr int NW = SWIGLU ? 2 : 1;
   __shared__ float4 red[4][NW][MB][4][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
@@ -162,6 +173,35 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
         *(uint2 *)(out_t + tiled_offset(m, n, N)) =
             pack4_bf16(silu_f(s[0].x) * s[NW - 1].x, silu_f(s[0].y) * s[NW - 1].y,
                        silu_f(s[0].z) * s[NW - 1].z, silu_f(s[0].w) * s[NW - 1].w);
+      } else if (ROPE) {
+        const int hd = ro.hd, half = hd >> 1, head = n / hd, jp = n % hd;
+        const int key = ro.row_off[m];
+        const size_t pelems = (size_t)ro.Hkv * hd * ro.pg;
+        if (head < ro.Hq + ro.Hkv) {
+          // outputs jp .. jp + 3 of this head are coordinates (i, i + half, i + 1, i + 1 + half)
+          const int i = jp >> 1;
+          const double2 t0 = ro.table[(size_t)ro.row_pos[m] * half + i], t1 = ro.table[(size_t)ro.row_pos[m] * half + i + 1];
+          const double lo0 = s[0].x, hi0 = s[0].y, lo1 = s[0].z, hi1 = s[0].w;
+          const uint32_t lo = (uint32_t)f32_to_bf16((float)(lo0 * t0.x - hi0 * t0.y)) |
+                              ((uint32_t)f32_to_bf16((float)(lo1 * t1.x - hi1 * t1.y)) << 16);
+          const uint32_t hi = (uint32_t)f32_to_bf16((float)(hi0 * t0.x + lo0 * t0.y)) |
+                              ((uint32_t)f32_to_bf16((float)(hi1 * t1.x + lo1 * t1.y)) << 16);
+          if (head < ro.Hq) {
+            bf16_t *q = (bf16_t *)ro.q_out + ((size_t)m * ro.Hq + head) * hd;
+            *(uint32_t *)(q + i) = lo;
+            *(uint32_t *)(q + i + half) = hi;
+          } else {
+            bf16_t *k = (bf16_t *)ro.k_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq) * ro.pg * hd;
+            *(uint32_t *)(k + k_elem_offset(key, i, ro.pg, hd)) = lo;          // i is even: i, i + 1 are adjacent
+            *(uint32_t *)(k + k_elem_offset(key, i + half, ro.pg, hd)) = hi;
+          }
+        } else {
+          bf16_t *v = (bf16_t *)ro.v_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq - ro.Hkv) * ro.pg * hd;
+          v[v_elem_offset(key, jp, ro.pg, hd)] = f32_to_bf16(s[0].x);
+          v[v_elem_offset(key, jp + 1, ro.pg, hd)] = f32_to_bf16(s[0].y);
+          v[v_elem_offset(key, jp + 2, ro.pg, hd)] = f32_to_bf16(s[0].z);
+          v[v_elem_offset(key, jp + 3, ro.pg, hd)] = f32_to_bf16(s[0].w);
+        }
       } else {
         *(float4 *)(out + ((size_t)split * M + m) * N + n) = s[0];
       }
@@ -186,22 +226,27 @@ int skinny_linear_splits(int M, int N, int K) {
 }
 
 int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                         const void *w2, float *out, void *out_t, int n_splits) {
+                         const void *w2, float *out, void *out_t, int n_splits, const RopeOut *rope) {
   const int units = K / 64;
   if (!skinny_linear_supported(M, N, K) || n_splits < 1 || units % (4 * n_splits))
     MC_FAIL(MC_ERR_UNSUPPORTED, "few-row linear: M=%d N=%d K=%d splits=%d not covered", M, N, K, n_splits);
   if (w2 && n_splits != 1) MC_FAIL(MC_ERR_INVALID, "the SwiGLU form cannot be split over K");
   if (w2 && N % 64) MC_FAIL(MC_ERR_UNSUPPORTED, "tiled SwiGLU output needs N %% 64 == 0");
+  if (rope && (w2 || n_splits != 1 || rope->hd % 4 || N != (rope->Hq + 2 * rope->Hkv) * rope->hd))
+    MC_FAIL(MC_ERR_INVALID, "fused QKV output: one K split, N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
+  const RopeOut none{};
   const int upw = units / (4 * n_splits);
   dim3 grid(N / 32, n_splits);
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
   bf16_t *OT = (bf16_t *)out_t;
   if (M <= 32) {
-    if (w2) skinny_linear_kernel<1, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT);
-    else skinny_linear_kernel<1, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT);
+    if (rope) skinny_linear_kernel<1, false, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
+    else if (w2) skinny_linear_kernel<1, true, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    else skinny_linear_kernel<1, false, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
   } else {
-    if (w2) skinny_linear_kernel<2, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT);
-    else skinny_linear_kernel<2, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT);
+    if (rope) skinny_linear_kernel<2, false, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
+    else if (w2) skinny_linear_kernel<2, true, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    else skinny_linear_kernel<2, false, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
   }
   MC_HIP(hipGetLastError());
   return MC_OK;

@@ -159,7 +159,8 @@ extern "C" int mc_model_create(const mc_config *cfg, const mc_weights *w, const 
   };
   // A matrix [rows][K]: plain copy, or (tiled models) repacked through the staging area in
   // row chunks.  row0 places it below earlier rows of a fused matrix (multiple of 32).
-  auto put_matrix = [&](size_t off, size_t row0, const void *src, size_t rows, size_t K) -> hipError_t {
+  auto put_matrix = [&](size_t off, size_t row0, const void *src, size_t rows, size_t K,
+                        int interleave_hd = 0) -> hipError_t {
     if (!lay.tiled) return put(off + row0 * K * e, src, rows * K * e);
     for (size_t r = 0; r < rows; r += lay.staging_rows) {
       const size_t n = std::min(rows - r, (size_t)lay.staging_rows);
@@ -167,7 +168,7 @@ extern "C" int mc_model_create(const mc_config *cfg, const mc_weights *w, const 
                                       hipMemcpyDefault, st);
       if (err != hipSuccess) return err;
       if (launch_pack_tiled(st, (int)n, (int)K, base + lay.staging,
-                            base + off + (row0 + r) / 32 * (K / 64) * 4096) != MC_OK)
+                            base + off + (row0 + r) / 32 * (K / 64) * 4096, interleave_hd) != MC_OK)
         return hipErrorLaunchFailure;
       // the staging area is reused by the next chunk: a copy from pageable host memory is not
       // guaranteed to wait for kernels enqueued earlier on the stream
@@ -193,9 +194,10 @@ extern "C" int mc_model_create(const mc_config *cfg, const mc_weights *w, const 
   for (int l = 0; l < c.n_layers; ++l) {
     const auto &L = lay.layers[l];
     hipError_t err = put(L.attn_norm, w->attn_norm[l], d * e);
-    // fused QKV: rows of wq, then wk, then wv
-    if (err == hipSuccess) err = put_matrix(L.wqkv, 0, w->wq[l], qd, d);
-    if (err == hipSuccess) err = put_matrix(L.wqkv, qd, w->wk[l], kd, d);
+    // fused QKV: rows of wq, then wk, then wv; tiled models keep the rows of every query / key
+    // head interleaved (coordinate i at 2i, i + hd/2 at 2i + 1) for the fused rotary epilogue
+    if (err == hipSuccess) err = put_matrix(L.wqkv, 0, w->wq[l], qd, d, c.head_dim);
+    if (err == hipSuccess) err = put_matrix(L.wqkv, qd, w->wk[l], kd, d, c.head_dim);
     if (err == hipSuccess) err = put_matrix(L.wqkv, qd + kd, w->wv[l], kd, d);
     if (err == hipSuccess) err = put_matrix(L.wo, 0, w->wo[l], d, qd);
     if (err == hipSuccess) err = put(L.ffn_norm, w->ffn_norm[l], d * e);
@@ -232,7 +234,7 @@ constexpr int kProfCap = 8192;
 
 struct SessionLayout {
   size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
-      hlast, attn_ws, alive, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
+      hlast, attn_ws, alive, rope_tab, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
       score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
   size_t total;
   // derived sizes
@@ -291,6 +293,7 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
                                               p.max_prefix, p.max_suffix, pg);
   o.attn_ws = at(o.attn_ws_bytes);
   o.alive = at((size_t)p.max_cands * 4);
+  o.rope_tab = at((size_t)(p.max_prefix + p.max_suffix) * (c.head_dim / 2) * sizeof(double2));
   o.row_tok = at(R * 4);
   o.row_pos = at(R * 4);
   o.row_page = at(R * 4);
@@ -455,20 +458,32 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       ProfScope ps(s, MC_K_ADD_RMSNORM);
       MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, pending, W.attn_norm, c.rms_eps, h, tl));
     }
-    const int s1 = splits_for(m->n_qkv, d);
-    {
-      ProfScope ps(s, MC_K_LINEAR_QKV);
-      MC_TRY(launch_linear(st, dt, rows, m->n_qkv, d, h, W.wqkv, part, s1, tl));
-    }
+    // few rows on the tiled path: one K split, so that the QKV layer can finish its outputs itself
+    const bool fuse_qkv = tl && rows <= 64 && c.head_dim % 4 == 0;
+    const int s1 = fuse_qkv ? 1 : splits_for(m->n_qkv, d);
     char *kl = s->k_layer(l), *vl = s->v_layer(l);
     void *kdst, *vdst;
     if (pass == PASS_PREFIX) { kdst = kl; vdst = vl; }
     else if (pass == PASS_DECODE || pass == PASS_SUFFIX) { kdst = kl + prefix_bytes; vdst = vl + prefix_bytes; }
     else { kdst = s->ptr<void>(L.kscr); vdst = s->ptr<void>(L.vscr); }
-    {
+    const double2 *rope_tab = s->ptr<double2>(L.rope_tab);
+    if (fuse_qkv) {
+      // few rows: the QKV layer rotates and stores queries, keys and values itself
+      RopeOut ro;
+      ro.row_pos = row_pos; ro.row_page = row_page; ro.row_off = row_off;
+      ro.q_out = q; ro.k_pages = kdst; ro.v_pages = vdst; ro.table = rope_tab;
+      ro.Hq = c.n_q_heads; ro.Hkv = c.n_kv_heads; ro.hd = c.head_dim; ro.pg = s->p.page_tokens;
+      ProfScope ps(s, MC_K_LINEAR_QKV);
+      MC_TRY(launch_linear_skinny(st, rows, m->n_qkv, d, h, W.wqkv, nullptr, nullptr, nullptr, 1, &ro));
+    } else {
+      {
+        ProfScope ps(s, MC_K_LINEAR_QKV);
+        MC_TRY(launch_linear(st, dt, rows, m->n_qkv, d, h, W.wqkv, part, s1, tl));
+      }
       ProfScope ps(s, MC_K_ROPE_KV);
       MC_TRY(launch_rope_kv(st, dt, rows, c.n_q_heads, c.n_kv_heads, c.head_dim, s->p.page_tokens,
-                            (double)c.rope_base, part, s1, row_pos, row_page, row_off, q, kdst, vdst));
+                            (double)c.rope_base, part, s1, row_pos, row_page, row_off, q, kdst, vdst,
+                            rope_tab, tl));
     }
     if (pass == PASS_DECODE) {
       DecodeAttnArgs a;
@@ -602,6 +617,11 @@ extern "C" int mc_session_create(const mc_model *m, const mc_arena *arena,
   // KV memory starts at zero so that unused tail slots of a page hold finite values
   if (err == hipSuccess)
     err = hipMemsetAsync(s->base + lay.kpool, 0, lay.vscr + (size_t)lay.n_score_pages * lay.page_bytes - lay.kpool, s->stream);
+  // rotary angles of every position this session can hold
+  if (err == hipSuccess &&
+      launch_rope_table(s->stream, p->max_prefix + p->max_suffix, m->cfg.head_dim, (double)m->cfg.rope_base,
+                        s->ptr<double2>(lay.rope_tab)) != MC_OK)
+    err = hipErrorLaunchFailure;
   if (err == hipSuccess) err = hipStreamSynchronize(s->stream);
   if (err != hipSuccess) {
     mc_session_destroy(s);
