@@ -32,9 +32,9 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115741.7, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115741.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "df563474358ed6287cd7a9963434fede956b4b7c1d55239e9f2879309d19b580"}
+                   "sha256": "6830dbb5ad6c61b32b173dea1cdd80ab983cff5adecef4e21e694b8a73ddb84a"}
 
 
 def measured_traffic_bytes(workload):
