@@ -23,8 +23,6 @@
 // O^T += V^T P^T because V's fragments list their keys in the accumulator's order.
 #include "kernels_mfma.h"
 
-#include <stdlib.h>
-
 #include <algorithm>
 
 namespace mc {
@@ -357,9 +355,7 @@ static AttnItems plan_items(const DecodeAttnArgs &a) {
   int ssplits = 1;
   it.suffix_bps = 0;
   if (it.n_suffix_blocks > 0) {
-    const char *env = getenv("MC_ATTN_SUFFIX_SPLITS");         // measurement override
-    if (env && atoi(env) > 0) ssplits = atoi(env);
-    else ssplits = (it.n_suffix_blocks + 4 * per_wave - 1) / (4 * per_wave);
+    ssplits = (it.n_suffix_blocks + 4 * per_wave - 1) / (4 * per_wave);
     ssplits = std::max(1, std::min(std::min(ssplits, kMaxSuffixSplits), it.n_suffix_blocks));
     it.suffix_bps = (it.n_suffix_blocks + ssplits - 1) / ssplits;
     ssplits = (it.n_suffix_blocks + it.suffix_bps - 1) / it.suffix_bps;
