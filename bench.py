@@ -298,8 +298,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # timed region; every 4th gate/up launch is bracketed by HIP events on the session stream
-    stride = max(1, (s.n_layers * K + 8191) // 8192)
+    # timed region; a sample of the gate/up launches is bracketed by HIP events on the session stream
+    # (the events of a bracket keep the stream idle for about 12 us around the launch, so only
+    # about 256 launches of the run are bracketed: every 64th at the default sizes)
+    stride = max(1, (s.n_layers * K) // 256)
     sess.profile_begin("linear_gate_up", stride)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
