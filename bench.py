@@ -9,7 +9,8 @@ seeded synthetic weights and token ids.  The prefix prefill is done before the t
 reported separately.  Everything is resident in HBM when the clock starts; nothing crosses to
 the host inside the timed region (sampled ids stay on the device).
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: the metric and its value, the per-step time, the roofline figures of the
+dominant kernel and of decode attention, and the oracle's rate on the host cores.
 """
 from __future__ import annotations
 
@@ -246,7 +247,7 @@ def main():
                          "that hardware-counter readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
     args.steps_given, args.warmup_given = args.steps is not None, args.warmup is not None
 
