@@ -107,14 +107,14 @@ def test_rope_kv_write(dtype, pg):
     assert np.all(kh[~written[:, None, :, None].repeat(Hkv, 1).repeat(hd, 3)] == 0)
 
 
-def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20, stride=1):
+def attention_case(dtype, B, Hq, Hkv, hd, pg, P, t, splits=0, seed=20, stride=1, qscale=1.0):
     import torch
     n_pre = -(-P // pg) if P else 0
     per = -(-t // pg) if t else 0
     kpd, vpd, kpv, vpv = make_pools(dtype, max(n_pre, 1), Hkv, pg, hd, seed)
     ksd, vsd, ksv, vsv = make_pools(dtype, max(B * per, 1), Hkv, pg, hd, seed + 2)
     table = np.random.default_rng(seed).permutation(max(B * per, 1)).astype(np.int32).reshape(B, -1) if per else np.zeros((B, 1), np.int32)
-    q = rnd(seed + 4, (B, Hq, hd))
+    q = rnd(seed + 4, (B, Hq, hd), qscale)
     qd, qv = to_dev(q, dtype)
     print("case: attention", dtype, B, Hq, Hkv, hd, pg, P, t, splits, flush=True)
     out = binding.op_attention_decode(qd, kpd if P else None, vpd if P else None, ksd if t else None,
@@ -313,7 +313,7 @@ def test_tiled_outputs_of_rmsnorm_and_attention():
 
 
 # ---------------------------------------------------------------- MFMA prefill / scoring attention
-def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False, item_rows=64):
+def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False, item_rows=64, qscale=1.0):
     """seqs: list of (pos_start, n_rows); pos_start < P means a prefix chunk (keys = prefix
     only, P grows to cover it), pos_start >= P a scored suffix starting at P."""
     import torch
@@ -325,7 +325,7 @@ def prefill_case(Hq, Hkv, hd, P, seqs, stride=1, seed=90, out_tiled=False, item_
     ksd, vsd, ksv, vsv = make_pools("bf16", len(seqs) * per, Hkv, pg, hd, seed + 2)
     table = np.random.default_rng(seed).permutation(len(seqs) * per).astype(np.int32).reshape(len(seqs), per)
     rows = sum(n for _, n in seqs)
-    q = rnd(seed + 4, (rows, Hq, hd)); qd, qv = to_dev(q, "bf16")
+    q = rnd(seed + 4, (rows, Hq, hd), qscale); qd, qv = to_dev(q, "bf16")
     items, r0 = [], 0
     for si, (p0, n) in enumerate(seqs):
         for j in range(0, n, item_rows):
@@ -383,3 +383,16 @@ def test_attention_prefill_item_sizes(item_rows):
 def test_attention_prefill_tiled_output_matches():
     a = prefill_case(8, 2, 128, 100, [(100, 40), (100, 9)], out_tiled=True)
     assert a < 1.5e-2, a
+
+
+@pytest.mark.parametrize("qscale", [8.0, 0.01])
+def test_attention_with_peaked_and_flat_softmax(qscale):
+    """Scores with a standard deviation of ~90 (one key takes nearly all the weight, the running
+    maximum jumps far past the lazy rescale threshold several times) and of ~0.1 (uniform
+    weights), on both MFMA attention kernels."""
+    worst, _ = attention_case("bf16", 9, 8, 2, 128, 64, 700, 130, qscale=qscale, stride=3)
+    assert worst < 2e-2, worst
+    worst, _ = attention_case("bf16", 4, 4, 4, 64, 64, 0, 257, qscale=qscale)
+    assert worst < 2e-2, worst
+    worst = prefill_case(8, 2, 128, 150, [(150, 130), (0, 0)][:1], qscale=qscale, stride=3)
+    assert worst < 2e-2, worst
