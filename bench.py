@@ -110,6 +110,21 @@ def cpu_baseline(wl, weights, n_layers_sample=2, n_cands_sample=4):
                       f"{t_head:.1f} s head measured)"}
 
 
+def measured_mfma_tflops(torch, binding):
+    """bf16 MFMA rate with nothing else running (every wave issues MFMAs on operands it holds),
+    operands ~ N(0, 1) like the activations of the run: the practical ceiling of a GEMM here."""
+    n_wg, iters = 1024, 4096
+    ops = torch.randn(n_wg * 256 * 48, device="cuda").to(torch.bfloat16)
+    binding.op_mfma_probe(ops, n_wg, 256)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    fl = binding.op_mfma_probe(ops, n_wg, iters)
+    e1.record()
+    torch.cuda.synchronize()
+    return fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def measured_copy_gbs(torch):
     """Read + write rate of a plain device copy of 1 GiB (an elementwise kernel), GB/s."""
     src = torch.zeros(256 << 20, dtype=torch.int32, device="cuda")
@@ -199,6 +214,7 @@ def bench_rerank(args, torch, binding, synth):
     sess.profile_begin("attn_prefill", 1)
     sess.score_candidates(suffix, lens, ids, vals, 1.0)
     n_at, ms_at = sess.profile_end()
+    mfma_meas = measured_mfma_tflops(torch, binding)
     rows = B * Ls
     n_chunks = -(-rows // (chunk // Ls * Ls))
     m_chunk = rows / n_chunks
@@ -217,7 +233,8 @@ def bench_rerank(args, torch, binding, synth):
         "roofline": {"bound": "mfma", "kernel": "gemm256_kernel<true> (gate/up + SwiGLU)",
                      "achieved": gu_flops / gu_us / 1e6, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gu_flops / gu_us / 1e6 / MFMA_PEAK_TFLOPS, "traffic": None,
-                     "launches_timed": n_gu, "avg_us": gu_us, "rows_per_launch": m_chunk},
+                     "launches_timed": n_gu, "avg_us": gu_us, "rows_per_launch": m_chunk,
+                     "peak_measured": mfma_meas, "frac_of_measured": gu_flops / gu_us / 1e6 / mfma_meas},
         "whole_pass": {"linear_flops": layer_flops * s.n_layers, "attention_flops": attn_flops * s.n_layers,
                        "achieved_tflops": (layer_flops + attn_flops) * s.n_layers / (elapsed / K) / 1e12,
                        "attention_ms_per_pass": ms_at, "attention_tflops": attn_flops * s.n_layers / (ms_at * 1e-3) / 1e12},

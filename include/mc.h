@@ -330,6 +330,14 @@ int mc_op_attention_prefill(void *stream, int32_t n_items, const int32_t *items,
                             const void *v_suffix, const int32_t *page_table,
                             int32_t table_stride, void *out, int32_t out_tiled);
 
+/* Matrix-core rate probe (a measurement aid, not part of the path): n_workgroups * 256 threads
+ * each read 96 bytes of bf16 operands (device, n_workgroups * 256 * 96 bytes) once and then issue
+ * iters * 8 MFMAs (32x32x16, bf16) on them, no other memory traffic; out: device, one float per
+ * thread.  Flops = n_workgroups * 4 waves * iters * 8 * 32768.  The rate depends on the operand
+ * values through the power-dependent clock. */
+int mc_op_mfma_probe(void *stream, const void *operands, float *out, int32_t n_workgroups,
+                     int32_t iters);
+
 /* Sampling from fp32 logits [rows][vocab] (row_stride 0 = every candidate reads row 0).
  * uniforms: device [n_cands].  out_tokens: device [n_cands]; out_topk: device
  * [n_cands][k] or NULL.  Same rule as mc_sample. */

@@ -97,6 +97,7 @@ SIGNATURES = {
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
     "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _i32]),
+    "mc_op_mfma_probe": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
     "mc_op_attention_prefill": (C.c_int, [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32]),
     "mc_op_sample": (C.c_int, [_vp, _i32, _i32, _vp, _sz, _f32, _i32, _vp, _vp, _vp]),
     "mc_op_reward_score": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
@@ -529,6 +530,16 @@ def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, p
         0 if page_table is None else page_table.shape[1], prefix_splits, ws.data_ptr(), ws.numel(),
         out.data_ptr(), int(out_tiled)))
     return out
+
+
+def op_mfma_probe(operands, n_workgroups: int, iters: int):
+    """operands: bf16 device tensor of n_workgroups * 256 * 48 elements.  Runs the MFMA-only probe
+    kernel once on the current stream; returns the flops it executed."""
+    import torch
+    assert operands.numel() >= n_workgroups * 256 * 48
+    out = torch.empty(n_workgroups * 256, dtype=torch.float32, device=operands.device)
+    _check(load_library().mc_op_mfma_probe(_stream(), operands.data_ptr(), out.data_ptr(), n_workgroups, iters))
+    return n_workgroups * 4 * iters * 8 * 32768.0
 
 
 def op_attention_prefill(q, items, k_prefix, v_prefix, k_suffix, v_suffix, page_table, prefix_len,

@@ -197,6 +197,43 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
   }
 }
 
+// Matrix-core rate with nothing else going on: every wave keeps 8 accumulator tiles and issues
+// MFMAs on operands it loaded once.  What this reaches with realistic operand values is the
+// practical ceiling of any GEMM on the part (the clock follows the power drawn, which depends on
+// the data: all-zero operands run markedly faster).
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const v4u *__restrict__ operands,
+                                                         float *__restrict__ out, int iters) {
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  v4u a[2], b[4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) a[i] = operands[t * 6 + i];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b[i] = operands[t * 6 + 2 + i];
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+      for (int y = 0; y < 2; ++y) acc[x * 2 + y] = mfma32g(b[x], a[y], acc[x * 2 + y]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[i][r];
+  out[t] = s;
+}
+
+int launch_mfma_probe(hipStream_t st, const void *operands, float *out, int n_workgroups, int iters) {
+  mfma_probe_kernel<<<n_workgroups, 256, 0, st>>>((const v4u *)operands, out, iters);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
 bool gemm256_supported(int M, int N, int K, bool swiglu) {
   return M >= 1 && K >= 64 && K % 64 == 0 && N % (swiglu ? 128 : 256) == 0;
 }

@@ -27,6 +27,9 @@ bool gemm256_supported(int M, int N, int K, bool swiglu);
 int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                    const void *w2, float *out, void *out_t);
 
+// MFMA-only probe: n_workgroups * 256 threads, each with 6 x 16 bytes of bf16 operands.
+int launch_mfma_probe(hipStream_t st, const void *operands, float *out, int n_workgroups, int iters);
+
 // Causal attention over many rows.  items[i] = (first row, rows <= 64, position of the first
 // row, page-table row or -1): up to 64 consecutive positions of one sequence.  Keys at positions
 // < prefix_len come from the prefix pages, later ones from the sequence's suffix pages.

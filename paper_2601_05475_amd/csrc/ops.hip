@@ -214,6 +214,13 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   return launch_attention_decode((hipStream_t)stream, dtype, a);
 }
 
+extern "C" int mc_op_mfma_probe(void *stream, const void *operands, float *out, int32_t n_workgroups,
+                                int32_t iters) {
+  if (!operands || !out || n_workgroups < 1 || n_workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
+    MC_FAIL(MC_ERR_INVALID, "mc_op_mfma_probe: NULL pointer or sizes out of range");
+  return launch_mfma_probe((hipStream_t)stream, operands, out, n_workgroups, iters);
+}
+
 extern "C" int mc_op_attention_prefill(void *stream, int32_t n_items, const int32_t *items,
                                        int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                                        int32_t page_tokens, int32_t prefix_len, const void *q,
