@@ -396,3 +396,17 @@ def test_attention_with_peaked_and_flat_softmax(qscale):
     assert worst < 2e-2, worst
     worst = prefill_case(8, 2, 128, 150, [(150, 130), (0, 0)][:1], qscale=qscale, stride=3)
     assert worst < 2e-2, worst
+
+
+def test_mfma_probe_counts_what_it_claims():
+    """All-ones operands: every accumulator element gains 16 per MFMA, so a thread's 8 tiles x 16
+    registers sum to 8 * 16 * 16 * iters."""
+    import torch
+    n_wg, iters = 3, 5
+    ops = torch.ones(n_wg * 256 * 48, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(n_wg * 256, dtype=torch.float32, device="cuda")
+    lib = binding.load_library()
+    assert lib.mc_op_mfma_probe(None, ops.data_ptr(), out.data_ptr(), n_wg, iters) == 0
+    torch.cuda.synchronize()
+    assert torch.all(out == 8 * 16 * 16 * iters)
+    assert binding.op_mfma_probe(ops, n_wg, iters) == n_wg * 4 * iters * 8 * 32768.0
