@@ -33,9 +33,9 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115741.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115740.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "6830dbb5ad6c61b32b173dea1cdd80ab983cff5adecef4e21e694b8a73ddb84a"}
+                   "sha256": "3bdb0fff5b8c7236c4d208b5cf54074163c7a99bfb58cf37946bfe16511c3f26"}
 
 
 def measured_traffic_bytes(workload):
@@ -123,6 +123,23 @@ def measured_mfma_tflops(torch, binding):
     e1.record()
     torch.cuda.synchronize()
     return fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def measured_read_gbs(torch, binding):
+    """HBM read rate of a kernel that only streams (2 GiB, 16-byte non-temporal loads), GB/s."""
+    buf = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda")
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    binding.op_read_probe(buf, word)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        binding.op_read_probe(buf, word)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    del buf
+    return (2 << 30) / (ms * 1e-3) / 1e9
 
 
 def measured_copy_gbs(torch):
@@ -345,6 +362,7 @@ def main():
     n_at, ms_at = sess.profile_end()
     at_bytes = float(np.mean([attention_bytes(s, B, P, t + 1) for t in range(K)]))
 
+    read_gbs = measured_read_gbs(torch, binding)
     gu_us = ms_gu * 1e3 / max(n_gu, 1)
     at_us = ms_at * 1e3 / max(n_at, 1)
     gu_gbs = gate_up_bytes(s, B) / gu_us / 1e3
@@ -360,6 +378,7 @@ def main():
                    "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens},
         "roofline": {"bound": "hbm", "kernel": "skinny_linear_kernel (gate/up + SwiGLU)",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
+                     "peak_measured": read_gbs, "frac_of_measured": gu_gbs / read_gbs,
                      "traffic": measured_traffic_bytes(args.workload), "algorithmic_bytes": gate_up_bytes(s, B),
                      "launches_timed": n_gu, "avg_us": gu_us},
         "roofline_attn": {"bound": "hbm", "kernel": "decode attention (all launches of one layer-step)",

@@ -330,6 +330,11 @@ int mc_op_attention_prefill(void *stream, int32_t n_items, const int32_t *items,
                             const void *v_suffix, const int32_t *page_table,
                             int32_t table_stride, void *out, int32_t out_tiled);
 
+/* HBM read-rate probe (a measurement aid): reads `bytes` of device memory once (a multiple of
+ * 64 MiB; larger than the 256 MB memory-side cache for an HBM figure) with 16-byte streaming
+ * loads and nothing else; out_word: device, 4 bytes, may be written. */
+int mc_op_read_probe(void *stream, const void *buf, size_t bytes, void *out_word);
+
 /* Matrix-core rate probe (a measurement aid, not part of the path): n_workgroups * 256 threads
  * each read 96 bytes of bf16 operands (device, n_workgroups * 256 * 96 bytes) once and then issue
  * iters * 8 MFMAs (32x32x16, bf16) on them, no other memory traffic; out: device, one float per

@@ -97,6 +97,7 @@ SIGNATURES = {
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
     "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _i32]),
+    "mc_op_read_probe": (C.c_int, [_vp, _vp, _sz, _vp]),
     "mc_op_mfma_probe": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
     "mc_op_attention_prefill": (C.c_int, [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32]),
     "mc_op_sample": (C.c_int, [_vp, _i32, _i32, _vp, _sz, _f32, _i32, _vp, _vp, _vp]),
@@ -530,6 +531,11 @@ def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, p
         0 if page_table is None else page_table.shape[1], prefix_splits, ws.data_ptr(), ws.numel(),
         out.data_ptr(), int(out_tiled)))
     return out
+
+
+def op_read_probe(buf, out_word):
+    """One streaming read of the whole uint8 device tensor `buf` (a multiple of 64 MiB)."""
+    _check(load_library().mc_op_read_probe(_stream(), buf.data_ptr(), buf.numel() * buf.element_size(), out_word.data_ptr()))
 
 
 def op_mfma_probe(operands, n_workgroups: int, iters: int):

@@ -27,6 +27,9 @@ bool gemm256_supported(int M, int N, int K, bool swiglu);
 int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                    const void *w2, float *out, void *out_t);
 
+// Streaming-read probe over `bytes` of device memory (a multiple of 64 MiB); out: one word.
+int launch_read_probe(hipStream_t st, const void *buf, size_t bytes, uint32_t *out);
+
 // MFMA-only probe: n_workgroups * 256 threads, each with 6 x 16 bytes of bf16 operands.
 int launch_mfma_probe(hipStream_t st, const void *operands, float *out, int n_workgroups, int iters);
 

@@ -80,6 +80,31 @@ int launch_pack_tiled(hipStream_t st, int rows, int K, const void *src, void *ds
   return MC_OK;
 }
 
+// ---- streaming-read probe: what a kernel that only reads (16-byte non-temporal loads, eight in
+// flight per thread, one contiguous range per workgroup) gets out of HBM
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4 *__restrict__ p, size_t per_wg,
+                                                         uint32_t *__restrict__ out) {
+  const u32x4 *q = p + (size_t)blockIdx.x * per_wg + threadIdx.x;
+  u32x4 acc = {0, 0, 0, 0};
+  for (size_t i = 0; i < per_wg; i += 256 * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(q + i + j * 256);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc ^= v[j];
+  }
+  if (acc[0] == 0x12345678u && acc[1] == 0x9abcdef0u) out[0] = acc[2];      // keeps the loads alive
+}
+
+int launch_read_probe(hipStream_t st, const void *buf, size_t bytes, uint32_t *out) {
+  const int n_wg = 2048;
+  const size_t per_wg = bytes / 16 / n_wg;
+  if (per_wg == 0 || per_wg % 2048) MC_FAIL(MC_ERR_INVALID, "read probe: bytes must be a positive multiple of %d", 2048 * 2048 * 16);
+  read_probe_kernel<<<n_wg, 256, 0, st>>>((const u32x4 *)buf, per_wg, out);
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+
 // =====================================================================================
 // Few-row linear layer on tiled operands: weights streamed once from HBM straight into MFMA
 // operands.  A workgroup owns one 32-row weight tile; its 4 waves take 4 slices of the K range

@@ -214,6 +214,11 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   return launch_attention_decode((hipStream_t)stream, dtype, a);
 }
 
+extern "C" int mc_op_read_probe(void *stream, const void *buf, size_t bytes, void *out_word) {
+  if (!buf || !out_word) MC_FAIL(MC_ERR_INVALID, "mc_op_read_probe: NULL pointer");
+  return launch_read_probe((hipStream_t)stream, buf, bytes, (uint32_t *)out_word);
+}
+
 extern "C" int mc_op_mfma_probe(void *stream, const void *operands, float *out, int32_t n_workgroups,
                                 int32_t iters) {
   if (!operands || !out || n_workgroups < 1 || n_workgroups > (1 << 20) || iters < 1 || iters > (1 << 24))
