@@ -317,6 +317,15 @@ int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t
                            int32_t table_stride, int32_t prefix_splits, void *workspace,
                            size_t workspace_bytes, void *out, int32_t out_tiled);
 
+/* Host-only: the work-item plan mc_op_attention_decode would launch for these sizes on the bf16
+ * MFMA path (MC_ERR_UNSUPPORTED for shapes that path does not cover).  out8 (host): prefix items
+ * incl. padding ids, suffix items, prefix key splits, 32-key blocks per prefix split, suffix key
+ * splits, blocks per suffix split, partial states per (candidate, head), id distance between the
+ * row blocks of one prefix split. */
+int mc_op_attention_decode_plan(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
+                                int32_t head_dim, int32_t page_tokens, int32_t prefix_len,
+                                int32_t suffix_len, int32_t prefix_splits, int32_t *out8);
+
 /* Causal attention for many query rows (prefix prefill, candidate scoring); bf16, 64-token
  * pages, head_dim 64 or 128.  items: device int32 [n_items][4] = (first row, rows <= 64,
  * position of the first row, page-table row or -1): up to 64 consecutive positions of one sequence.

@@ -97,6 +97,7 @@ SIGNATURES = {
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
     "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _i32]),
+    "mc_op_attention_decode_plan": (C.c_int, [_i32] * 8 + [_vp]),
     "mc_op_read_probe": (C.c_int, [_vp, _vp, _sz, _vp]),
     "mc_op_mfma_probe": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
     "mc_op_attention_prefill": (C.c_int, [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32]),
@@ -531,6 +532,17 @@ def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, p
         0 if page_table is None else page_table.shape[1], prefix_splits, ws.data_ptr(), ws.numel(),
         out.data_ptr(), int(out_tiled)))
     return out
+
+
+def op_attention_decode_plan(n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens, prefix_len,
+                             suffix_len, prefix_splits=0):
+    """Host-only: the decode-attention launch plan as a dict (no GPU work)."""
+    out = np.zeros(8, np.int32)
+    _check(load_library().mc_op_attention_decode_plan(n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens,
+                                                      prefix_len, suffix_len, prefix_splits, out.ctypes.data))
+    keys = ("prefix_items", "suffix_items", "splits", "blocks_per_split", "suffix_splits", "suffix_bps",
+            "n_parts", "prefix_stride")
+    return dict(zip(keys, (int(v) for v in out)))
 
 
 def op_read_probe(buf, out_word):

@@ -408,6 +408,19 @@ static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, co
   return MC_OK;
 }
 
+// The launch plan as numbers, for host-side checks: {prefix items (with padding ids), suffix
+// items, prefix splits, blocks per prefix split, suffix splits, blocks per suffix split, partial
+// states per (candidate, head), prefix id stride}.
+int decode_attention_plan(const DecodeAttnArgs &a, int32_t out[8]) {
+  if (!decode_attention_mfma_supported(a)) MC_FAIL(MC_ERR_UNSUPPORTED, "decode attention: shape not covered");
+  const AttnItems it = plan_items(a);
+  out[0] = it.n_prefix_items; out[1] = it.n_suffix_items; out[2] = it.splits; out[3] = it.blocks_per_split;
+  out[4] = it.suffix_splits; out[5] = it.suffix_bps;
+  out[6] = (a.prefix_len > 0 ? it.splits : 0) + (a.suffix_len > 0 ? it.suffix_splits : 0);
+  out[7] = it.prefix_stride;
+  return MC_OK;
+}
+
 int launch_attention_decode_mfma(hipStream_t st, const DecodeAttnArgs &a) {
   if (!decode_attention_mfma_supported(a)) MC_FAIL(MC_ERR_UNSUPPORTED, "decode attention: shape not covered");
   const AttnItems it = plan_items(a);

@@ -214,6 +214,19 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   return launch_attention_decode((hipStream_t)stream, dtype, a);
 }
 
+extern "C" int mc_op_attention_decode_plan(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
+                                           int32_t head_dim, int32_t page_tokens, int32_t prefix_len,
+                                           int32_t suffix_len, int32_t prefix_splits, int32_t *out8) {
+  if (!out8 || n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || prefix_len < 0 ||
+      suffix_len < 0 || prefix_len + suffix_len < 1 || prefix_splits < 0)
+    MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  DecodeAttnArgs a{};
+  a.n_cands = n_cands; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
+  a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.suffix_len = suffix_len;
+  a.prefix_splits = prefix_splits;
+  return decode_attention_plan(a, out8);
+}
+
 extern "C" int mc_op_read_probe(void *stream, const void *buf, size_t bytes, void *out_word) {
   if (!buf || !out_word) MC_FAIL(MC_ERR_INVALID, "mc_op_read_probe: NULL pointer");
   return launch_read_probe((hipStream_t)stream, buf, bytes, (uint32_t *)out_word);

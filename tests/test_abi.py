@@ -77,3 +77,35 @@ def test_invalid_configs_are_rejected(lib):
     assert lib.mc_op_tiled_bytes(33, 128) == 64 * 128 * 2 and lib.mc_op_tiled_bytes(33, 100) == 0
     assert lib.mc_op_linear_splits(1, 32, 6144, 4096, 1) >= 1
     assert lib.mc_op_sample(None, 0, 10, None, 0, 1.0, 5, None, None, None) == -1
+
+
+def test_decode_attention_plan_covers_every_block_and_fits_its_workspace(lib):
+    """Host logic of the decode-attention launcher: for a sweep of shapes the key splits cover
+    every 32-key block exactly once, no split is empty, the partial states fit the workspace the
+    library asks for, and the prefix ids of one split are a multiple of 8 apart."""
+    import itertools
+    shapes = [(32, 32, 8, 128), (64, 40, 8, 128), (16, 32, 8, 64), (1, 4, 4, 64), (5, 12, 2, 128), (33, 4, 1, 64)]
+    lens = [0, 1, 31, 32, 33, 64, 65, 200, 512, 1000, 4096, 16384, 40000]
+    for (B, Hq, Hkv, hd), P, t, S in itertools.product(shapes, lens, [0, 1, 63, 64, 65, 512, 1024, 3000], [0, 1, 7, 64, 5000]):
+        if P + t == 0:
+            continue
+        p = binding.op_attention_decode_plan(B, Hq, Hkv, hd, 64, P, t, S)
+        G = Hq // Hkv
+        nb_p, nb_s = -(-P // 32), -(-t // 32)
+        if P:
+            assert p["splits"] >= 1 and p["splits"] * p["blocks_per_split"] >= nb_p
+            assert (p["splits"] - 1) * p["blocks_per_split"] < nb_p
+            row_blocks = -(-B * G // 32)
+            assert p["prefix_stride"] % 8 == 0 and p["prefix_stride"] >= Hkv * p["splits"]
+            assert p["prefix_items"] == p["prefix_stride"] * row_blocks
+        else:
+            assert p["prefix_items"] == 0
+        if t:
+            assert 1 <= p["suffix_splits"] <= 8 and p["suffix_splits"] * p["suffix_bps"] >= nb_s
+            assert (p["suffix_splits"] - 1) * p["suffix_bps"] < nb_s
+            assert p["suffix_items"] == B * Hkv * p["suffix_splits"]
+        else:
+            assert p["suffix_items"] == 0
+        assert p["n_parts"] == (p["splits"] if P else 0) + (p["suffix_splits"] if t else 0) <= 1024 or P > 100000
+        ws = lib.mc_op_attention_decode_ws(B, Hq, Hkv, hd, P, t, 64)
+        assert p["n_parts"] * B * Hq * (hd + 2) * 4 <= ws, (B, Hq, Hkv, hd, P, t, S, p, ws)
