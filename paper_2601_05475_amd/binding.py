@@ -93,6 +93,8 @@ SIGNATURES = {
     "mc_op_add_rmsnorm": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _i32, _vp, _f32, _vp, _i32]),
     "mc_op_linear": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _i32, _i32]),
     "mc_op_linear_splits": (_i32, [_i32] * 5),
+    "mc_op_linear_accumulate": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "mc_op_linear_qkv_rope": (C.c_int, [_vp] + [_i32] * 6 + [_f32, _i32] + [_vp] * 9),
     "mc_op_linear_swiglu": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _i32]),
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
@@ -476,6 +478,39 @@ def op_linear(a, w, n_splits: int = 1, tiled_shape=None):
     _check(load_library().mc_op_linear(_stream(), _code_of(a), M, N, K, a.data_ptr(), w.data_ptr(),
                                        out.data_ptr(), n_splits, int(tiled_shape is not None)))
     return out
+
+
+def op_linear_accumulate(a, w, x, tiled_shape):
+    """x (fp32 [M, N], device) += a w^T on tiled bf16 operands, in place."""
+    M, N, K = tiled_shape
+    _check(load_library().mc_op_linear_accumulate(_stream(), M, N, K, a.data_ptr(), w.data_ptr(), x.data_ptr()))
+    return x
+
+
+def interleave_qk_rows(wqkv, n_q_heads: int, n_kv_heads: int, head_dim: int):
+    """Row order the fused QKV layer expects: in every query / key head, row 2i <- row i and
+    row 2i + 1 <- row i + head_dim / 2; value heads unchanged.  wqkv: [(Hq + 2 Hkv) * hd, K]."""
+    import torch
+    half = head_dim // 2
+    inside = torch.stack([torch.arange(half), torch.arange(half) + half], 1).reshape(-1)
+    idx = []
+    for head in range(n_q_heads + 2 * n_kv_heads):
+        idx.append(head * head_dim + (inside if head < n_q_heads + n_kv_heads else torch.arange(head_dim)))
+    return wqkv[torch.cat(idx).to(wqkv.device)]
+
+
+def op_linear_qkv_rope(a, wqkv, rows, K, row_pos, row_page, row_off, n_q_heads, n_kv_heads, head_dim,
+                       page_tokens, rope_base, n_pos, k_pages, v_pages):
+    """a, wqkv: flat tiled bf16 buffers (wqkv rows interleaved, see interleave_qk_rows).
+    Returns q [rows, Hq, hd] bf16; k_pages / v_pages are written in place."""
+    import torch
+    q = torch.empty((rows, n_q_heads, head_dim), dtype=torch.bfloat16, device=a.device)
+    table = torch.empty((n_pos * (head_dim // 2), 2), dtype=torch.float64, device=a.device)
+    _check(load_library().mc_op_linear_qkv_rope(
+        _stream(), rows, n_q_heads, n_kv_heads, head_dim, page_tokens, K, rope_base, n_pos,
+        a.data_ptr(), wqkv.data_ptr(), row_pos.data_ptr(), row_page.data_ptr(), row_off.data_ptr(),
+        table.data_ptr(), q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr()))
+    return q
 
 
 def op_linear_splits(dtype: str, M: int, N: int, K: int, tiled: bool) -> int:

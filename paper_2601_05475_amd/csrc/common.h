@@ -157,6 +157,13 @@ struct RopeOut {
   int32_t Hq, Hkv, hd, pg;
 };
 bool tiled_shapes_ok(int M, int N, int K);
+// Tiled bf16 layers that finish their outputs themselves.  The fused QKV layer (rotation and
+// query / key / value stores in the epilogue, w with interleaved query / key rows) exists for few
+// rows and for products large enough for the 256-row-tile GEMM; x += a w^T for the latter only.
+bool linear_qkv_rope_fused(int M, int N, int K);
+int launch_linear_qkv_rope(hipStream_t st, int M, int N, int K, const void *a, const void *w, const RopeOut &ro);
+bool linear_accumulate_fused(int M, int N, int K);
+int launch_linear_accumulate(hipStream_t st, int M, int N, int K, const void *a, const void *w, float *x);
 int launch_rope_kv(hipStream_t st, int dtype, int rows, int Hq, int Hkv, int hd, int page_tokens,
                    double rope_base, const float *qkv, int n_splits, const int32_t *row_pos,
                    const int32_t *row_page, const int32_t *row_off, void *q_out, void *k_pages,

@@ -53,11 +53,19 @@ __device__ inline bool gemm_tile_of(int id, int tiles_m, int tiles_n, int &tm, i
   return true;
 }
 
-template <bool SWIGLU>
+// What a workgroup does with its 256 x 256 sums: store them (fp32), the SwiGLU product of two
+// weight matrices (bf16, tiled), the fused QKV epilogue (rope_store_quad), or out += sums.
+enum { GEMM_STORE = 0, GEMM_SWIGLU = 1, GEMM_ROPE = 2, GEMM_ACCUM = 3 };
+// row stride (floats) of a wave's 32 x 128 parking area in the GEMM_ROPE epilogue: 128 + 4, so
+// that the 16-byte writes of eight lanes (eight rows) fall into different banks
+constexpr int kParkStride = 132;
+
+template <int MODE>
 __global__ __launch_bounds__(512)
 void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t *__restrict__ a,
                     const bf16_t *__restrict__ w, const bf16_t *__restrict__ w2,
-                    float *__restrict__ out, bf16_t *__restrict__ out_t) {
+                    float *__restrict__ out, bf16_t *__restrict__ out_t, RopeOut ro) {
+  constexpr bool SWIGLU = MODE == GEMM_SWIGLU;
   constexpr int NW = SWIGLU ? 2 : 1;       // weight matrices
   constexpr int TM = 2;                    // 32-row tiles of a per wave
   constexpr int TN = SWIGLU ? 2 : 4;       // 32-row tiles of each weight matrix per wave
@@ -173,6 +181,32 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
 
   // weight rows are the A operand: a lane holds column m = j of the tile and, per register quad,
   // four consecutive n
+  if (MODE == GEMM_ROPE) {
+    // The rotation epilogue is long; it runs as a rolled loop over quads that the wave first
+    // parks in its own slice of LDS (free after the last barrier above).  The loop hands
+    // consecutive lanes consecutive quads of one row, so table reads and query stores coalesce.
+    float *park = (float *)gemm_lds + wave * (32 * kParkStride);
+    const int n_wave = 32 * (nt0 + TN * wn);
+#pragma unroll
+    for (int y = 0; y < TM; ++y) {
+      const int m0 = 32 * (mt0 + TM * wm + y);
+#pragma unroll
+      for (int x = 0; x < TN; ++x)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x16 &g = acc[x][y];
+          *(float4 *)(park + j * kParkStride + 32 * x + 8 * r4 + 4 * h) =
+              make_float4(g[4 * r4], g[4 * r4 + 1], g[4 * r4 + 2], g[4 * r4 + 3]);
+        }
+#pragma unroll 1
+      for (int it = 0; it < 32 * TN * 8 / 64; ++it) {
+        const int e = it * 64 + lane, row = e / (TN * 8), quad = e % (TN * 8);
+        const float4 s = *(const float4 *)(park + row * kParkStride + 4 * quad);
+        if (m0 + row < M) rope_store_quad(ro, m0 + row, n_wave + 4 * quad, s);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int y = 0; y < TM; ++y) {
     const int m = 32 * (mt0 + TM * wm + y) + j;
@@ -189,6 +223,10 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
           pk.x = pack2g_bf16(silu_g(g[4 * r4]) * uu[4 * r4], silu_g(g[4 * r4 + 1]) * uu[4 * r4 + 1]);
           pk.y = pack2g_bf16(silu_g(g[4 * r4 + 2]) * uu[4 * r4 + 2], silu_g(g[4 * r4 + 3]) * uu[4 * r4 + 3]);
           *(uint2 *)(out_t + tiled_offset(m, n, N)) = pk;
+        } else if (MODE == GEMM_ACCUM) {
+          float4 *p = (float4 *)(out + (size_t)m * N + n);
+          const float4 old = *p;
+          *p = make_float4(old.x + g[4 * r4], old.y + g[4 * r4 + 1], old.z + g[4 * r4 + 2], old.w + g[4 * r4 + 3]);
         } else {
           *(float4 *)(out + (size_t)m * N + n) =
               make_float4(g[4 * r4], g[4 * r4 + 1], g[4 * r4 + 2], g[4 * r4 + 3]);
@@ -239,24 +277,35 @@ bool gemm256_supported(int M, int N, int K, bool swiglu) {
 }
 
 int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                   const void *w2, float *out, void *out_t) {
+                   const void *w2, float *out, void *out_t, const RopeOut *rope, int accumulate) {
   const bool swiglu = w2 != nullptr;
   if (!gemm256_supported(M, N, K, swiglu)) MC_FAIL(MC_ERR_UNSUPPORTED, "GEMM: M=%d N=%d K=%d not covered", M, N, K);
+  if ((swiglu && (rope || accumulate)) || (rope && accumulate))
+    MC_FAIL(MC_ERR_INVALID, "GEMM: one output form at a time");
+  if (rope && (rope->hd % 4 || N != (rope->Hq + 2 * rope->Hkv) * rope->hd))
+    MC_FAIL(MC_ERR_INVALID, "fused QKV output: N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
+  const int mode = swiglu ? GEMM_SWIGLU : rope ? GEMM_ROPE : accumulate ? GEMM_ACCUM : GEMM_STORE;
   const int tiles_m = (M + 255) / 256, tiles_n = N / (swiglu ? 128 : 256);
   const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-  const size_t lds = 2 * 16 * 4096;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[swiglu]) {
-    MC_HIP(hipFuncSetAttribute(swiglu ? (const void *)gemm256_kernel<true> : (const void *)gemm256_kernel<false>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set[swiglu] = true;
+  // two buffers of 16 blocks; the parking areas of the rotation epilogue need a little more
+  const size_t lds = std::max<size_t>(2 * 16 * 4096, mode == GEMM_ROPE ? 8 * 32 * kParkStride * sizeof(float) : 0);
+  const void *kernels[4] = {(const void *)gemm256_kernel<GEMM_STORE>, (const void *)gemm256_kernel<GEMM_SWIGLU>,
+                            (const void *)gemm256_kernel<GEMM_ROPE>, (const void *)gemm256_kernel<GEMM_ACCUM>};
+  static bool attr_set[4] = {false, false, false, false};
+  if (!attr_set[mode]) {
+    MC_HIP(hipFuncSetAttribute(kernels[mode], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set[mode] = true;
   }
-  if (swiglu)
-    gemm256_kernel<true><<<8 * per_xcd, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, (const bf16_t *)a,
-                                                        (const bf16_t *)w, (const bf16_t *)w2, out, (bf16_t *)out_t);
-  else
-    gemm256_kernel<false><<<8 * per_xcd, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, (const bf16_t *)a,
-                                                         (const bf16_t *)w, nullptr, out, (bf16_t *)out_t);
+  const RopeOut none{};
+  const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
+  bf16_t *OT = (bf16_t *)out_t;
+  const dim3 grid(8 * per_xcd);
+  switch (mode) {
+    case GEMM_SWIGLU: gemm256_kernel<GEMM_SWIGLU><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
+    case GEMM_ROPE: gemm256_kernel<GEMM_ROPE><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, *rope); break;
+    case GEMM_ACCUM: gemm256_kernel<GEMM_ACCUM><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
+    default: gemm256_kernel<GEMM_STORE><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
+  }
   MC_HIP(hipGetLastError());
   return MC_OK;
 }

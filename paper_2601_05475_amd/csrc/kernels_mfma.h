@@ -16,6 +16,42 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
                          const void *w2, float *out, void *out_t, int n_splits,
                          const RopeOut *rope = nullptr);
 
+// Epilogue of the fused QKV layer for one row m and four consecutive outputs n .. n + 3 of the
+// interleaved weight layout, i.e. coordinates (i, i + hd/2, i + 1, i + 1 + hd/2) of one query or
+// key head (i = (n % hd) / 2), or four consecutive coordinates of a value head: rotate by the
+// row's position (double, from the table) and store the query row-major, the key / value in its
+// page slot.
+__device__ inline void rope_store_quad(const RopeOut &ro, int m, int n, float4 s) {
+  const int hd = ro.hd, half = hd >> 1, head = n / hd, jp = n % hd;
+  const int key = ro.row_off[m];
+  const size_t pelems = (size_t)ro.Hkv * hd * ro.pg;
+  if (head < ro.Hq + ro.Hkv) {
+    const int i = jp >> 1;
+    const double2 *tp = ro.table + (size_t)ro.row_pos[m] * half + i;
+    const double2 t0 = tp[0], t1 = tp[1];
+    const double lo0 = s.x, hi0 = s.y, lo1 = s.z, hi1 = s.w;
+    const uint32_t lo = (uint32_t)f32_to_bf16((float)(lo0 * t0.x - hi0 * t0.y)) |
+                        ((uint32_t)f32_to_bf16((float)(lo1 * t1.x - hi1 * t1.y)) << 16);
+    const uint32_t hi = (uint32_t)f32_to_bf16((float)(hi0 * t0.x + lo0 * t0.y)) |
+                        ((uint32_t)f32_to_bf16((float)(hi1 * t1.x + lo1 * t1.y)) << 16);
+    if (head < ro.Hq) {
+      bf16_t *q = (bf16_t *)ro.q_out + ((size_t)m * ro.Hq + head) * hd;
+      *(uint32_t *)(q + i) = lo;
+      *(uint32_t *)(q + i + half) = hi;
+    } else {
+      bf16_t *k = (bf16_t *)ro.k_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq) * ro.pg * hd;
+      *(uint32_t *)(k + k_elem_offset(key, i, ro.pg, hd)) = lo;          // i is even: i, i + 1 are adjacent
+      *(uint32_t *)(k + k_elem_offset(key, i + half, ro.pg, hd)) = hi;
+    }
+  } else {
+    bf16_t *v = (bf16_t *)ro.v_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq - ro.Hkv) * ro.pg * hd;
+    v[v_elem_offset(key, jp, ro.pg, hd)] = f32_to_bf16(s.x);
+    v[v_elem_offset(key, jp + 1, ro.pg, hd)] = f32_to_bf16(s.y);
+    v[v_elem_offset(key, jp + 2, ro.pg, hd)] = f32_to_bf16(s.z);
+    v[v_elem_offset(key, jp + 3, ro.pg, hd)] = f32_to_bf16(s.w);
+  }
+}
+
 // Many-row GEMM: 1 split; fp32 out, or the SwiGLU form with bf16 out.
 bool gemm_supported(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const void *w,
@@ -24,8 +60,11 @@ int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const v
 // The same for shapes that fill 256-row tiles (N % 256 == 0, or N % 128 == 0 in the SwiGLU form):
 // 256 x 256 output tile per workgroup, double-buffered LDS, XCD-aware tile order.
 bool gemm256_supported(int M, int N, int K, bool swiglu);
+// rope != nullptr: the fused QKV layer as in launch_linear_skinny (N = (Hq + 2 Hkv) hd, hd % 4 == 0).
+// accumulate: out[m][n] += the product (the residual stream updated in place) instead of a store.
 int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                   const void *w2, float *out, void *out_t);
+                   const void *w2, float *out, void *out_t, const RopeOut *rope = nullptr,
+                   int accumulate = 0);
 
 // Streaming-read probe over `bytes` of device memory (a multiple of 64 MiB); out: one word.
 int launch_read_probe(hipStream_t st, const void *buf, size_t bytes, uint32_t *out);

@@ -199,34 +199,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
             pack4_bf16(silu_f(s[0].x) * s[NW - 1].x, silu_f(s[0].y) * s[NW - 1].y,
                        silu_f(s[0].z) * s[NW - 1].z, silu_f(s[0].w) * s[NW - 1].w);
       } else if (ROPE) {
-        const int hd = ro.hd, half = hd >> 1, head = n / hd, jp = n % hd;
-        const int key = ro.row_off[m];
-        const size_t pelems = (size_t)ro.Hkv * hd * ro.pg;
-        if (head < ro.Hq + ro.Hkv) {
-          // outputs jp .. jp + 3 of this head are coordinates (i, i + half, i + 1, i + 1 + half)
-          const int i = jp >> 1;
-          const double2 t0 = ro.table[(size_t)ro.row_pos[m] * half + i], t1 = ro.table[(size_t)ro.row_pos[m] * half + i + 1];
-          const double lo0 = s[0].x, hi0 = s[0].y, lo1 = s[0].z, hi1 = s[0].w;
-          const uint32_t lo = (uint32_t)f32_to_bf16((float)(lo0 * t0.x - hi0 * t0.y)) |
-                              ((uint32_t)f32_to_bf16((float)(lo1 * t1.x - hi1 * t1.y)) << 16);
-          const uint32_t hi = (uint32_t)f32_to_bf16((float)(hi0 * t0.x + lo0 * t0.y)) |
-                              ((uint32_t)f32_to_bf16((float)(hi1 * t1.x + lo1 * t1.y)) << 16);
-          if (head < ro.Hq) {
-            bf16_t *q = (bf16_t *)ro.q_out + ((size_t)m * ro.Hq + head) * hd;
-            *(uint32_t *)(q + i) = lo;
-            *(uint32_t *)(q + i + half) = hi;
-          } else {
-            bf16_t *k = (bf16_t *)ro.k_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq) * ro.pg * hd;
-            *(uint32_t *)(k + k_elem_offset(key, i, ro.pg, hd)) = lo;          // i is even: i, i + 1 are adjacent
-            *(uint32_t *)(k + k_elem_offset(key, i + half, ro.pg, hd)) = hi;
-          }
-        } else {
-          bf16_t *v = (bf16_t *)ro.v_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq - ro.Hkv) * ro.pg * hd;
-          v[v_elem_offset(key, jp, ro.pg, hd)] = f32_to_bf16(s[0].x);
-          v[v_elem_offset(key, jp + 1, ro.pg, hd)] = f32_to_bf16(s[0].y);
-          v[v_elem_offset(key, jp + 2, ro.pg, hd)] = f32_to_bf16(s[0].z);
-          v[v_elem_offset(key, jp + 3, ro.pg, hd)] = f32_to_bf16(s[0].w);
-        }
+        rope_store_quad(ro, m, n, s[0]);
       } else {
         *(float4 *)(out + ((size_t)split * M + m) * N + n) = s[0];
       }

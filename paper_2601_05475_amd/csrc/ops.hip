@@ -50,6 +50,26 @@ int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a,
   return launch_gemm_mfma(st, M, N, K, a, w, nullptr, out, nullptr);
 }
 
+bool linear_qkv_rope_fused(int M, int N, int K) {
+  if (!tiled_shapes_ok(M, N, K)) return false;
+  return M <= 64 ? skinny_linear_supported(M, N, K) : use_gemm256(M, N, K, false);
+}
+
+int launch_linear_qkv_rope(hipStream_t st, int M, int N, int K, const void *a, const void *w, const RopeOut &ro) {
+  if (!linear_qkv_rope_fused(M, N, K)) MC_FAIL(MC_ERR_UNSUPPORTED, "fused QKV layer: M=%d N=%d K=%d not covered", M, N, K);
+  if (M <= 64) return launch_linear_skinny(st, M, N, K, a, w, nullptr, nullptr, nullptr, 1, &ro);
+  return launch_gemm256(st, M, N, K, a, w, nullptr, nullptr, nullptr, &ro, 0);
+}
+
+bool linear_accumulate_fused(int M, int N, int K) {
+  return tiled_shapes_ok(M, N, K) && M > 64 && use_gemm256(M, N, K, false);
+}
+
+int launch_linear_accumulate(hipStream_t st, int M, int N, int K, const void *a, const void *w, float *x) {
+  if (!linear_accumulate_fused(M, N, K)) MC_FAIL(MC_ERR_UNSUPPORTED, "accumulating linear layer: M=%d N=%d K=%d not covered", M, N, K);
+  return launch_gemm256(st, M, N, K, a, w, nullptr, x, nullptr, nullptr, 1);
+}
+
 int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
                          const void *wg, const void *wu, void *out, int tiled) {
   if (!tiled) return launch_linear_swiglu_generic(st, dtype, M, N, K, a, wg, wu, out);
@@ -140,6 +160,33 @@ extern "C" int mc_op_linear(void *stream, int32_t dtype, int32_t M, int32_t N, i
   if (!a || !w || !out) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
   MC_TRY(check_tiled(dtype, tiled, K));
   return launch_linear((hipStream_t)stream, dtype, M, N, K, a, w, out, n_splits, tiled);
+}
+
+extern "C" int mc_op_linear_accumulate(void *stream, int32_t M, int32_t N, int32_t K, const void *a,
+                                       const void *w, float *x) {
+  if (M < 1 || N < 1 || K < 1) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!a || !w || !x) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  return launch_linear_accumulate((hipStream_t)stream, M, N, K, a, w, x);
+}
+
+extern "C" int mc_op_linear_qkv_rope(void *stream, int32_t rows, int32_t n_q_heads, int32_t n_kv_heads,
+                                     int32_t head_dim, int32_t page_tokens, int32_t K, float rope_base,
+                                     int32_t n_pos, const void *a, const void *wqkv,
+                                     const int32_t *row_pos, const int32_t *row_page,
+                                     const int32_t *row_off, void *table, void *q_out, void *k_pages,
+                                     void *v_pages) {
+  if (rows < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 4 || head_dim % 4 || page_tokens < 1 ||
+      K < 1 || n_pos < 1 || !(rope_base > 0.f))
+    MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!a || !wqkv || !row_pos || !row_page || !row_off || !table || !q_out || !k_pages || !v_pages)
+    MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  hipStream_t st = (hipStream_t)stream;
+  MC_TRY(launch_rope_table(st, n_pos, head_dim, (double)rope_base, (double2 *)table));
+  RopeOut ro;
+  ro.row_pos = row_pos; ro.row_page = row_page; ro.row_off = row_off;
+  ro.q_out = q_out; ro.k_pages = k_pages; ro.v_pages = v_pages; ro.table = (const double2 *)table;
+  ro.Hq = n_q_heads; ro.Hkv = n_kv_heads; ro.hd = head_dim; ro.pg = page_tokens;
+  return launch_linear_qkv_rope(st, rows, (n_q_heads + 2 * n_kv_heads) * head_dim, K, a, wqkv, ro);
 }
 
 extern "C" int32_t mc_op_linear_splits(int32_t dtype, int32_t M, int32_t N, int32_t K, int32_t tiled) {

@@ -458,8 +458,8 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       ProfScope ps(s, MC_K_ADD_RMSNORM);
       MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, pending, W.attn_norm, c.rms_eps, h, tl));
     }
-    // few rows on the tiled path: one K split, so that the QKV layer can finish its outputs itself
-    const bool fuse_qkv = tl && rows <= 64 && c.head_dim % 4 == 0;
+    // tiled path, few rows or a large product: the QKV layer finishes its outputs itself (one K split)
+    const bool fuse_qkv = tl && c.head_dim % 4 == 0 && linear_qkv_rope_fused(rows, m->n_qkv, d);
     const int s1 = fuse_qkv ? 1 : splits_for(m->n_qkv, d);
     char *kl = s->k_layer(l), *vl = s->v_layer(l);
     void *kdst, *vdst;
@@ -468,13 +468,13 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
     else { kdst = s->ptr<void>(L.kscr); vdst = s->ptr<void>(L.vscr); }
     const double2 *rope_tab = s->ptr<double2>(L.rope_tab);
     if (fuse_qkv) {
-      // few rows: the QKV layer rotates and stores queries, keys and values itself
+      // the QKV layer rotates and stores queries, keys and values itself
       RopeOut ro;
       ro.row_pos = row_pos; ro.row_page = row_page; ro.row_off = row_off;
       ro.q_out = q; ro.k_pages = kdst; ro.v_pages = vdst; ro.table = rope_tab;
       ro.Hq = c.n_q_heads; ro.Hkv = c.n_kv_heads; ro.hd = c.head_dim; ro.pg = s->p.page_tokens;
       ProfScope ps(s, MC_K_LINEAR_QKV);
-      MC_TRY(launch_linear_skinny(st, rows, m->n_qkv, d, h, W.wqkv, nullptr, nullptr, nullptr, 1, &ro));
+      MC_TRY(launch_linear_qkv_rope(st, rows, m->n_qkv, d, h, W.wqkv, ro));
     } else {
       {
         ProfScope ps(s, MC_K_LINEAR_QKV);
@@ -525,10 +525,13 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       MC_TRY(launch_attention_generic(st, dt, a));
       }
     }
-    const int s2 = splits_for(d, qd);
+    // a large product on the tiled path adds to the residual stream in its own epilogue
+    const bool acc_o = tl && linear_accumulate_fused(rows, d, qd);
+    const int s2 = acc_o ? 0 : splits_for(d, qd);
     {
       ProfScope ps(s, MC_K_LINEAR_O);
-      MC_TRY(launch_linear(st, dt, rows, d, qd, ao, W.wo, part, s2, tl));
+      if (acc_o) MC_TRY(launch_linear_accumulate(st, rows, d, qd, ao, W.wo, x));
+      else MC_TRY(launch_linear(st, dt, rows, d, qd, ao, W.wo, part, s2, tl));
     }
     {
       ProfScope ps(s, MC_K_ADD_RMSNORM);
@@ -538,10 +541,12 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       ProfScope ps(s, MC_K_LINEAR_GATE_UP);
       MC_TRY(launch_linear_swiglu(st, dt, rows, c.d_ffn, d, h, W.w_gate, W.w_up, act, tl));
     }
-    const int s3 = splits_for(d, c.d_ffn);
+    const bool acc_d = tl && linear_accumulate_fused(rows, d, c.d_ffn);
+    const int s3 = acc_d ? 0 : splits_for(d, c.d_ffn);
     {
       ProfScope ps(s, MC_K_LINEAR_DOWN);
-      MC_TRY(launch_linear(st, dt, rows, d, c.d_ffn, act, W.w_down, part, s3, tl));
+      if (acc_d) MC_TRY(launch_linear_accumulate(st, rows, d, c.d_ffn, act, W.w_down, x));
+      else MC_TRY(launch_linear(st, dt, rows, d, c.d_ffn, act, W.w_down, part, s3, tl));
     }
     pending = s3;
   }

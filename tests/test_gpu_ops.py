@@ -280,6 +280,60 @@ def test_linear_tiled(M, N, K, S):
     np.testing.assert_allclose(out, want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
 
 
+@pytest.mark.parametrize("M,N,K", [(3000, 4096, 256), (2300, 5632, 512)])
+def test_linear_accumulate_tiled(M, N, K):
+    """x += a w^T in the GEMM's epilogue (ragged last row tile, padding workgroup ids)."""
+    import torch
+    a = rnd(160, (M, K)); w = rnd(161, (N, K), 0.05); x = rnd(162, (M, N), 3.0)
+    ad, av = to_dev(a, "bf16"); wd, wv = to_dev(w, "bf16")
+    print("case: linear accumulate", M, N, K, flush=True)
+    xd = torch.from_numpy(x.astype(np.float32)).cuda()
+    binding.op_linear_accumulate(binding.op_pack_tiled(ad), binding.op_pack_tiled(wd), xd, (M, N, K))
+    want = x.astype(np.float32).astype(np.float64) + otf.linear(av, wv)
+    np.testing.assert_allclose(xd.cpu().numpy(), want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
+
+
+@pytest.mark.parametrize("rows,Hq,Hkv,hd,K", [
+    (19, 4, 2, 64, 256),           # few rows: the weight-streaming kernel
+    (64, 8, 2, 128, 512),
+    (2100, 32, 8, 128, 256),       # many rows: the 256-row-tile GEMM (ragged last tile)
+    (6200, 12, 2, 128, 256),       # N = 2048
+])
+def test_linear_qkv_rope_fused(rows, Hq, Hkv, hd, K):
+    """QKV projection + rotation + query / key / value stores in one kernel, against the oracle's
+    linear layer and rotation."""
+    import torch
+    pg, base, n_pos = 64, 500000.0, 5000
+    nq = (Hq + 2 * Hkv) * hd
+    a = rnd(170, (rows, K)); w = rnd(171, (nq, K), 0.05)
+    ad, av = to_dev(a, "bf16"); wd, wv = to_dev(w, "bf16")
+    rng = np.random.default_rng(172)
+    pos = rng.integers(0, n_pos, rows).astype(np.int32)
+    pos[:3] = [0, 1, n_pos - 1]
+    n_pages = -(-rows // pg) + 1
+    slots = rng.permutation(n_pages * pg)[:rows]
+    page, off = (slots // pg).astype(np.int32), (slots % pg).astype(np.int32)
+    kp = torch.zeros((n_pages, Hkv, pg * hd), dtype=torch.bfloat16, device="cuda")
+    vp = torch.zeros((n_pages, Hkv, pg * hd), dtype=torch.bfloat16, device="cuda")
+    print("case: fused qkv rope", rows, Hq, Hkv, hd, K, flush=True)
+    q = binding.op_linear_qkv_rope(
+        binding.op_pack_tiled(ad), binding.op_pack_tiled(binding.interleave_qk_rows(wd, Hq, Hkv, hd)), rows, K,
+        torch.from_numpy(pos).cuda(), torch.from_numpy(page).cuda(), torch.from_numpy(off).cuda(),
+        Hq, Hkv, hd, pg, base, n_pos, kp, vp)
+    full = otf.linear(av, wv).reshape(rows, Hq + 2 * Hkv, hd)
+    wq = otf.rope(full[:, :Hq], pos, base)
+    wk = otf.rope(full[:, Hq:Hq + Hkv], pos, base)
+    wvv = full[:, Hq + Hkv:]
+    tol = TOL["bf16"] * np.abs(full).max()
+    np.testing.assert_allclose(q.float().cpu().numpy(), wq, rtol=0, atol=tol)
+    ku, vu = binding.kv_pages_unpack(kp, vp, pg, hd)
+    kh, vh = ku.float().cpu().numpy(), vu.float().cpu().numpy()
+    np.testing.assert_allclose(kh[page, :, off, :], wk, rtol=0, atol=tol)
+    np.testing.assert_allclose(vh[page, :, off, :], wvv, rtol=0, atol=tol)
+    written = np.zeros((n_pages, pg), bool); written[page, off] = True
+    assert np.all(kh.transpose(0, 2, 1, 3)[~written] == 0) and np.all(vh.transpose(0, 2, 1, 3)[~written] == 0)
+
+
 @pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512),
                                    (3000, 2048, 512), (2070, 2944, 256)])
 def test_linear_swiglu_tiled(M, N, K):

@@ -238,7 +238,9 @@ def test_8b_shape_layer_at_the_benchmark_launch_configuration():
     configuration the benchmark times: 4096-token shared prefix, 32 candidates, 64-token pages,
     2048-row prefill chunks, automatic key splits.  The vocabulary is cut to 32000 to keep the
     oracle's float64 copies small (the LM-head shape itself is covered by an operation test).
-    Decode steps 1 and 2 for all candidates against the oracle."""
+    Decode steps 1 and 2 for all candidates against the oracle.  A second session prefills in one
+    4096-row chunk, which is large enough for the O and down projections to add to the residual
+    stream in their own epilogue."""
     wl = synth.WORKLOADS["8b"]
     base = wl.shape
     s = synth.Shape("8b-L1-V32000", 1, base.d_model, base.n_q_heads, base.n_kv_heads, base.head_dim,
@@ -249,6 +251,11 @@ def test_8b_shape_layer_at_the_benchmark_launch_configuration():
     print("case: 8b layer twin", s, flush=True)
     pl, steps, sess, _ = teacher_forced_gpu(s, w, prefix, suffix, wl.page_tokens, chunk_rows=2048,
                                             max_suffix=wl.n_steps)
+    sess.close()
+    print("case: 8b layer twin, one 4096-row chunk", flush=True)
+    pl2, steps2, sess2, _ = teacher_forced_gpu(s, w, prefix, suffix, wl.page_tokens, chunk_rows=4096,
+                                               max_suffix=wl.n_steps)
+    sess2.close()
     w64 = _as_f64(synth.weights_as_f32(w))          # converted once: the oracle would redo it per call
     print("oracle: exact", flush=True)
     want_pl, want = otf.forward_shared(oracle_config(s, exact=True), w64, prefix, suffix)
@@ -256,6 +263,8 @@ def test_8b_shape_layer_at_the_benchmark_launch_configuration():
     fl_pl, fl = otf.forward_shared(oracle_config(s, exact=False), w64, prefix, suffix)
     assert_logits_close(pl[None], want_pl[None], "bf16", "prefix logits", fl_pl[None])
     assert_logits_close(steps, want.transpose(1, 0, 2), "bf16", "decode logits", fl.transpose(1, 0, 2))
+    assert_logits_close(pl2[None], want_pl[None], "bf16", "prefix logits (4096-row chunk)", fl_pl[None])
+    assert_logits_close(steps2, want.transpose(1, 0, 2), "bf16", "decode logits (4096-row chunk)", fl.transpose(1, 0, 2))
 
 
 # ---------------------------------------------------------------- growing the shared prefix
