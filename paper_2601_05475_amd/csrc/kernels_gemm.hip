@@ -198,11 +198,22 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
           *(float4 *)(park + j * kParkStride + 32 * x + 8 * r4 + 4 * h) =
               make_float4(g[4 * r4], g[4 * r4 + 1], g[4 * r4 + 2], g[4 * r4 + 3]);
         }
+      constexpr int kBatch = 4;        // quads per lane whose loads go out together
 #pragma unroll 1
-      for (int it = 0; it < 32 * TN * 8 / 64; ++it) {
-        const int e = it * 64 + lane, row = e / (TN * 8), quad = e % (TN * 8);
-        const float4 s = *(const float4 *)(park + row * kParkStride + 4 * quad);
-        if (m0 + row < M) rope_store_quad(ro, m0 + row, n_wave + 4 * quad, s);
+      for (int it0 = 0; it0 < 32 * TN * 8 / 64; it0 += kBatch) {
+        float4 s[kBatch];
+        RopeQuad rq[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int e = (it0 + u) * 64 + lane, row = e / (TN * 8), quad = e % (TN * 8);
+          s[u] = *(const float4 *)(park + row * kParkStride + 4 * quad);
+          rq[u] = rope_load_quad(ro, min(m0 + row, M - 1), n_wave + 4 * quad);
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int e = (it0 + u) * 64 + lane, row = e / (TN * 8), quad = e % (TN * 8);
+          if (m0 + row < M) rope_store_quad(ro, m0 + row, n_wave + 4 * quad, s[u], rq[u]);
+        }
       }
     }
     return;

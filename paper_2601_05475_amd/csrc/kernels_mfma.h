@@ -20,35 +20,53 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
 // interleaved weight layout, i.e. coordinates (i, i + hd/2, i + 1, i + 1 + hd/2) of one query or
 // key head (i = (n % hd) / 2), or four consecutive coordinates of a value head: rotate by the
 // row's position (double, from the table) and store the query row-major, the key / value in its
-// page slot.
-__device__ inline void rope_store_quad(const RopeOut &ro, int m, int n, float4 s) {
+// page slot.  In two steps, so that a caller with several quads can have all their loads in
+// flight before the first store (stores may alias later loads as far as the compiler knows).
+struct RopeQuad {
+  double2 t0, t1;      // cos / sin of coordinates i and i + 1 at the row's position
+  int32_t key, page;   // slot of the row in its KV page
+};
+
+__device__ inline RopeQuad rope_load_quad(const RopeOut &ro, int m, int n) {
+  RopeQuad r;
+  const int hd = ro.hd, head = n / hd, i = (n % hd) >> 1;
+  r.key = ro.row_off[m];
+  r.page = ro.row_page[m];
+  if (head < ro.Hq + ro.Hkv) {
+    const double2 *tp = ro.table + (size_t)ro.row_pos[m] * (hd >> 1) + i;
+    r.t0 = tp[0];
+    r.t1 = tp[1];
+  } else {
+    r.t0 = r.t1 = double2{1.0, 0.0};
+  }
+  return r;
+}
+
+__device__ inline void rope_store_quad(const RopeOut &ro, int m, int n, float4 s, const RopeQuad &r) {
   const int hd = ro.hd, half = hd >> 1, head = n / hd, jp = n % hd;
-  const int key = ro.row_off[m];
   const size_t pelems = (size_t)ro.Hkv * hd * ro.pg;
   if (head < ro.Hq + ro.Hkv) {
     const int i = jp >> 1;
-    const double2 *tp = ro.table + (size_t)ro.row_pos[m] * half + i;
-    const double2 t0 = tp[0], t1 = tp[1];
     const double lo0 = s.x, hi0 = s.y, lo1 = s.z, hi1 = s.w;
-    const uint32_t lo = (uint32_t)f32_to_bf16((float)(lo0 * t0.x - hi0 * t0.y)) |
-                        ((uint32_t)f32_to_bf16((float)(lo1 * t1.x - hi1 * t1.y)) << 16);
-    const uint32_t hi = (uint32_t)f32_to_bf16((float)(hi0 * t0.x + lo0 * t0.y)) |
-                        ((uint32_t)f32_to_bf16((float)(hi1 * t1.x + lo1 * t1.y)) << 16);
+    const uint32_t lo = (uint32_t)f32_to_bf16((float)(lo0 * r.t0.x - hi0 * r.t0.y)) |
+                        ((uint32_t)f32_to_bf16((float)(lo1 * r.t1.x - hi1 * r.t1.y)) << 16);
+    const uint32_t hi = (uint32_t)f32_to_bf16((float)(hi0 * r.t0.x + lo0 * r.t0.y)) |
+                        ((uint32_t)f32_to_bf16((float)(hi1 * r.t1.x + lo1 * r.t1.y)) << 16);
     if (head < ro.Hq) {
       bf16_t *q = (bf16_t *)ro.q_out + ((size_t)m * ro.Hq + head) * hd;
       *(uint32_t *)(q + i) = lo;
       *(uint32_t *)(q + i + half) = hi;
     } else {
-      bf16_t *k = (bf16_t *)ro.k_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq) * ro.pg * hd;
-      *(uint32_t *)(k + k_elem_offset(key, i, ro.pg, hd)) = lo;          // i is even: i, i + 1 are adjacent
-      *(uint32_t *)(k + k_elem_offset(key, i + half, ro.pg, hd)) = hi;
+      bf16_t *k = (bf16_t *)ro.k_pages + (size_t)r.page * pelems + (size_t)(head - ro.Hq) * ro.pg * hd;
+      *(uint32_t *)(k + k_elem_offset(r.key, i, ro.pg, hd)) = lo;          // i is even: i, i + 1 are adjacent
+      *(uint32_t *)(k + k_elem_offset(r.key, i + half, ro.pg, hd)) = hi;
     }
   } else {
-    bf16_t *v = (bf16_t *)ro.v_pages + (size_t)ro.row_page[m] * pelems + (size_t)(head - ro.Hq - ro.Hkv) * ro.pg * hd;
-    v[v_elem_offset(key, jp, ro.pg, hd)] = f32_to_bf16(s.x);
-    v[v_elem_offset(key, jp + 1, ro.pg, hd)] = f32_to_bf16(s.y);
-    v[v_elem_offset(key, jp + 2, ro.pg, hd)] = f32_to_bf16(s.z);
-    v[v_elem_offset(key, jp + 3, ro.pg, hd)] = f32_to_bf16(s.w);
+    bf16_t *v = (bf16_t *)ro.v_pages + (size_t)r.page * pelems + (size_t)(head - ro.Hq - ro.Hkv) * ro.pg * hd;
+    v[v_elem_offset(r.key, jp, ro.pg, hd)] = f32_to_bf16(s.x);
+    v[v_elem_offset(r.key, jp + 1, ro.pg, hd)] = f32_to_bf16(s.y);
+    v[v_elem_offset(r.key, jp + 2, ro.pg, hd)] = f32_to_bf16(s.z);
+    v[v_elem_offset(r.key, jp + 3, ro.pg, hd)] = f32_to_bf16(s.w);
   }
 }
 

@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
             pack4_bf16(silu_f(s[0].x) * s[NW - 1].x, silu_f(s[0].y) * s[NW - 1].y,
                        silu_f(s[0].z) * s[NW - 1].z, silu_f(s[0].w) * s[NW - 1].w);
       } else if (ROPE) {
-        rope_store_quad(ro, m, n, s[0]);
+        rope_store_quad(ro, m, n, s[0], rope_load_quad(ro, m, n));
       } else {
         *(float4 *)(out + ((size_t)split * M + m) * N + n) = s[0];
       }
