@@ -247,7 +247,7 @@ def bench_rerank(args, torch, binding, synth):
         "config": {"workload": f"{args.workload}: {s.n_layers} layers of the 8B shape; {B} suffixes of {Ls} tokens on a "
                                f"shared prefix of {P}; {R} reward tokens; chunks of {chunk} rows",
                    "n_cands": B, "prefix_len": P, "suffix_len": Ls, "page_tokens": wl.page_tokens},
-        "roofline": {"bound": "mfma", "kernel": "gemm256_kernel<true> (gate/up + SwiGLU)",
+        "roofline": {"bound": "mfma", "kernel": "gemm256_kernel<GEMM_SWIGLU> (gate/up + SwiGLU)",
                      "achieved": gu_flops / gu_us / 1e6, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": gu_flops / gu_us / 1e6 / MFMA_PEAK_TFLOPS, "traffic": None,
                      "launches_timed": n_gu, "avg_us": gu_us, "rows_per_launch": m_chunk,

@@ -155,6 +155,10 @@ def test_attention_decode(dtype, B, Hq, Hkv, hd, pg, P, t):
     (64, 32, 8, 128, 4096, 0, 13),       # reranking fan-out, prefix only
     (2, 8, 8, 128, 63, 65, 1), (3, 8, 4, 64, 65, 64, 1), (5, 16, 2, 128, 129, 127, 1),
     (1, 32, 1, 64, 128, 129, 1), (7, 4, 2, 128, 0, 200, 1), (33, 8, 2, 128, 257, 1, 1),
+    # many query rows per KV head
+    (50, 32, 8, 128, 1000, 70, 3),       # 7 row blocks (the last of 8 rows), last page of 40 keys
+    (64, 32, 2, 64, 200, 33, 17),        # head_dim 64, 32 row blocks, last page of 8 keys
+    (48, 16, 4, 128, 130, 5, 1),         # 6 row blocks, 3 pages (the last with 2 keys)
 ])
 def test_attention_decode_mfma_shapes(B, Hq, Hkv, hd, P, t, stride):
     worst, _ = attention_case("bf16", B, Hq, Hkv, hd, 64, P, t, stride=stride)
@@ -165,6 +169,13 @@ def test_attention_split_count_invariance():
     outs = [attention_case("bf16", 8, 32, 8, 128, 64, 2048, 100, splits=s)[1] for s in (1, 2, 8, 32)]
     for o in outs[1:]:
         np.testing.assert_allclose(o, outs[0], rtol=0, atol=8e-3)   # bf16 output rounding only
+
+
+def test_attention_split_count_invariance_many_rows():
+    """The same with 256 query rows per KV head (8 row blocks) and a ragged last page."""
+    outs = [attention_case("bf16", 64, 32, 8, 128, 64, 2048 + 40, 3, splits=s, stride=29)[1] for s in (1, 2, 8, 16)]
+    for o in outs[1:]:
+        np.testing.assert_allclose(o, outs[0], rtol=0, atol=8e-3)
 
 
 def test_sample_op_cases():
