@@ -91,12 +91,18 @@ __global__ __launch_bounds__(256) void add_rmsnorm_kernel(
 // The same, four elements per thread and the row kept in registers between the two phases
 // (d % 4 == 0, d <= 4 * VEC * blockDim).  bf16 output goes out as 8-byte stores; in the tiled
 // layout four consecutive k stay inside one 16-byte chunk.
+// rows_per_xcd > 0 (many rows): workgroups are dealt round-robin to the 8 XCDs, so block b works
+// on row (b % 8) * rows_per_xcd + b / 8 and every XCD gets a contiguous range of rows.  In the
+// tiled layout the 16-byte pieces of 8 consecutive rows share a 128-byte line; written from one
+// L2 they leave as whole lines instead of eight partial ones.
 template <typename T, int VEC>
 __global__ __launch_bounds__(1024) void add_rmsnorm_vec_kernel(
-    int d, float *__restrict__ x, const float *__restrict__ partials, int n_partials,
+    int rows, int rows_per_xcd, int d, float *__restrict__ x, const float *__restrict__ partials, int n_partials,
     size_t pstride, const T *__restrict__ gain, float eps, T *__restrict__ h, int h_tiled) {
   __shared__ float scratch[16];
-  const int r = blockIdx.x, nt = blockDim.x;
+  const int nt = blockDim.x;
+  const int r = rows_per_xcd > 0 ? (int)(blockIdx.x & 7) * rows_per_xcd + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  if (r >= rows) return;
   const size_t row = (size_t)r * d;
   float4 v[VEC];
   float ss = 0.f;
@@ -141,12 +147,17 @@ static void launch_add_rmsnorm_t(hipStream_t st, int rows, int d, float *x, cons
   if (d % 4 == 0 && d <= 16384) {
     // enough threads for one float4 each where possible; at least one wave
     const int quads = d / 4;
+    // many rows: 512 threads with two loads each in flight were measured faster than 1024 x 1
+    const int nt_max = (rows >= 2048 && quads <= 4 * 512) ? 512 : 1024;
     int nt = 64;
-    while (nt < 1024 && nt < quads) nt *= 2;
+    while (nt < nt_max && nt < quads) nt *= 2;
     const int vec = (quads + nt - 1) / nt;
-    if (vec <= 1) add_rmsnorm_vec_kernel<T, 1><<<rows, nt, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
-    else if (vec <= 2) add_rmsnorm_vec_kernel<T, 2><<<rows, nt, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
-    else add_rmsnorm_vec_kernel<T, 4><<<rows, nt, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+    // many rows into the tiled layout: a contiguous range of rows per XCD
+    const int rpx = (h_tiled && rows >= 256) ? ((rows + 7) / 8 + 7) / 8 * 8 : 0;
+    const int grid = rpx > 0 ? 8 * rpx : rows;
+    if (vec <= 1) add_rmsnorm_vec_kernel<T, 1><<<grid, nt, 0, st>>>(rows, rpx, d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+    else if (vec <= 2) add_rmsnorm_vec_kernel<T, 2><<<grid, nt, 0, st>>>(rows, rpx, d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
+    else add_rmsnorm_vec_kernel<T, 4><<<grid, nt, 0, st>>>(rows, rpx, d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
   } else {
     add_rmsnorm_kernel<T><<<rows, 256, 0, st>>>(d, x, partials, n_partials, ps, gain, eps, h, h_tiled);
   }

@@ -115,19 +115,25 @@ int launch_read_probe(hipStream_t st, const void *buf, size_t bytes, uint32_t *o
 // coordinates by the row's position and write queries (bf16, row-major), keys and values (into
 // their page slots).  The weight rows of every query / key head are interleaved so that the two
 // members of a rotary pair are neighbours in a thread's four consecutive outputs.
-template <int MB, bool SWIGLU, bool ROPE>
+// PAIR (plain sums, one K split, an even number of weight tiles): the workgroup takes weight tiles
+// 2 rt and 2 rt + 1 (w2 = the second one), so that every activation fragment it fetches serves two
+// weight tiles, as in the SwiGLU form; used where the tiles outnumber the CUs many times (LM head).
+enum { SKINNY_PLAIN = 0, SKINNY_SWIGLU = 1, SKINNY_PAIR = 2 };
+template <int MB, int MODE, bool ROPE>
 __global__ __launch_bounds__(256) void skinny_linear_kernel(
     int M, int N, int K, int units_per_wave, const bf16_t *__restrict__ a,
     const bf16_t *__restrict__ w, const bf16_t *__restrict__ w2, float *__restrict__ out,
     bf16_t *__restrict__ out_t, RopeOut ro) {
-  constexpr int NW = SWIGLU ? 2 : 1;
+  constexpr bool SWIGLU = MODE == SKINNY_SWIGLU, PAIR = MODE == SKINNY_PAIR;
+  constexpr int NW = MODE != SKINNY_PLAIN ? 2 : 1;
   __shared__ float4 red[4][NW][MB][4][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
   const int rt = blockIdx.x, split = blockIdx.y;
   const int U = K >> 6;
   const int u0 = (split * 4 + wave) * units_per_wave;
-  const bf16_t *wp = w + ((size_t)rt * U + u0) * 2048 + lane * 8;
-  const bf16_t *up = SWIGLU ? w2 + ((size_t)rt * U + u0) * 2048 + lane * 8 : nullptr;
+  const int wt = PAIR ? 2 * rt : rt;                          // weight tile of w (and of w2)
+  const bf16_t *wp = w + ((size_t)wt * U + u0) * 2048 + lane * 8;
+  const bf16_t *up = NW == 2 ? w2 + ((size_t)wt * U + u0) * 2048 + lane * 8 : nullptr;
   const bf16_t *ap = a + (size_t)u0 * 2048 + lane * 8;      // activation tile mb adds mb * U * 2048
   f32x16 acc[NW][MB];
 #pragma unroll
@@ -142,7 +148,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       wf[slot][c] = load_stream(wp + (size_t)u * 2048 + c * 512);
-      if (SWIGLU) uf[slot][c] = load_stream(up + (size_t)u * 2048 + c * 512);
+      if (NW == 2) uf[slot][c] = load_stream(up + (size_t)u * 2048 + c * 512);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
         af[slot][mb][c] = *(const v4u *)(ap + ((size_t)mb * U + u) * 2048 + c * 512);
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         acc[0][mb] = mfma32(wf[slot][c], af[slot][mb][c], acc[0][mb]);
-        if (SWIGLU) acc[NW - 1][mb] = mfma32(uf[slot][c], af[slot][mb][c], acc[NW - 1][mb]);
+        if (NW == 2) acc[NW - 1][mb] = mfma32(uf[slot][c], af[slot][mb][c], acc[NW - 1][mb]);
       }
   };
   issue(0, 0);
@@ -178,7 +184,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   __syncthreads();
   // thread (r4 = wave, lane) adds the four waves' quads in a fixed order and stores 4 outputs
   const int r4 = wave;
-  const int n = 32 * rt + 8 * r4 + 4 * h;
+  const int n = 32 * wt + 8 * r4 + 4 * h;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
     const int m = mb * 32 + nl;
@@ -202,6 +208,7 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
         rope_store_quad(ro, m, n, s[0], rope_load_quad(ro, m, n));
       } else {
         *(float4 *)(out + ((size_t)split * M + m) * N + n) = s[0];
+        if (PAIR) *(float4 *)(out + ((size_t)split * M + m) * N + n + 32) = s[NW - 1];
       }
     }
   }
@@ -234,17 +241,22 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
     MC_FAIL(MC_ERR_INVALID, "fused QKV output: one K split, N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
   const RopeOut none{};
   const int upw = units / (4 * n_splits);
-  dim3 grid(N / 32, n_splits);
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
   bf16_t *OT = (bf16_t *)out_t;
+  // many more tiles than CUs, plain sums: two weight tiles per workgroup
+  const bool pair = !rope && !w2 && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
+  dim3 grid(pair ? N / 64 : N / 32, n_splits);
+  if (pair) W2 = W + (size_t)units * 2048;                     // the tile after w's
   if (M <= 32) {
-    if (rope) skinny_linear_kernel<1, false, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
-    else if (w2) skinny_linear_kernel<1, true, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
-    else skinny_linear_kernel<1, false, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    if (rope) skinny_linear_kernel<1, SKINNY_PLAIN, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
+    else if (pair) skinny_linear_kernel<1, SKINNY_PAIR, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    else if (w2) skinny_linear_kernel<1, SKINNY_SWIGLU, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    else skinny_linear_kernel<1, SKINNY_PLAIN, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
   } else {
-    if (rope) skinny_linear_kernel<2, false, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
-    else if (w2) skinny_linear_kernel<2, true, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
-    else skinny_linear_kernel<2, false, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    if (rope) skinny_linear_kernel<2, SKINNY_PLAIN, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
+    else if (pair) skinny_linear_kernel<2, SKINNY_PAIR, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    else if (w2) skinny_linear_kernel<2, SKINNY_SWIGLU, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    else skinny_linear_kernel<2, SKINNY_PLAIN, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
   }
   MC_HIP(hipGetLastError());
   return MC_OK;

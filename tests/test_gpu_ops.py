@@ -274,7 +274,8 @@ def test_pack_tiled_roundtrip():
 @pytest.mark.parametrize("M,N,K,S", [
     (32, 256, 512, 1), (32, 256, 512, 2), (16, 3072, 2048, 0), (1, 128, 256, 1), (33, 128, 1024, 2),
     (64, 384, 768, 1), (5, 6144, 4096, 0), (32, 4096, 14336, 0),
-    (32, 128256, 4096, 0),         # the LM head of the 8B shape
+    (32, 128256, 4096, 0),         # the LM head of the 8B shape (two weight tiles per workgroup)
+    (40, 65664, 256, 1),           # the same form with two row tiles of activations
     (65, 128, 256, 1), (200, 256, 512, 1), (130, 384, 1024, 1), (4096, 128, 256, 1),
     # 256-row-tile GEMM: ragged last row tile, a last band of fewer than 8 row tiles, padding ids
     (3000, 4096, 256, 1), (2300, 5632, 512, 1),
@@ -360,12 +361,17 @@ def test_linear_swiglu_tiled(M, N, K):
 
 def test_tiled_outputs_of_rmsnorm_and_attention():
     import torch
-    rows, d = 37, 256
-    x = rnd(65, (rows, d)); g = 1 + rnd(66, (d,), 0.1)
-    gd, gv = to_dev(g, "bf16")
-    h_plain = binding.op_add_rmsnorm(torch.from_numpy(x.copy()).cuda(), None, gd, 1e-6)
-    h_tiled = binding.op_add_rmsnorm(torch.from_numpy(x.copy()).cuda(), None, gd, 1e-6, tiled=True)
-    assert torch.equal(binding.tiled_to_rowmajor(h_tiled.cpu(), rows, d), h_plain.cpu())
+    for rows, d in [(37, 256), (1001, 512)]:      # the second: many rows, dealt to the XCDs in contiguous ranges
+        x = rnd(65, (rows, d)); g = 1 + rnd(66, (d,), 0.1); p = rnd(67, (1, rows, d))
+        gd, gv = to_dev(g, "bf16")
+        h_plain = binding.op_add_rmsnorm(torch.from_numpy(x.copy()).cuda(), torch.from_numpy(p).cuda(), gd, 1e-6)
+        xt = torch.from_numpy(x.copy()).cuda()
+        h_tiled = binding.op_add_rmsnorm(xt, torch.from_numpy(p).cuda(), gd, 1e-6, tiled=True)
+        assert torch.equal(binding.tiled_to_rowmajor(h_tiled.cpu(), rows, d), h_plain.cpu())
+        want_x = x.astype(np.float64) + p[0]
+        np.testing.assert_allclose(xt.cpu().numpy(), want_x, rtol=0, atol=1e-6)
+        want_h = otf.rmsnorm(want_x, gv, 1e-6)
+        np.testing.assert_allclose(h_plain.float().cpu().numpy(), want_h, rtol=0, atol=TOL["bf16"] * 4)
     # attention output, [B][Hq*hd] tiled
     B, Hq, Hkv, hd, pg, P, t = 5, 4, 2, 64, 16, 40, 9
     kpd, vpd, _, _ = make_pools("bf16", 3, Hkv, pg, hd, 70)
