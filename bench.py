@@ -33,9 +33,9 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115740.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115734.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "3bdb0fff5b8c7236c4d208b5cf54074163c7a99bfb58cf37946bfe16511c3f26"}
+                   "sha256": "49398105877ad501c58f44e31e0ace18cfdf4d324d1cc63f0d8f91e7db087d70"}
 
 
 def measured_traffic_bytes(workload):
