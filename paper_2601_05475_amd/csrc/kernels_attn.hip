@@ -68,6 +68,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   // the wave index as a scalar: block ranges, page ids and addresses derived from it stay in
   // scalar registers and the loop branches are uniform
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int swap_addr = (lane ^ 32) << 2;    // ds_bpermute address of the lane with the other 16 keys
   const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, G = Hq / Hkv, B = a.n_cands;
   const bool is_prefix = (int)blockIdx.x < it.n_prefix_items;
 
@@ -191,10 +192,8 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
         for (int r = 0; r < 16; ++r)
           if (8 * (r >> 2) + 4 * h + (r & 3) >= n_valid) s[r] = -INFINITY;
       }
-      float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-#pragma unroll
-      for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float mx = max16f(s);
+      mx = fmaxf(mx, swap_halves(mx, swap_addr));
       // Lazy reference: m only has to stay within kTau of the true running maximum (then every
       // 2^(score - m) <= 2^kTau, harmless in fp32 and bf16); sums and weighted values are all taken
       // against the same m, so the normalised result does not depend on it.  The costly rescale of
@@ -217,7 +216,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
         s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m));
         rs += s[r];
       }
-      rs += __shfl_xor(rs, 32, 64);
+      rs += swap_halves(rs, swap_addr);
       l += rs;
       // probabilities as the B operand: slab sl holds keys kmap(8 sl .. 8 sl + 7)
       v4u pb[2];

@@ -54,6 +54,7 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hw = wave & 3, half = wave >> 2;    // head within the group, half of the item's rows
+  const int swap_addr = (lane ^ 32) << 2;       // ds_bpermute address of the lane with the other 16 keys
   const int Hq = a.n_q_heads, Hkv = a.n_kv_heads, G = Hq / Hkv, HG = (G + 3) / 4;
 
   int id = blockIdx.x;
@@ -147,10 +148,8 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
       for (int r = 0; r < 16; ++r)
         if (8 * (r >> 2) + 4 * h + (r & 3) >= lim) s[r] = -INFINITY;
     }
-    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-#pragma unroll
-    for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float mx = max16f(s);
+    mx = fmaxf(mx, swap_halves(mx, swap_addr));
     constexpr float kTau = 8.0f;
     const float mx2 = mx * scale2;                // -inf for a column that sees no key here
     if (__any(mx2 > m + kTau)) {
@@ -171,7 +170,7 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
       s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -mref));
       rs += s[r];
     }
-    rs += __shfl_xor(rs, 32, 64);
+    rs += swap_halves(rs, swap_addr);
     l += rs;
     v4u pb[2];
     pb[0] = v4u{pack2p_bf16(s[0], s[1]), pack2p_bf16(s[2], s[3]), pack2p_bf16(s[4], s[5]), pack2p_bf16(s[6], s[7])};
