@@ -359,6 +359,61 @@ def test_linear_swiglu_tiled(M, N, K):
     np.testing.assert_allclose(out, want, rtol=0, atol=TOL["bf16"] * np.abs(want).max())
 
 
+def test_scoring_size_gemms_on_sampled_rows():
+    """The many-row GEMMs at the sizes one scoring chunk of the 8B shape launches (8192 rows):
+    gate/up + SwiGLU 8192 x 14336 x 4096, down with the residual update 8192 x 4096 x 14336, QKV
+    with rotation and page stores 8192 x 6144 x 4096.  The oracle computes 24 sampled rows of each
+    (first, last, tile borders, random ones); every column of those rows is compared."""
+    import torch
+    M = 8192
+    rng = np.random.default_rng(180)
+    rows_s = np.unique(np.concatenate([[0, 31, 32, 255, 256, M - 257, M - 1], rng.integers(0, M, 17)]))
+    # gate/up + SwiGLU
+    d, F = 4096, 14336
+    a = rnd(181, (M, d)); wg = rnd(182, (F, d), 0.02); wu = rnd(183, (F, d), 0.02)
+    ad, av = to_dev(a, "bf16"); gd, gv = to_dev(wg, "bf16"); ud, uv = to_dev(wu, "bf16")
+    print("case: scoring-size swiglu", flush=True)
+    flat = binding.op_linear_swiglu(binding.op_pack_tiled(ad), binding.op_pack_tiled(gd), binding.op_pack_tiled(ud),
+                                    tiled_shape=(M, F, d))
+    act = binding.tiled_to_rowmajor(flat.cpu(), M, F)
+    want = otf.silu(otf.linear(av[rows_s], gv)) * otf.linear(av[rows_s], uv)
+    np.testing.assert_allclose(act[rows_s].float().numpy(), want, rtol=0, atol=TOL["bf16"] * np.abs(want).max())
+    del gd, ud, flat
+    # down projection adding to the residual stream; its input is the product above
+    wd_ = rnd(184, (d, F), 0.02); x = rnd(185, (M, d), 2.0)
+    dd, dv = to_dev(wd_, "bf16")
+    print("case: scoring-size accumulate", flush=True)
+    xd = torch.from_numpy(x.astype(np.float32)).cuda()
+    actd = act.cuda()
+    binding.op_linear_accumulate(binding.op_pack_tiled(actd), binding.op_pack_tiled(dd), xd, (M, d, F))
+    want = x[rows_s].astype(np.float32).astype(np.float64) + otf.linear(act[rows_s].float().numpy(), dv)
+    np.testing.assert_allclose(xd.cpu().numpy()[rows_s], want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
+    del dd, actd, xd
+    # QKV + rotation + page stores
+    Hq, Hkv, hd, pg, base, n_pos = 32, 8, 128, 64, 500000.0, 5120
+    nq = (Hq + 2 * Hkv) * hd
+    w = rnd(186, (nq, d), 0.02)
+    wd2, wv = to_dev(w, "bf16")
+    pos = rng.integers(0, n_pos, M).astype(np.int32)
+    slots = rng.permutation((M // pg + 2) * pg)[:M]
+    page, off = (slots // pg).astype(np.int32), (slots % pg).astype(np.int32)
+    kp = torch.zeros((M // pg + 2, Hkv, pg * hd), dtype=torch.bfloat16, device="cuda")
+    vp = torch.zeros_like(kp)
+    print("case: scoring-size fused qkv rope", flush=True)
+    q = binding.op_linear_qkv_rope(
+        binding.op_pack_tiled(ad), binding.op_pack_tiled(binding.interleave_qk_rows(wd2, Hq, Hkv, hd)), M, d,
+        torch.from_numpy(pos).cuda(), torch.from_numpy(page).cuda(), torch.from_numpy(off).cuda(),
+        Hq, Hkv, hd, pg, base, n_pos, kp, vp)
+    full = otf.linear(av[rows_s], wv).reshape(len(rows_s), Hq + 2 * Hkv, hd)
+    tol = TOL["bf16"] * np.abs(full).max()
+    np.testing.assert_allclose(q[torch.from_numpy(rows_s).cuda()].float().cpu().numpy(),
+                               otf.rope(full[:, :Hq], pos[rows_s], base), rtol=0, atol=tol)
+    ku, vu = binding.kv_pages_unpack(kp, vp, pg, hd)
+    kh, vh = ku.float().cpu().numpy(), vu.float().cpu().numpy()
+    np.testing.assert_allclose(kh[page[rows_s], :, off[rows_s], :], otf.rope(full[:, Hq:Hq + Hkv], pos[rows_s], base), rtol=0, atol=tol)
+    np.testing.assert_allclose(vh[page[rows_s], :, off[rows_s], :], full[:, Hq + Hkv:], rtol=0, atol=tol)
+
+
 def test_tiled_outputs_of_rmsnorm_and_attention():
     import torch
     for rows, d in [(37, 256), (1001, 512)]:      # the second: many rows, dealt to the XCDs in contiguous ranges
