@@ -5,20 +5,13 @@
 
 namespace mc {
 
-// max of three floats in one instruction.  Written out because fmaxf() of values the compiler
-// cannot prove to be canonical (MFMA results) costs an extra v_max(x, x) per input; none of the
-// callers can see a NaN.
-__device__ inline float max3f(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
-// maximum of the 16 values of an accumulator tile: eight instructions
+// maximum of the 16 values of an accumulator tile
 template <typename V16>
 __device__ inline float max16f(const V16 &s) {
-  const float t0 = max3f(s[0], s[1], s[2]), t1 = max3f(s[3], s[4], s[5]), t2 = max3f(s[6], s[7], s[8]);
-  const float t3 = max3f(s[9], s[10], s[11]), t4 = max3f(s[12], s[13], s[14]);
-  return max3f(max3f(t0, t1, t2), max3f(t3, t4, s[15]), t0);
+  float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+#pragma unroll
+  for (int r = 4; r < 16; r += 4) mx = fmaxf(mx, fmaxf(fmaxf(s[r], s[r + 1]), fmaxf(s[r + 2], s[r + 3])));
+  return mx;
 }
 
 // x of lane (l ^ 32).  `addr` = ((l ^ 32) << 2), computed once by the caller: __shfl_xor would

@@ -178,6 +178,45 @@ def test_attention_split_count_invariance_many_rows():
         np.testing.assert_allclose(o, outs[0], rtol=0, atol=8e-3)
 
 
+def test_kernels_are_run_to_run_identical():
+    """Every MFMA kernel twice on the same inputs: bit-identical outputs.  (A vector instruction
+    that reads matrix-core results before they have landed shows up here as last-bit noise long
+    before it shows up in a tolerance.)"""
+    import torch
+
+    def twice(name, f):
+        a = f(); torch.cuda.synchronize(); b = f(); torch.cuda.synchronize()
+        assert torch.equal(a, b), name
+
+    for M, N, K in [(1, 32000, 2048), (40, 3072, 2048), (32, 4096, 14336)]:
+        a = binding.op_pack_tiled(to_dev(rnd(190, (M, K)), "bf16")[0])
+        w = binding.op_pack_tiled(to_dev(rnd(191, (N, K), 0.05), "bf16")[0])
+        w2 = binding.op_pack_tiled(to_dev(rnd(192, (N, K), 0.05), "bf16")[0])
+        S = binding.op_linear_splits("bf16", M, N, K, True)
+        twice(f"few-row linear {M} {N} {K}", lambda: binding.op_linear(a, w, S, tiled_shape=(M, N, K)))
+        twice(f"few-row swiglu {M} {N} {K}", lambda: binding.op_linear_swiglu(a, w, w2, tiled_shape=(M, N, K)))
+    for M, N, K in [(232, 2048, 2048), (3000, 4096, 512)]:
+        a = binding.op_pack_tiled(to_dev(rnd(193, (M, K)), "bf16")[0])
+        w = binding.op_pack_tiled(to_dev(rnd(194, (N, K), 0.05), "bf16")[0])
+        twice(f"gemm {M} {N} {K}", lambda: binding.op_linear(a, w, 1, tiled_shape=(M, N, K)))
+    pg = 64
+    for Hq, Hkv, hd, P, rows, pos0 in [(32, 8, 64, 40, 40, 0), (32, 8, 128, 1024, 64, 960), (8, 2, 128, 330, 200, 130)]:
+        npg = -(-P // pg)
+        kp = to_dev(rnd(195, (npg, Hkv, pg * hd)), "bf16")[0]; vp = to_dev(rnd(196, (npg, Hkv, pg * hd)), "bf16")[0]
+        q = to_dev(rnd(197, (rows, Hq, hd)), "bf16")[0]
+        items = torch.tensor([[j, min(64, rows - j), pos0 + j, -1] for j in range(0, rows, 64)], dtype=torch.int32, device="cuda")
+        twice(f"prefill attention {Hq} {Hkv} {hd} {P} {rows}",
+              lambda: binding.op_attention_prefill(q, items, kp, vp, None, None, None, P, pg, False))
+    for B, Hq, Hkv, hd, P, t in [(16, 32, 8, 64, 1000, 3), (32, 32, 8, 128, 4096, 200), (64, 40, 8, 128, 2048, 70)]:
+        per = -(-t // pg)
+        kp = to_dev(rnd(198, (-(-P // pg), Hkv, pg * hd)), "bf16")[0]; vp = to_dev(rnd(199, (-(-P // pg), Hkv, pg * hd)), "bf16")[0]
+        ks = to_dev(rnd(200, (B * per, Hkv, pg * hd)), "bf16")[0]; vs = to_dev(rnd(201, (B * per, Hkv, pg * hd)), "bf16")[0]
+        table = torch.arange(B * per, dtype=torch.int32, device="cuda").reshape(B, per)
+        q = to_dev(rnd(202, (B, Hq, hd)), "bf16")[0]
+        twice(f"decode attention {B} {Hq} {Hkv} {hd} {P} {t}",
+              lambda: binding.op_attention_decode(q, kp, vp, ks, vs, table, P, t, pg))
+
+
 def test_sample_op_cases():
     import torch
     V, B = 128256, 32

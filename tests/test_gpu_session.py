@@ -224,6 +224,26 @@ def test_1b_shape_two_layer_twin():
         check_sampler_on_logits(steps[-1][b], wl.temperature, wl.top_k, us[b], toks[b], topk[b])
 
 
+def test_two_runs_give_identical_bits():
+    """No kernel on the path adds floating-point numbers in an order that depends on scheduling
+    (partial sums meet in a fixed order, no floating-point atomics): two sessions on the same
+    inputs (1B width, 2 layers, bf16 MFMA path with key splits, prefix of 1000 tokens, 70 steps
+    crossing a page) leave bit-identical logits at every step and sample identical tokens."""
+    wl = synth.WORKLOADS["1b"]
+    s = wl.shape.with_layers(2)
+    w = synth.make_weights(s, wl.seed_weights)
+    prefix, suffix = synth.prefix_tokens(wl, 1000), synth.suffix_tokens(wl, 16, 70)
+    us = synth.step_uniforms(wl, 16, 1)[0]
+    runs = []
+    for _ in range(2):
+        pl, steps, sess, _ = teacher_forced_gpu(s, w, prefix, suffix, wl.page_tokens, chunk_rows=256)
+        toks, topk = sess.sample(16, wl.temperature, wl.top_k, us, want_topk=True)
+        runs.append((pl, steps, toks, topk))
+        sess.close()
+    for x, y in zip(runs[0], runs[1]):
+        np.testing.assert_array_equal(x, y)
+
+
 def _as_f64(w):
     if isinstance(w, dict):
         return {k: _as_f64(v) for k, v in w.items()}
