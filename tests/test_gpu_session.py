@@ -242,6 +242,23 @@ def test_two_runs_give_identical_bits():
         sess.close()
     for x, y in zip(runs[0], runs[1]):
         np.testing.assert_array_equal(x, y)
+    # the scoring pass (many-row GEMMs with their fused epilogues, causal attention over
+    # prefix + own suffix, reward read-out), twice on one session and once on a fresh one
+    model = binding.Model(s, w)
+    lens = np.array([2300, 2048, 1, 777], np.int32)
+    sfx = synth.suffix_tokens(wl, 4, 2300)
+    ids, vals = synth.reward_token_ids(wl, 5), np.arange(5, dtype=np.float32)
+    outs = []
+    for rep in range(2):
+        sess = binding.Session(model, len(prefix), 4, 2300, wl.page_tokens, chunk_rows=4096)
+        sess.prefill_shared(prefix)
+        outs.append(sess.score_candidates(sfx, lens, ids, vals, 1.0))
+        if rep == 0:
+            outs.append(sess.score_candidates(sfx, lens, ids, vals, 1.0))
+        sess.close()
+    for o in outs[1:]:
+        for x, y in zip(outs[0], o):
+            np.testing.assert_array_equal(x, y)
 
 
 def _as_f64(w):
