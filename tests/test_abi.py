@@ -77,6 +77,22 @@ def test_invalid_configs_are_rejected(lib):
     assert lib.mc_op_tiled_bytes(33, 128) == 64 * 128 * 2 and lib.mc_op_tiled_bytes(33, 100) == 0
     assert lib.mc_op_linear_splits(1, 32, 6144, 4096, 1) >= 1
     assert lib.mc_op_sample(None, 0, 10, None, 0, 1.0, 5, None, None, None) == -1
+    # the fused many-row layers: bad arguments and shapes they do not cover are refused on the host
+    fake = C.c_void_p(256)                     # never dereferenced: the checks come first
+    assert lib.mc_op_linear_accumulate(None, 4096, 4096, 4096, None, None, None) == -1
+    assert lib.mc_op_linear_accumulate(None, 0, 4096, 4096, fake, fake, fake) == -1
+    assert lib.mc_op_linear_accumulate(None, 100, 4096, 4096, fake, fake, fake) == -5      # too few rows for 256-row tiles
+    assert lib.mc_op_linear_accumulate(None, 8192, 4000, 4096, fake, fake, fake) == -5     # N not a multiple of 256
+    args = [fake] * 9
+    assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 128, 64, 4096, 5e5, 100, *([None] * 9)) == -1
+    assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 126, 64, 4096, 5e5, 100, *args) == -1   # head_dim % 4
+    assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 128, 64, 4096, -1.0, 100, *args) == -1
+    out = (C.c_int32 * 8)()
+    assert lib.mc_op_attention_decode_plan(32, 32, 8, 128, 64, 4096, 1, 0, out) == 0 and out[2] >= 1
+    assert lib.mc_op_attention_decode_plan(32, 32, 8, 128, 64, 0, 0, 0, out) == -1           # no keys
+    assert lib.mc_op_attention_decode_plan(32, 32, 7, 128, 64, 4096, 1, 0, out) == -1        # heads do not divide
+    assert lib.mc_op_attention_decode_plan(32, 32, 8, 96, 64, 4096, 1, 0, out) == -5         # head_dim not covered
+    assert lib.mc_op_attention_decode_plan(32, 32, 8, 128, 16, 4096, 1, 0, out) == -5        # page size not covered
 
 
 def test_decode_attention_plan_covers_every_block_and_fits_its_workspace(lib):
