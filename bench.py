@@ -307,7 +307,7 @@ def main():
     t_gen = time.perf_counter() - t0
     t0 = time.perf_counter()
     model = binding.Model(s, weights)
-    sess = binding.Session(model, P, B, wl.n_steps, wl.page_tokens, chunk_rows=args.chunk_rows or 2048)
+    sess = binding.Session(model, P, B, wl.n_steps, wl.page_tokens, chunk_rows=args.chunk_rows or 4096)
     torch.cuda.synchronize()
     t_upload = time.perf_counter() - t0
 

@@ -273,11 +273,11 @@ def _as_f64(w):
 def test_8b_shape_layer_at_the_benchmark_launch_configuration():
     """One layer of the 8B shape at full width (4096 wide, 32/8 heads of 128, FFN 14336) in the
     configuration the benchmark times: 4096-token shared prefix, 32 candidates, 64-token pages,
-    2048-row prefill chunks, automatic key splits.  The vocabulary is cut to 32000 to keep the
-    oracle's float64 copies small (the LM-head shape itself is covered by an operation test).
-    Decode steps 1 and 2 for all candidates against the oracle.  A second session prefills in one
-    4096-row chunk, which is large enough for the O and down projections to add to the residual
-    stream in their own epilogue."""
+    automatic key splits.  The vocabulary is cut to 32000 to keep the oracle's float64 copies
+    small (the LM-head shape itself is covered by an operation test).  Decode steps 1 and 2 for
+    all candidates against the oracle.  One session prefills in 2048-row chunks; a second one in a
+    single 4096-row chunk, as the benchmark does, which is large enough for the O and down
+    projections to add to the residual stream in their own epilogue."""
     wl = synth.WORKLOADS["8b"]
     base = wl.shape
     s = synth.Shape("8b-L1-V32000", 1, base.d_model, base.n_q_heads, base.n_kv_heads, base.head_dim,
