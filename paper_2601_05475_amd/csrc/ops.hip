@@ -26,7 +26,7 @@ bool tiled_shapes_ok(int M, int N, int K) {
 static bool use_gemm256(int M, int N, int K, bool swiglu) {
   if (!gemm256_supported(M, N, K, swiglu)) return false;
   const long tiles = (long)((M + 255) / 256) * (N / (swiglu ? 128 : 256));
-  return tiles >= 192;
+  return tiles >= 160;
 }
 
 int linear_auto_splits(int dtype, int M, int N, int K, int tiled) {
