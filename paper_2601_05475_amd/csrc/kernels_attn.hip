@@ -192,16 +192,23 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
         for (int r = 0; r < 16; ++r)
           if (8 * (r >> 2) + 4 * h + (r & 3) >= n_valid) s[r] = -INFINITY;
       }
-      float mx = max16f(s);
-      mx = fmaxf(mx, swap_halves(mx, swap_addr));
-      // Lazy reference: m only has to stay within kTau of the true running maximum (then every
-      // 2^(score - m) <= 2^kTau, harmless in fp32 and bf16); sums and weighted values are all taken
-      // against the same m, so the normalised result does not depend on it.  The costly rescale of
-      // the 16 * HD/32 accumulators then happens in the first block(s) only.
-      constexpr float kTau = 8.0f;
-      const float mx2 = mx * scale2;              // finite: a processed block has a valid key
-      if (__any(mx2 > m + kTau)) {
-        const float m_new = fmaxf(m, mx2);
+      // Lazy reference: sums and weighted values are all taken against the same m, so the
+      // normalised result does not depend on it; m only has to keep the numbers in range.  The
+      // probabilities are therefore computed against m as it stands, and only if a lane's sum
+      // leaves the range (a score far above m, or the first block, where m = -inf gives inf or
+      // NaN) the block's maximum is taken, m moved there and the 16 * HD/32 accumulators
+      // rescaled.  The common case spends no instruction on maxima.
+      f32x16 p;
+      float rs = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m));
+        rs += p[r];
+      }
+      if (__any(!(rs <= kSoftmaxSumLimit))) {
+        float mx = max16f(s);
+        mx = fmaxf(mx, swap_halves(mx, swap_addr));
+        const float m_new = fmaxf(m, mx * scale2);              // finite: a processed block has a valid key
         const float corr = __builtin_amdgcn_exp2f(m - m_new);   // m = -inf at the start: 0
         l *= corr;
         m = m_new;
@@ -209,19 +216,19 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
         for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[dt][r] *= corr;
-      }
-      float rs = 0.f;
+        rs = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m));
-        rs += s[r];
+        for (int r = 0; r < 16; ++r) {
+          p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m));
+          rs += p[r];
+        }
       }
       rs += swap_halves(rs, swap_addr);
       l += rs;
       // probabilities as the B operand: slab sl holds keys kmap(8 sl .. 8 sl + 7)
       v4u pb[2];
-      pb[0] = make_v4u(pack2_bf16(s[0], s[1]), pack2_bf16(s[2], s[3]), pack2_bf16(s[4], s[5]), pack2_bf16(s[6], s[7]));
-      pb[1] = make_v4u(pack2_bf16(s[8], s[9]), pack2_bf16(s[10], s[11]), pack2_bf16(s[12], s[13]), pack2_bf16(s[14], s[15]));
+      pb[0] = make_v4u(pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]));
+      pb[1] = make_v4u(pack2_bf16(p[8], p[9]), pack2_bf16(p[10], p[11]), pack2_bf16(p[12], p[13]), pack2_bf16(p[14], p[15]));
 #pragma unroll
       for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll

@@ -5,6 +5,12 @@
 
 namespace mc {
 
+// Attention kernels: a lane's sum of 16 probabilities above this means the reference maximum of
+// the online softmax lags too far behind (or does not exist yet) and has to be moved.  2^20:
+// far from overflow even after thousands of keys, and reached only when a score exceeds the
+// reference by more than 16 in base-2 units.
+constexpr float kSoftmaxSumLimit = 1048576.0f;
+
 // maximum of the 16 values of an accumulator tile
 template <typename V16>
 __device__ inline float max16f(const V16 &s) {

@@ -148,12 +148,22 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
       for (int r = 0; r < 16; ++r)
         if (8 * (r >> 2) + 4 * h + (r & 3) >= lim) s[r] = -INFINITY;
     }
-    float mx = max16f(s);
-    mx = fmaxf(mx, swap_halves(mx, swap_addr));
-    constexpr float kTau = 8.0f;
-    const float mx2 = mx * scale2;                // -inf for a column that sees no key here
-    if (__any(mx2 > m + kTau)) {
-      const float m_new = fmaxf(m, mx2);
+    // Probabilities against the reference m as it stands (see the decode kernel: any reference
+    // gives the same normalised result, it only has to keep the numbers in range).  Only if a
+    // lane's sum leaves the range - a score far above the reference, or no reference yet (m =
+    // -inf yields inf or NaN) - the block's maximum is taken, the reference moved and the
+    // accumulators rescaled; the common case spends no instruction on maxima.
+    f32x16 p;
+    float rs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -m));
+      rs += p[r];
+    }
+    if (__any(!(rs <= kSoftmaxSumLimit))) {
+      float mx = max16f(s);
+      mx = fmaxf(mx, swap_halves(mx, swap_addr));
+      const float m_new = fmaxf(m, mx * scale2);    // stays -inf for a column that has seen no key
       const float corr = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - m_new);
       l *= corr;
       m = m_new;
@@ -161,20 +171,20 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
       for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] *= corr;
-    }
-    // a column with no visible key so far keeps m = -inf: use 0 as reference, all its p are 0
-    const float mref = (m == -INFINITY) ? 0.f : m;
-    float rs = 0.f;
+      // a column with no visible key so far: 0 as reference, all its p are 0
+      const float mref = (m == -INFINITY) ? 0.f : m;
+      rs = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      s[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -mref));
-      rs += s[r];
+      for (int r = 0; r < 16; ++r) {
+        p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], scale2, -mref));
+        rs += p[r];
+      }
     }
     rs += swap_halves(rs, swap_addr);
     l += rs;
     v4u pb[2];
-    pb[0] = v4u{pack2p_bf16(s[0], s[1]), pack2p_bf16(s[2], s[3]), pack2p_bf16(s[4], s[5]), pack2p_bf16(s[6], s[7])};
-    pb[1] = v4u{pack2p_bf16(s[8], s[9]), pack2p_bf16(s[10], s[11]), pack2p_bf16(s[12], s[13]), pack2p_bf16(s[14], s[15])};
+    pb[0] = v4u{pack2p_bf16(p[0], p[1]), pack2p_bf16(p[2], p[3]), pack2p_bf16(p[4], p[5]), pack2p_bf16(p[6], p[7])};
+    pb[1] = v4u{pack2p_bf16(p[8], p[9]), pack2p_bf16(p[10], p[11]), pack2p_bf16(p[12], p[13]), pack2p_bf16(p[14], p[15])};
 #pragma unroll
     for (int dt = 0; dt < HD / 32; ++dt)
 #pragma unroll
