@@ -35,7 +35,7 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
 TRAFFIC_GATE_UP = {"fetch_kib": 115734.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "49398105877ad501c58f44e31e0ace18cfdf4d324d1cc63f0d8f91e7db087d70"}
+                   "sha256": "ebeb820df8bf1787cf57798156687d210a6b1877e0ad01f6d7dd56ff0013f2a8"}
 
 
 def measured_traffic_bytes(workload):

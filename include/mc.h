@@ -240,8 +240,11 @@ typedef enum {
   MC_K_LINEAR_GATE_UP, MC_K_LINEAR_DOWN, MC_K_LINEAR_LM_HEAD, MC_K_SAMPLE,
   MC_K_REWARD, MC_K_COUNT
 } mc_kernel_class;
-/* Bracket every `stride`-th launch of one kernel class with HIP events on the session
- * stream (kernel_class = MC_K_NONE switches it off; at most 8192 launches recorded). */
+/* Time every `stride`-th launch of one kernel class with HIP events on the session stream
+ * (kernel_class = MC_K_NONE switches it off; at most 8192 launches recorded).  For the few-row
+ * gate/up layer and for decode attention (+ merge) the events are attached to the kernel launches
+ * themselves and carry the kernels' own begin and end times; for the other classes they are
+ * recorded on the stream before and after the launch, which adds a few microseconds. */
 int mc_profile_begin(mc_session *s, int32_t kernel_class, int32_t stride);
 /* Synchronise, then report how many launches were timed and their total duration. */
 int mc_profile_end(mc_session *s, int32_t *n_timed, double *total_ms);

@@ -156,6 +156,15 @@ struct RopeOut {
   const double2 *table;                          // launch_rope_table
   int32_t Hq, Hkv, hd, pg;
 };
+// Events a profiling scope hands to the next launcher that knows how to attach them to its
+// kernels (hipExtLaunchKernelGGL: the events then carry the kernel's own begin / end times, with
+// no barrier packets around the launch).  A launcher takes them (which clears them); start goes to
+// its first kernel, stop to its last.
+struct LaunchEvents {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+void offer_launch_events(hipEvent_t start, hipEvent_t stop);
+LaunchEvents take_launch_events();
 bool tiled_shapes_ok(int M, int N, int K);
 // Tiled bf16 layers that finish their outputs themselves.  The fused QKV layer (rotation and
 // query / key / value stores in the epilogue, w with interleaved query / key rows) exists for few

@@ -23,6 +23,8 @@
 // O^T += V^T P^T because V's fragments list their keys in the accumulator's order.
 #include "kernels_mfma.h"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 namespace mc {
@@ -406,10 +408,21 @@ static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, co
                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024));
     attr_set = true;
   }
-  decode_attention_kernel<HD><<<it.n_prefix_items + it.n_suffix_items, 256, lds, st>>>(a, it, part_o, part_ml);
+  // events offered by a profiling scope: begin of the first kernel, end of the second
+  const LaunchEvents ev = take_launch_events();
+  if (ev.start)
+    hipExtLaunchKernelGGL(decode_attention_kernel<HD>, dim3(it.n_prefix_items + it.n_suffix_items), dim3(256),
+                          (uint32_t)lds, st, ev.start, nullptr, 0, a, it, part_o, part_ml);
+  else
+    decode_attention_kernel<HD><<<it.n_prefix_items + it.n_suffix_items, 256, lds, st>>>(a, it, part_o, part_ml);
   MC_HIP(hipGetLastError());
-  decode_attention_merge_kernel<HD><<<(unsigned)rows, HD, 0, st>>>(
-      n_parts, a.n_cands, a.n_q_heads, part_o, part_ml, (bf16_t *)a.out, a.out_tiled);
+  if (ev.stop)
+    hipExtLaunchKernelGGL(decode_attention_merge_kernel<HD>, dim3((unsigned)rows), dim3(HD), 0, st, nullptr, ev.stop, 0,
+                          n_parts, a.n_cands, a.n_q_heads, (const float *)part_o, (const float *)part_ml,
+                          (bf16_t *)a.out, a.out_tiled);
+  else
+    decode_attention_merge_kernel<HD><<<(unsigned)rows, HD, 0, st>>>(
+        n_parts, a.n_cands, a.n_q_heads, part_o, part_ml, (bf16_t *)a.out, a.out_tiled);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }

@@ -15,6 +15,8 @@
 // directly in the A (or B) operand registers of four consecutive MFMA steps.
 #include "kernels_mfma.h"
 
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 namespace mc {
@@ -247,16 +249,24 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   const bool pair = !rope && !w2 && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
   dim3 grid(pair ? N / 64 : N / 32, n_splits);
   if (pair) W2 = W + (size_t)units * 2048;                     // the tile after w's
+  // events offered by a profiling scope ride on the launch itself
+  const LaunchEvents ev = take_launch_events();
+  auto go = [&](auto kernel, const RopeOut &ro) {
+    if (ev.start || ev.stop)
+      hipExtLaunchKernelGGL(kernel, grid, dim3(256), 0, st, ev.start, ev.stop, 0, M, N, K, upw, A, W, W2, out, OT, ro);
+    else
+      kernel<<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, ro);
+  };
   if (M <= 32) {
-    if (rope) skinny_linear_kernel<1, SKINNY_PLAIN, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
-    else if (pair) skinny_linear_kernel<1, SKINNY_PAIR, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
-    else if (w2) skinny_linear_kernel<1, SKINNY_SWIGLU, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
-    else skinny_linear_kernel<1, SKINNY_PLAIN, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    if (rope) go(skinny_linear_kernel<1, SKINNY_PLAIN, true>, *rope);
+    else if (pair) go(skinny_linear_kernel<1, SKINNY_PAIR, false>, none);
+    else if (w2) go(skinny_linear_kernel<1, SKINNY_SWIGLU, false>, none);
+    else go(skinny_linear_kernel<1, SKINNY_PLAIN, false>, none);
   } else {
-    if (rope) skinny_linear_kernel<2, SKINNY_PLAIN, true><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, *rope);
-    else if (pair) skinny_linear_kernel<2, SKINNY_PAIR, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
-    else if (w2) skinny_linear_kernel<2, SKINNY_SWIGLU, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
-    else skinny_linear_kernel<2, SKINNY_PLAIN, false><<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, none);
+    if (rope) go(skinny_linear_kernel<2, SKINNY_PLAIN, true>, *rope);
+    else if (pair) go(skinny_linear_kernel<2, SKINNY_PAIR, false>, none);
+    else if (w2) go(skinny_linear_kernel<2, SKINNY_SWIGLU, false>, none);
+    else go(skinny_linear_kernel<2, SKINNY_PLAIN, false>, none);
   }
   MC_HIP(hipGetLastError());
   return MC_OK;

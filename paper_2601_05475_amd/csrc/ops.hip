@@ -16,6 +16,17 @@ int launch_linear_swiglu_generic(hipStream_t st, int dtype, int M, int N, int K,
 
 // Shapes the tiled bf16 kernels cover for every row count: few rows go to the weight-streaming
 // kernel (K % 256), many rows to the tiled GEMM (N % 128).
+static thread_local LaunchEvents tl_launch_events;
+void offer_launch_events(hipEvent_t start, hipEvent_t stop) {
+  tl_launch_events.start = start;
+  tl_launch_events.stop = stop;
+}
+LaunchEvents take_launch_events() {
+  const LaunchEvents e = tl_launch_events;
+  tl_launch_events = LaunchEvents{};
+  return e;
+}
+
 bool tiled_shapes_ok(int M, int N, int K) {
   (void)M;
   return N % 128 == 0 && K % 256 == 0;

@@ -359,18 +359,33 @@ struct mc_session {
 
 namespace mc {
 
+// Times the launches made while it lives, if its class is the one being profiled and this
+// occurrence is sampled.  on_kernel: the launcher inside the scope attaches the two events to its
+// own kernels (the few-row linear layers and decode attention do), so they carry the kernels'
+// begin and end times; otherwise the events are recorded on the stream before and after the
+// launches, which adds a few microseconds of event handling to what they enclose.
 struct ProfScope {
   mc_session *s;
-  bool active = false;
-  ProfScope(mc_session *s_, int cls) : s(s_) {
+  bool active = false, on_kernel = false;
+  ProfScope(mc_session *s_, int cls, bool on_kernel_ = false) : s(s_), on_kernel(on_kernel_) {
     if (s->prof_class != cls || cls == MC_K_NONE) return;
     if ((s->prof_seen++ % s->prof_stride) != 0 || s->prof_n >= kProfCap) return;
     if ((size_t)(2 * s->prof_n + 2) > s->prof_ev.size()) return;
-    active = hipEventRecord(s->prof_ev[2 * s->prof_n], s->stream) == hipSuccess;
+    if (on_kernel) {
+      offer_launch_events(s->prof_ev[2 * s->prof_n], s->prof_ev[2 * s->prof_n + 1]);
+      active = true;
+    } else {
+      active = hipEventRecord(s->prof_ev[2 * s->prof_n], s->stream) == hipSuccess;
+    }
   }
   ~ProfScope() {
     if (!active) return;
-    (void)hipEventRecord(s->prof_ev[2 * s->prof_n + 1], s->stream);
+    if (on_kernel) {
+      const LaunchEvents left = take_launch_events();     // not taken: the launch failed before it got there
+      if (left.start || left.stop) return;
+    } else {
+      (void)hipEventRecord(s->prof_ev[2 * s->prof_n + 1], s->stream);
+    }
     s->prof_n++;
   }
 };
@@ -496,7 +511,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       a.row_cand = s->dropped_any ? row_tab : nullptr;
       a.workspace = s->ptr<void>(L.attn_ws); a.workspace_bytes = L.attn_ws_bytes; a.out = ao;
       a.out_tiled = tl;
-      ProfScope ps(s, MC_K_ATTN_DECODE);
+      ProfScope ps(s, MC_K_ATTN_DECODE, dt == MC_BF16 && decode_attention_mfma_supported(a));
       MC_TRY(launch_attention_decode(st, dt, a));
     } else {
       if (tl && prefill_attention_mfma_supported(s->p.page_tokens, c.head_dim, c.n_q_heads, c.n_kv_heads)) {
@@ -538,7 +553,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       MC_TRY(launch_add_rmsnorm(st, dt, rows, d, x, part, s2, W.ffn_norm, c.rms_eps, h, tl));
     }
     {
-      ProfScope ps(s, MC_K_LINEAR_GATE_UP);
+      ProfScope ps(s, MC_K_LINEAR_GATE_UP, tl && rows <= 64);
       MC_TRY(launch_linear_swiglu(st, dt, rows, c.d_ffn, d, h, W.w_gate, W.w_up, act, tl));
     }
     const bool acc_d = tl && linear_accumulate_fused(rows, d, c.d_ffn);

@@ -261,6 +261,32 @@ def test_two_runs_give_identical_bits():
             np.testing.assert_array_equal(x, y)
 
 
+def test_profiling_events_do_not_change_results():
+    """Timing a kernel class (events attached to the launches for the few-row gate/up layer and
+    decode attention, recorded around the launch for the others) reports one duration per
+    sampled launch and leaves the logits bit-identical."""
+    wl = synth.WORKLOADS["1b"]
+    s = wl.shape.with_layers(2)
+    w = synth.make_weights(s, wl.seed_weights)
+    prefix, suffix = synth.prefix_tokens(wl, 300), synth.suffix_tokens(wl, 16, 6)
+    model = binding.Model(s, w)
+    ref = None
+    for cls, per_step in [(None, 0), ("linear_gate_up", 2), ("attn_decode", 2), ("linear_down", 2), ("add_rmsnorm", 5)]:
+        sess = binding.Session(model, len(prefix), 16, 8, wl.page_tokens, chunk_rows=128)
+        sess.prefill_shared(prefix)
+        if cls:
+            sess.profile_begin(cls, 1)
+        steps = _decode_all(sess, suffix)
+        if cls:
+            n, ms = sess.profile_end()
+            assert n == per_step * suffix.shape[1], (cls, n)
+            assert 0.0 < ms / n < 1.0, (cls, ms / n)          # a few microseconds each, not garbage
+            np.testing.assert_array_equal(steps, ref)
+        else:
+            ref = steps
+        sess.close()
+
+
 def _as_f64(w):
     if isinstance(w, dict):
         return {k: _as_f64(v) for k, v in w.items()}
