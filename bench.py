@@ -33,9 +33,9 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115734.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115741.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "ebeb820df8bf1787cf57798156687d210a6b1877e0ad01f6d7dd56ff0013f2a8"}
+                   "sha256": "33c05e695d525fe32bb3d1b95672a1d3a8d23b4c4b31c03331205c72bf8ea464"}
 
 
 def measured_traffic_bytes(workload):

@@ -130,7 +130,16 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   constexpr int NW = MODE != SKINNY_PLAIN ? 2 : 1;
   __shared__ float4 red[4][NW][MB][4][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
-  const int rt = blockIdx.x, split = blockIdx.y;
+  // PAIR: the grid is rounded up to a multiple of 8 and every XCD (workgroups are dealt to them
+  // round-robin) takes a contiguous range of tile pairs, so that the 256-byte pieces its
+  // workgroups write into a row of the output sit next to each other in one L2
+  int rt = blockIdx.x;
+  if (PAIR) {
+    const int per_xcd = gridDim.x >> 3;
+    rt = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (rt >= N / 64) return;
+  }
+  const int split = blockIdx.y;
   const int U = K >> 6;
   const int u0 = (split * 4 + wave) * units_per_wave;
   const int wt = PAIR ? 2 * rt : rt;                          // weight tile of w (and of w2)
@@ -247,7 +256,7 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   bf16_t *OT = (bf16_t *)out_t;
   // many more tiles than CUs, plain sums: two weight tiles per workgroup
   const bool pair = !rope && !w2 && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
-  dim3 grid(pair ? N / 64 : N / 32, n_splits);
+  dim3 grid(pair ? (N / 64 + 7) / 8 * 8 : N / 32, n_splits);
   if (pair) W2 = W + (size_t)units * 2048;                     // the tile after w's
   // events offered by a profiling scope ride on the launch itself
   const LaunchEvents ev = take_launch_events();
