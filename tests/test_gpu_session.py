@@ -330,6 +330,46 @@ def test_8b_shape_layer_at_the_benchmark_launch_configuration():
     assert_logits_close(steps2, want.transpose(1, 0, 2), "bf16", "decode logits (4096-row chunk)", fl.transpose(1, 0, 2))
 
 
+@pytest.mark.timeout(1500)
+def test_8b_shape_layer_scoring_in_one_large_chunk():
+    """mc_score_candidates on one layer of the 8B shape at full width (vocabulary cut to 32000),
+    4096-token shared prefix, four ragged suffixes (1024, 1024, 700 and 1 tokens) scored as one
+    chunk of 2749 rows: large enough for the QKV rotation and the residual updates to run in the
+    GEMM epilogues, as in the reranking benchmark.  Last-position logits against the oracle; the
+    reward log-probs, scores and ranks against the oracle's rules applied to the device logits."""
+    wl = synth.WORKLOADS["8b"]
+    base = wl.shape
+    s = synth.Shape("8b-L1-V32000", 1, base.d_model, base.n_q_heads, base.n_kv_heads, base.head_dim,
+                    base.d_ffn, 32000, base.rope_base, base.dtype, base.rms_eps)
+    w = synth.make_weights(s, wl.seed_weights)
+    prefix = synth.tokens(11, 1, (wl.prefix_len,), s.vocab)
+    lens = np.array([1024, 1024, 700, 1], np.int32)
+    suffix = synth.tokens(11, 2, (4, 1024), s.vocab)
+    ids = synth.tokens(11, 3, (64,), s.vocab)
+    ids = np.unique(ids)[:8].astype(np.int32)
+    vals = np.arange(8, dtype=np.float32)
+    print("case: 8b layer scoring twin", s, flush=True)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, wl.prefix_len, 4, 1024, wl.page_tokens, chunk_rows=8192)
+    sess.prefill_shared(prefix)
+    lp, sc, rk = sess.score_candidates(suffix, lens, ids, vals, 1.0)
+    got = sess.logits(4)
+    sess.close()
+    want_lp = np.stack([osamp.reward_logprobs(got[b], ids) for b in range(4)])
+    np.testing.assert_allclose(lp, want_lp, rtol=0, atol=1e-4)
+    want_sc = np.array([osamp.expected_value(want_lp[b], vals, 1.0) for b in range(4)])
+    np.testing.assert_allclose(sc, want_sc, rtol=0, atol=1e-4)
+    assert list(rk) == list(osamp.rank(sc))
+    w64 = _as_f64(synth.weights_as_f32(w))
+    last = lambda out: np.stack([out[b, lens[b] - 1] for b in range(4)])
+    print("oracle: exact", flush=True)
+    _, want = otf.forward_shared(oracle_config(s, exact=True), w64, prefix, suffix)
+    want = last(want)
+    print("oracle: bf16 tensors", flush=True)
+    _, fl = otf.forward_shared(oracle_config(s, exact=False), w64, prefix, suffix)
+    assert_logits_close(got, want, "bf16", "scoring logits", last(fl))
+
+
 # ---------------------------------------------------------------- growing the shared prefix
 def _decode_all(sess, suffix):
     out = []
