@@ -331,6 +331,35 @@ def test_8b_shape_layer_at_the_benchmark_launch_configuration():
 
 
 @pytest.mark.timeout(1500)
+def test_32b_shape_layer_twin():
+    """One layer of the 32B shape at full width (5120 wide, 40/8 heads of 128: five query heads
+    per KV head; FFN 27648; vocabulary cut to 32000) with 64 candidates, i.e. two 32-row
+    activation tiles in every weight-streaming layer and 320 query rows per KV head in decode
+    attention.  Prefix of 1000 tokens (ragged against pages and blocks), decode steps 1..3."""
+    wl = synth.WORKLOADS["32b"]
+    base = wl.shape
+    s = synth.Shape("32b-L1-V32000", 1, base.d_model, base.n_q_heads, base.n_kv_heads, base.head_dim,
+                    base.d_ffn, 32000, base.rope_base, base.dtype, base.rms_eps)
+    w = synth.make_weights(s, wl.seed_weights)
+    prefix = synth.tokens(12, 1, (1000,), s.vocab)
+    suffix = synth.tokens(12, 2, (wl.n_cands, 3), s.vocab)
+    print("case: 32b layer twin", s, flush=True)
+    pl, steps, sess, _ = teacher_forced_gpu(s, w, prefix, suffix, wl.page_tokens, chunk_rows=1024, max_suffix=64)
+    us = synth.step_uniforms(wl, wl.n_cands, 1)[0]
+    toks, topk = sess.sample(wl.n_cands, wl.temperature, wl.top_k, us, want_topk=True)
+    sess.close()
+    for b in range(0, wl.n_cands, 7):
+        check_sampler_on_logits(steps[-1][b], wl.temperature, wl.top_k, us[b], toks[b], topk[b])
+    w64 = _as_f64(synth.weights_as_f32(w))
+    print("oracle: exact", flush=True)
+    want_pl, want = otf.forward_shared(oracle_config(s, exact=True), w64, prefix, suffix)
+    print("oracle: bf16 tensors", flush=True)
+    fl_pl, fl = otf.forward_shared(oracle_config(s, exact=False), w64, prefix, suffix)
+    assert_logits_close(pl[None], want_pl[None], "bf16", "prefix logits", fl_pl[None])
+    assert_logits_close(steps, want.transpose(1, 0, 2), "bf16", "decode logits", fl.transpose(1, 0, 2))
+
+
+@pytest.mark.timeout(1500)
 def test_8b_shape_layer_scoring_in_one_large_chunk():
     """mc_score_candidates on one layer of the 8B shape at full width (vocabulary cut to 32000),
     4096-token shared prefix, four ragged suffixes (1024, 1024, 700 and 1 tokens) scored as one
