@@ -117,9 +117,11 @@ int launch_read_probe(hipStream_t st, const void *buf, size_t bytes, uint32_t *o
 // coordinates by the row's position and write queries (bf16, row-major), keys and values (into
 // their page slots).  The weight rows of every query / key head are interleaved so that the two
 // members of a rotary pair are neighbours in a thread's four consecutive outputs.
-// PAIR (plain sums, one K split, an even number of weight tiles): the workgroup takes weight tiles
-// 2 rt and 2 rt + 1 (w2 = the second one), so that every activation fragment it fetches serves two
-// weight tiles, as in the SwiGLU form; used where the tiles outnumber the CUs many times (LM head).
+// PAIR (plain sums, one K split, an even number of weight tiles; used where the tiles outnumber
+// the CUs many times: the LM head): every WAVE takes its own pair of weight tiles (w2 = the second
+// one) over the whole K range, so an activation fragment serves two weight tiles, the four waves
+// of a workgroup fetch the same activation units at about the same time (L1), and there is
+// nothing to reduce across waves: each wave stores its own 64 output columns.
 enum { SKINNY_PLAIN = 0, SKINNY_SWIGLU = 1, SKINNY_PAIR = 2 };
 template <int MB, int MODE, bool ROPE>
 __global__ __launch_bounds__(256) void skinny_linear_kernel(
@@ -131,17 +133,17 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   __shared__ float4 red[4][NW][MB][4][64];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
   // PAIR: the grid is rounded up to a multiple of 8 and every XCD (workgroups are dealt to them
-  // round-robin) takes a contiguous range of tile pairs, so that the 256-byte pieces its
-  // workgroups write into a row of the output sit next to each other in one L2
+  // round-robin) takes a contiguous range of tile pairs, so that the pieces its workgroups write
+  // into a row of the output sit next to each other in one L2
   int rt = blockIdx.x;
   if (PAIR) {
     const int per_xcd = gridDim.x >> 3;
-    rt = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
-    if (rt >= N / 64) return;
+    rt = 4 * ((int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3)) + wave;   // this wave's tile pair
+    if (rt >= N / 64) return;                                 // no barrier on this path
   }
   const int split = blockIdx.y;
   const int U = K >> 6;
-  const int u0 = (split * 4 + wave) * units_per_wave;
+  const int u0 = PAIR ? 0 : (split * 4 + wave) * units_per_wave;
   const int wt = PAIR ? 2 * rt : rt;                          // weight tile of w (and of w2)
   const bf16_t *wp = w + ((size_t)wt * U + u0) * 2048 + lane * 8;
   const bf16_t *up = NW == 2 ? w2 + ((size_t)wt * U + u0) * 2048 + lane * 8 : nullptr;
@@ -184,6 +186,22 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   }
   if (u < units_per_wave) compute(0);
 
+  if (PAIR) {
+    // the wave's own sums: lane (nl, h) holds row nl of the tile and, per register quad r4,
+    // columns 8 r4 + 4 h .. + 3
+#pragma unroll
+    for (int i = 0; i < NW; ++i)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const int m = mb * 32 + nl;
+        if (m >= M) continue;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *(float4 *)(out + (size_t)m * N + 32 * (wt + i) + 8 * r4 + 4 * h) =
+              make_float4(acc[i][mb][4 * r4], acc[i][mb][4 * r4 + 1], acc[i][mb][4 * r4 + 2], acc[i][mb][4 * r4 + 3]);
+      }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < NW; ++i)
 #pragma unroll
@@ -219,7 +237,6 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
         rope_store_quad(ro, m, n, s[0], rope_load_quad(ro, m, n));
       } else {
         *(float4 *)(out + ((size_t)split * M + m) * N + n) = s[0];
-        if (PAIR) *(float4 *)(out + ((size_t)split * M + m) * N + n + 32) = s[NW - 1];
       }
     }
   }
@@ -251,13 +268,16 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   if (rope && (w2 || n_splits != 1 || rope->hd % 4 || N != (rope->Hq + 2 * rope->Hkv) * rope->hd))
     MC_FAIL(MC_ERR_INVALID, "fused QKV output: one K split, N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
   const RopeOut none{};
-  const int upw = units / (4 * n_splits);
+  int upw = units / (4 * n_splits);
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
   bf16_t *OT = (bf16_t *)out_t;
   // many more tiles than CUs, plain sums: two weight tiles per workgroup
   const bool pair = !rope && !w2 && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
-  dim3 grid(pair ? (N / 64 + 7) / 8 * 8 : N / 32, n_splits);
-  if (pair) W2 = W + (size_t)units * 2048;                     // the tile after w's
+  dim3 grid(pair ? ((N / 64 + 3) / 4 + 7) / 8 * 8 : N / 32, n_splits);
+  if (pair) {
+    W2 = W + (size_t)units * 2048;                             // the tile after w's
+    upw = units;                                               // every wave walks the whole K range
+  }
   // events offered by a profiling scope ride on the launch itself
   const LaunchEvents ev = take_launch_events();
   auto go = [&](auto kernel, const RopeOut &ro) {
