@@ -29,3 +29,37 @@ def page_tables(n_cands: int, n_steps: int, page_tokens: int, free_list) -> np.n
 def slot_of(table: np.ndarray, b: int, j: int, page_tokens: int):
     """(page id, offset in page) of candidate b's j-th suffix token."""
     return int(table[b, j // page_tokens]), j % page_tokens
+
+
+class PagePool:
+    """The same rule with candidates that leave early: the free list is a queue.  A candidate
+    that is dropped gives its pages back to the tail of the queue (candidates in ascending index,
+    each one's pages in the order it took them); at a page boundary only the candidates still
+    decoding are visited.  Written event by event so that a test can replay a call sequence."""
+
+    def __init__(self, n_cands: int, page_tokens: int, free_list):
+        self.free = list(free_list)
+        self.page_tokens = page_tokens
+        self.alive = list(range(n_cands))
+        self.pages = {b: [] for b in range(n_cands)}
+        self.length = 0                                  # common suffix length
+
+    def append(self, n_tokens: int = 1):
+        """n_tokens lock-step appends; raises MemoryError (state untouched by the failing append)
+        if a boundary needs more pages than the queue holds."""
+        for _ in range(n_tokens):
+            if self.length % self.page_tokens == 0:
+                if len(self.free) < len(self.alive):
+                    raise MemoryError("page pool exhausted")
+                for b in self.alive:
+                    self.pages[b].append(self.free.pop(0))
+            self.length += 1
+
+    def drop(self, ids):
+        for b in sorted(ids):
+            self.alive.remove(b)
+            self.free.extend(self.pages[b])
+            self.pages[b] = []
+
+    def table(self, b: int):
+        return list(self.pages[b])

@@ -281,6 +281,35 @@ def test_page_table_reference_small_example():
     assert paging.page_tables(1, 5, 4, range(4)).tolist() == [[0, 1]]
 
 
+def test_page_pool_with_drops_worked_example():
+    # worked by hand: 3 candidates, pages of 2 tokens, a pool of 7 pages in the order 10..16.
+    # t=0: cands 0,1,2 take 10,11,12.  After 2 tokens candidate 1 leaves: queue 13,14,15,16,11.
+    # t=2: cands 0,2 take 13,14.  t=4: 15,16.  t=6: 11 (reused) and then nothing is left.
+    pool = paging.PagePool(3, 2, range(10, 17))
+    pool.append(2)
+    assert [pool.table(b) for b in range(3)] == [[10], [11], [12]]
+    pool.drop([1])
+    assert pool.free == [13, 14, 15, 16, 11] and pool.table(1) == []
+    pool.append(4)
+    assert pool.table(0) == [10, 13, 15] and pool.table(2) == [12, 14, 16]
+    with pytest.raises(MemoryError):
+        pool.append(1)
+    assert pool.length == 6 and pool.free == [11] and pool.table(0) == [10, 13, 15]   # untouched
+    pool.drop([0])
+    assert pool.free == [11, 10, 13, 15]
+    pool.append(3)
+    assert pool.table(2) == [12, 14, 16, 11, 10] and pool.length == 9 and pool.alive == [2]
+    # without drops it is the lock-step table
+    pool = paging.PagePool(3, 2, range(100))
+    pool.append(5)
+    assert [pool.table(b) for b in range(3)] == paging.page_tables(3, 5, 2, range(100)).tolist()
+    # several leave at once: pages return in ascending candidate order, whatever order is given
+    pool = paging.PagePool(4, 1, range(8))
+    pool.append(2)
+    pool.drop([3, 0])
+    assert pool.free == [0, 4, 3, 7]
+
+
 # ---------------------------------------------------------------- bf16 activation mode
 def test_round_bf16_against_closed_forms_and_library():
     import torch
