@@ -90,6 +90,12 @@ typedef struct {
   int32_t max_suffix;   /* longest per-candidate suffix (decode steps / scoring)  */
   int32_t page_tokens;  /* KV page size in tokens: power of two, 4..128           */
   int32_t chunk_rows;   /* rows processed at once by prefill/scoring (0 = default)*/
+  int32_t pool_pages;   /* KV pages shared by the candidates' suffixes; 0 = max_cands *
+                           ceil(max_suffix / page_tokens), enough for every candidate to
+                           reach max_suffix.  A smaller pool serves searches that start
+                           many candidates and keep few (mc_drop_candidates returns pages
+                           to the pool); a step that needs more pages than are free fails
+                           with MC_ERR_OOM and changes nothing                          */
 } mc_session_params;
 
 /* ---- lifecycle ------------------------------------------------------------------ */
@@ -143,7 +149,10 @@ int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_can
  *    ones (Sec. 3.3).  mc_drop_candidates removes the n candidates cands[.] (ids as numbered when
  *    the candidates were started, each still decoding, at least one other must stay): they take
  *    no further part in mc_decode_step / mc_sample / mc_prefill_suffix, whose work (rows, KV
- *    traffic) shrinks accordingly, and their pages count as released.  From then on those calls
+ *    traffic) shrinks accordingly, and their pages go back to the pool: the free pages are a
+ *    queue, a page boundary hands its head to the candidates still decoding in ascending id
+ *    order, and the pages of dropped candidates join its tail (ascending candidate id, each
+ *    one's pages in the order it took them), so later boundaries reuse them.  From then on those calls
  *    are given the number of candidates still decoding, and every per-candidate array (tokens,
  *    uniforms, sampled ids, logits rows) lists the survivors in ascending id order; results that
  *    were pending for the survivors (logits, sampled tokens) stay valid.
@@ -225,7 +234,8 @@ int mc_debug_copy_logits(mc_session *s, float *out, int32_t n_rows);
 /* Page ids of every candidate's allocated suffix pages.  out: host
  * [max_cands][max_pages] (unused entries -1), n_pages: host [max_cands]. */
 int mc_debug_page_table(mc_session *s, int32_t *out, int32_t *n_pages, int32_t max_pages);
-/* Replace the free list's order (a permutation of 0..n-1, n = pool size); only
+/* Replace the order in which an untouched pool hands out its pages (a permutation of
+ * 0..n-1, n = pool size; mc_session_reset_candidates returns to this order); only
  * allowed while no candidate holds a page.  mc_debug_pool_pages gives n. */
 int mc_debug_set_free_list(mc_session *s, const int32_t *perm, int32_t n);
 int32_t mc_debug_pool_pages(const mc_session *s);

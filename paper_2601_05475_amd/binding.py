@@ -51,7 +51,7 @@ class mc_arena(C.Structure):
 
 class mc_session_params(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("max_prefix", "max_cands", "max_suffix", "page_tokens",
-                                         "chunk_rows")]
+                                         "chunk_rows", "pool_pages")]
 
 
 # name -> (restype, argtypes); must list every symbol include/mc.h declares
@@ -202,10 +202,10 @@ class Model:
 
 class Session:
     def __init__(self, model: Model, max_prefix: int, max_cands: int, max_suffix: int,
-                 page_tokens: int, chunk_rows: int = 0):
+                 page_tokens: int, chunk_rows: int = 0, pool_pages: int = 0):
         lib = load_library()
         self.model = model
-        self.params = mc_session_params(max_prefix, max_cands, max_suffix, page_tokens, chunk_rows)
+        self.params = mc_session_params(max_prefix, max_cands, max_suffix, page_tokens, chunk_rows, pool_pages)
         nbytes = lib.mc_session_bytes(C.byref(model.cfg), C.byref(self.params))
         if nbytes == 0:
             raise McError(-1, lib.mc_last_error().decode())

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <deque>
 #include <new>
 #include <vector>
 
@@ -235,7 +236,7 @@ constexpr int kProfCap = 8192;
 struct SessionLayout {
   size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
       hlast, attn_ws, alive, rope_tab, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
-      score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
+      page_new, score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
   size_t total;
   // derived sizes
   int rows_cap, n_prefix_pages, n_pool_pages, pages_per_cand, n_score_pages;
@@ -249,6 +250,7 @@ static int check_params(const mc_session_params *p) {
   const int pg = p->page_tokens;
   if (pg < 4 || pg > 128 || (pg & (pg - 1))) MC_FAIL(MC_ERR_INVALID, "page_tokens must be a power of two in 4..128");
   if (p->chunk_rows < 0) MC_FAIL(MC_ERR_INVALID, "chunk_rows < 0");
+  if (p->pool_pages < 0) MC_FAIL(MC_ERR_INVALID, "pool_pages < 0");
   return MC_OK;
 }
 
@@ -269,6 +271,7 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.n_prefix_pages = (p.max_prefix + pg - 1) / pg;
   o.pages_per_cand = (p.max_suffix + pg - 1) / pg;
   o.n_pool_pages = p.max_cands * o.pages_per_cand;
+  if (p.pool_pages > 0) o.n_pool_pages = std::min(o.n_pool_pages, p.pool_pages);
   o.n_score_pages = chunk / pg + std::min(p.max_cands, chunk) + 1;
   o.page_bytes = page_elems(c.n_kv_heads, c.head_dim, pg) * e;
   const size_t R = o.rows_cap;
@@ -301,6 +304,7 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.row_tab = at(R * 4);
   o.last_idx = at((size_t)p.max_cands * 4);
   o.page_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
+  o.page_new = at((size_t)p.max_cands * 4);
   o.score_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
   o.items = at((R / 32 + p.max_cands + 2) * 16);
   o.samp_tok = at((size_t)p.max_cands * 4);
@@ -332,14 +336,17 @@ struct mc_session {
   int chunk_rows;
   // state
   int prefix_len = 0, n_cands = 0, suffix_len = 0, logits_state = LOGITS_NONE, logits_rows = 0;
-  bool sampled_on_device = false, table_ready = false;
+  bool sampled_on_device = false;
   // candidates still decoding, ascending ids (all of 0..n_cands-1 until some are dropped); row r
   // of every per-candidate buffer belongs to candidate alive[r]
   std::vector<int32_t> alive;
   bool dropped_any = false;
   int prefix_splits = 0;
+  // The pool's free pages are a queue: at a page boundary the candidates still decoding take
+  // pages from its head in ascending candidate order; a dropped candidate's pages go to its tail.
   std::vector<int32_t> free_list;           // initial order of the pool
-  std::vector<int32_t> host_table;          // [max_cands][pages_per_cand], pool-relative ids
+  std::deque<int32_t> free_q;               // pages free now
+  std::vector<int32_t> host_table;          // [max_cands][pages_per_cand], pool-relative ids, -1 = none
   // pinned staging ring for small host->device parameter blocks
   char *ring = nullptr;
   size_t slot_bytes = 0;
@@ -628,6 +635,7 @@ extern "C" int mc_session_create(const mc_model *m, const mc_arena *arena,
   s->chunk_rows = effective_chunk_rows(*p);
   s->free_list.resize(lay.n_pool_pages);
   for (int i = 0; i < lay.n_pool_pages; ++i) s->free_list[i] = i;
+  s->free_q.assign(s->free_list.begin(), s->free_list.end());
   s->host_table.assign((size_t)p->max_cands * lay.pages_per_cand, -1);
   s->slot_bytes = align_up((size_t)lay.rows_cap * 4 * 5 + 256, 256);
   for (int i = 0; i < kRingSlots; ++i) { s->ring_used[i] = false; s->ring_ev[i] = nullptr; }
@@ -637,6 +645,8 @@ extern "C" int mc_session_create(const mc_model *m, const mc_arena *arena,
   // KV memory starts at zero so that unused tail slots of a page hold finite values
   if (err == hipSuccess)
     err = hipMemsetAsync(s->base + lay.kpool, 0, lay.vscr + (size_t)lay.n_score_pages * lay.page_bytes - lay.kpool, s->stream);
+  if (err == hipSuccess)
+    err = hipMemsetAsync(s->base + lay.page_table, 0, (size_t)p->max_cands * lay.pages_per_cand * 4, s->stream);
   // rotary angles of every position this session can hold
   if (err == hipSuccess &&
       launch_rope_table(s->stream, p->max_prefix + p->max_suffix, m->cfg.head_dim, (double)m->cfg.rope_base,
@@ -672,7 +682,7 @@ extern "C" int mc_session_reset_candidates(mc_session *s) {
   s->n_cands = 0;
   s->suffix_len = 0;
   s->sampled_on_device = false;
-  s->table_ready = false;
+  s->free_q.assign(s->free_list.begin(), s->free_list.end());
   s->alive.clear();
   s->dropped_any = false;
   std::fill(s->host_table.begin(), s->host_table.end(), -1);
@@ -839,19 +849,40 @@ static void unfix_cands(mc_session *s, int saved_total) {
   if (saved_total == 0) { s->n_cands = 0; s->alive.clear(); }
 }
 
-// Page ids are a pure function of (candidate, page slot) under the lock-step rule: at the
-// boundary t = p * page_tokens candidates take pages in ascending order from the list head.
-// The whole table goes to the device once per set of candidates.
-static int ensure_page_table(mc_session *s, int n_cands) {
-  if (s->table_ready) return MC_OK;
+__global__ void set_pages_kernel(int n, int slot, int stride, const int32_t *__restrict__ alive,
+                                 const int32_t *__restrict__ ids, int32_t *table) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < n) table[(size_t)(alive ? alive[r] : r) * stride + slot] = ids[r];
+}
+
+// Pages for the slots slot0 .. slot0 + n_slots - 1 of every candidate still decoding, read off
+// the head of the queue without removing them (slot by slot, candidates ascending within a slot:
+// fresh[i * n_alive + r]), and written into the device page table.  The queue and the host table
+// change only in commit_pages, once the step that needed the pages has been enqueued.
+static int stage_pages(mc_session *s, int slot0, int n_slots, std::vector<int32_t> &fresh) {
   const SessionLayout &L = s->lay;
-  std::vector<int32_t> full((size_t)s->p.max_cands * L.pages_per_cand, 0);
-  for (int p = 0; p < L.pages_per_cand; ++p)
-    for (int b = 0; b < n_cands; ++b) full[(size_t)b * L.pages_per_cand + p] = s->free_list[(size_t)p * n_cands + b];
-  MC_HIP(hipMemcpyAsync(s->ptr<void>(L.page_table), full.data(), full.size() * 4, hipMemcpyHostToDevice, s->stream));
-  MC_HIP(hipStreamSynchronize(s->stream));
-  s->table_ready = true;
+  const int n_alive = (int)s->alive.size();
+  fresh.clear();
+  if (n_slots <= 0) return MC_OK;
+  if (slot0 + n_slots > L.pages_per_cand) MC_FAIL(MC_ERR_OOM, "suffix longer than max_suffix");
+  if ((size_t)n_slots * n_alive > s->free_q.size())
+    MC_FAIL(MC_ERR_OOM, "page pool exhausted: %d candidates need %d page(s) each, %zu of %d pages are free", n_alive,
+            n_slots, s->free_q.size(), L.n_pool_pages);
+  fresh.assign(s->free_q.begin(), s->free_q.begin() + (size_t)n_slots * n_alive);
+  for (int i = 0; i < n_slots; ++i) {
+    MC_TRY(upload(s, s->ptr<void>(L.page_new), fresh.data() + (size_t)i * n_alive, (size_t)n_alive * 4));
+    set_pages_kernel<<<(n_alive + 63) / 64, 64, 0, s->stream>>>(n_alive, slot0 + i, L.pages_per_cand,
+        s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.page_new), s->ptr<int32_t>(L.page_table));
+    MC_HIP(hipGetLastError());
+  }
   return MC_OK;
+}
+static void commit_pages(mc_session *s, int slot0, const std::vector<int32_t> &fresh) {
+  const int n_alive = (int)s->alive.size();
+  for (size_t i = 0; i < fresh.size(); ++i) {
+    s->host_table[(size_t)s->alive[i % n_alive] * s->lay.pages_per_cand + slot0 + i / n_alive] = fresh[i];
+    s->free_q.pop_front();
+  }
 }
 
 extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_cands) {
@@ -867,7 +898,8 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   const int pg = s->p.page_tokens, t = s->suffix_len;
   const int saved_n = s->n_cands;
   fix_cands(s, n_cands);
-  if (int rc0 = ensure_page_table(s, s->n_cands)) { unfix_cands(s, saved_n); return rc0; }
+  std::vector<int32_t> fresh;
+  if (int rc0 = stage_pages(s, t / pg, t % pg == 0 ? 1 : 0, fresh)) { unfix_cands(s, saved_n); return rc0; }
   if (tokens) MC_TRY(upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4));
   else MC_HIP(hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4, hipMemcpyDeviceToDevice, s->stream));
   decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
@@ -879,9 +911,7 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, 0, &tail);
   if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
   if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
-  if (t % pg == 0)
-    for (int b : s->alive)
-      s->host_table[(size_t)b * L.pages_per_cand + t / pg] = s->free_list[(size_t)(t / pg) * s->n_cands + b];
+  commit_pages(s, t / pg, fresh);
   s->suffix_len = t + 1;
   s->logits_state = LOGITS_CANDS;
   s->logits_rows = n_cands;
@@ -1051,7 +1081,11 @@ extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n
   MC_TRY(upload(s, s->ptr<void>(L.alive), new_alive.data(), (size_t)new_n * 4));
   for (int b = 0; b < s->n_cands; ++b)
     if (gone[b])
-      for (int p = 0; p < L.pages_per_cand; ++p) s->host_table[(size_t)b * L.pages_per_cand + p] = -1;
+      for (int p = 0; p < L.pages_per_cand; ++p) {
+        int32_t &id = s->host_table[(size_t)b * L.pages_per_cand + p];
+        if (id >= 0) s->free_q.push_back(id);
+        id = -1;
+      }
   s->alive = new_alive;
   s->dropped_any = true;
   if (s->logits_state == LOGITS_CANDS) s->logits_rows = new_n;
@@ -1073,9 +1107,14 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
   const int pg = s->p.page_tokens;
   const int saved_n = s->n_cands;
   fix_cands(s, n_cands);
-  if (int rc0 = ensure_page_table(s, s->n_cands)) { unfix_cands(s, saved_n); return rc0; }
-  const int n_total = s->n_cands;
-  auto page_of = [&](int cand, int slot) { return s->free_list[(size_t)slot * n_total + cand]; };
+  // slots below slot0 are held already; the others come off the queue
+  const int slot0 = (t + pg - 1) / pg, n_new = (t + len - 1) / pg - slot0 + 1, n_alive = (int)s->alive.size();
+  std::vector<int32_t> fresh;
+  if (int rc0 = stage_pages(s, slot0, n_new, fresh)) { unfix_cands(s, saved_n); return rc0; }
+  auto page_of = [&](int row, int slot) {
+    return slot < slot0 ? s->host_table[(size_t)s->alive[row] * L.pages_per_cand + slot]
+                        : fresh[(size_t)(slot - slot0) * n_alive + row];
+  };
   std::vector<int32_t> tok, pos, page, off, tab, last, items;
   const int per_chunk = std::max(1, s->chunk_rows / len);          // whole candidates per chunk
   for (int b0 = 0; b0 < n_cands; b0 += per_chunk) {
@@ -1093,7 +1132,7 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
       for (int j = 0; j < len; ++j, ++r) {
         tok[r] = suffix_tokens[(size_t)b * len + j];
         pos[r] = s->prefix_len + t + j;
-        page[r] = page_of(cand, (t + j) / pg);
+        page[r] = page_of(b, (t + j) / pg);
         off[r] = (t + j) % pg;
         tab[r] = cand;
       }
@@ -1111,8 +1150,7 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
     if (rc == MC_OK) rc = lm_head(s, rows, tail, nc, true, s->ptr<float>(L.logits) + (size_t)b0 * c.vocab);
     if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
   }
-  for (int slot = t / pg; slot <= (t + len - 1) / pg; ++slot)
-    for (int b : s->alive) s->host_table[(size_t)b * L.pages_per_cand + slot] = page_of(b, slot);
+  commit_pages(s, slot0, fresh);
   s->suffix_len = t + len;
   s->logits_state = LOGITS_CANDS;
   s->logits_rows = n_cands;
@@ -1157,6 +1195,7 @@ extern "C" int mc_debug_set_free_list(mc_session *s, const int32_t *perm, int32_
     seen[perm[i]] = 1;
   }
   s->free_list.assign(perm, perm + n);
+  s->free_q.assign(s->free_list.begin(), s->free_list.end());
   return MC_OK;
 }
 

@@ -52,6 +52,12 @@ def test_model_and_session_sizes(lib):
     p8 = binding.mc_session_params(4096, 32, 512, 64, 4096)
     sb8 = lib.mc_session_bytes(C.byref(cfg8), C.byref(p8))
     assert sb8 > 2.5 * 2 ** 30 and sb8 < 6 * 2 ** 30
+    # a smaller page pool shrinks the session by exactly the pages it leaves out (K and V, every layer)
+    p8s = binding.mc_session_params(4096, 32, 512, 64, 4096, 64)
+    page = 2 * 8 * 128 * 64 * 2 * 32
+    assert sb8 - lib.mc_session_bytes(C.byref(cfg8), C.byref(p8s)) == (32 * 8 - 64) * page
+    p8b = binding.mc_session_params(4096, 32, 512, 64, 4096, 10 ** 6)     # more than can be used: capped
+    assert lib.mc_session_bytes(C.byref(cfg8), C.byref(p8b)) == sb8
 
 
 def test_invalid_configs_are_rejected(lib):
@@ -62,7 +68,7 @@ def test_invalid_configs_are_rejected(lib):
         assert lib.mc_model_bytes(C.byref(cfg)) == 0
         assert len(lib.mc_last_error()) > 0
     cfg = binding.make_config(s)
-    for field, bad in [("page_tokens", 3), ("page_tokens", 256), ("max_cands", 0), ("max_suffix", 0)]:
+    for field, bad in [("page_tokens", 3), ("page_tokens", 256), ("max_cands", 0), ("max_suffix", 0), ("pool_pages", -1)]:
         p = binding.mc_session_params(128, 4, 16, 4, 0)
         setattr(p, field, bad)
         assert lib.mc_session_bytes(C.byref(cfg), C.byref(p)) == 0

@@ -577,14 +577,101 @@ def test_drop_candidates_midway(kw, dtype):
     tab, n = sess.page_table()
     held = -(-N // kw["pg"])
     assert [int(x) for x in n[:B]] == [held if b in alive else 0 for b in range(B)]
-    ref_tab = opaging.page_tables(B, N, kw["pg"], range(sess.pool_pages()))
+    pool = opaging.PagePool(B, kw["pg"], range(sess.pool_pages()))   # the same calls on the reference pool
+    for t in range(N):
+        if t in drops:
+            pool.drop(drops[t])
+        pool.append(1)
     for b in alive:
-        np.testing.assert_array_equal(tab[b, :held], ref_tab[b])
+        assert tab[b, :held].tolist() == pool.table(b)
     # a survivor can be promoted, a dropped candidate cannot
     with pytest.raises(binding.McError):
         sess.promote_candidate(1)
     sess.promote_candidate(alive[-1])
     np.testing.assert_array_equal(sess.logits(1)[0], got[-1])
+
+
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4, N=26, n0=7, n1=9, bulk=6), "f32"),
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64, N=330, n0=70, n1=130, bulk=100), "bf16"),
+])
+def test_small_page_pool_reuses_the_pages_of_dropped_candidates(kw, dtype):
+    """Start many candidates, keep few: a pool far smaller than candidates x longest suffix is
+    enough, because the pages of dropped candidates go back to the queue and are handed out
+    again.  The survivors' logits are the oracle's although their later tokens sit in pages that
+    held other candidates' keys before; the page table is the reference pool's, bit for bit; a
+    step that would need more pages than are free is refused and changes nothing."""
+    s = small_shape("pool", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 83)
+    pg, N, n0, n1, bulk = kw["pg"], kw["N"], kw["n0"], kw["n1"], kw["bulk"]
+    P, B = 70, 6
+    pages_full = B * -(-N // pg)
+    # the smallest pool that carries 6 candidates to n0, 3 to n1 and 2 to N
+    keep1, keep2 = [0, 2, 5], [2, 5]
+    ref_pool = None
+    for n_pool in range(1, pages_full):
+        trial = opaging.PagePool(B, pg, range(n_pool))
+        try:
+            trial.append(n0); trial.drop([1, 3, 4]); trial.append(n1 - n0); trial.drop([0]); trial.append(N - n1)
+        except MemoryError:
+            continue
+        ref_pool = n_pool
+        break
+    assert ref_pool is not None and ref_pool < pages_full // 2
+    prefix = synth.tokens(12, 1, (P,), s.vocab)
+    suffix = synth.tokens(12, 2, (B, N), s.vocab)
+    print("case: small page pool", kw, dtype, "pool", ref_pool, "of", pages_full, flush=True)
+    model = binding.Model(s, w)
+    perm = np.random.default_rng(5).permutation(ref_pool).astype(np.int32)
+    sess = binding.Session(model, P, B, N, pg, pool_pages=ref_pool)
+    assert sess.pool_pages() == ref_pool
+    sess.set_free_list(perm)
+    pool = opaging.PagePool(B, pg, perm.tolist())
+    sess.prefill_shared(prefix)
+    alive = list(range(B))
+    got = None
+    t = 0
+    while t < N:
+        if t == n0:
+            sess.drop_candidates([1, 3, 4]); pool.drop([1, 3, 4]); alive = keep1
+        if t == n1:
+            sess.drop_candidates([0]); pool.drop([0]); alive = keep2
+        if t == n1 + 3:
+            # a stretch written in bulk takes its pages off the same queue
+            sess.prefill_suffix(suffix[alive, t:t + bulk]); pool.append(bulk)
+            t += bulk
+            continue
+        sess.decode_step(suffix[alive, t]); pool.append(1)
+        t += 1
+    got = sess.logits(len(alive))
+    tab, n = sess.page_table()
+    held = -(-N // pg)
+    assert [int(x) for x in n[:B]] == [held if b in alive else 0 for b in range(B)]
+    for b in alive:
+        assert tab[b, :held].tolist() == pool.table(b)
+    reused = set(pool.table(2)) | set(pool.table(5))
+    assert len(reused) == 2 * held and max(reused) < ref_pool
+    want_pl, want = oracle_shared(s, w, prefix, suffix[alive])
+    fl = oracle_shared(s, w, prefix, suffix[alive], exact=False)[1] if dtype == "bf16" else None
+    assert_logits_close(got[None], want[-1:], dtype, "survivors after page reuse", None if fl is None else fl[-1:])
+    # the pool is used up to within what one more boundary needs: a fresh set of 6 candidates
+    # cannot start beyond it, and the refusal leaves the session as it was
+    sess.reset_candidates()
+    many = ref_pool // B * pg                                         # tokens all 6 can hold
+    for t in range(min(many, N)):
+        sess.decode_step(suffix[:, t])
+    if many < N:
+        before = sess.logits(B)
+        with pytest.raises(binding.McError) as ei:
+            sess.decode_step(suffix[:, many])
+        assert ei.value.code == -3
+        np.testing.assert_array_equal(sess.logits(B), before)
+        sess.drop_candidates([0, 1, 2, 3])
+        sess.decode_step(suffix[[4, 5], many])                        # goes on once pages are free
+        want2 = oracle_shared(s, w, prefix, suffix[[4, 5], :many + 1])[1]
+        fl2 = oracle_shared(s, w, prefix, suffix[[4, 5], :many + 1], exact=False)[1] if dtype == "bf16" else None
+        assert_logits_close(sess.logits(2)[None], want2[-1:], dtype, "after a refused step",
+                            None if fl2 is None else fl2[-1:])
 
 
 def test_drop_candidates_with_tokens_pending_on_the_device(tiny):
