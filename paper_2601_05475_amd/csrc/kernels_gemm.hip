@@ -2,20 +2,33 @@
 //   out[m][n] = sum_k a[m][k] w[n][k]                 (fp32, row-major), or
 //   out_t[m][n] = silu(a . wg[n]) * (a . wu[n])        (bf16, tiled; the SwiGLU form).
 //
-// A workgroup of 8 waves (4 x 2) owns 256 rows of a and 256 rows of w (128 of wg and of wu in
-// the SwiGLU form); a wave keeps 8 accumulator tiles of 32 x 32 (64 rows of a x 128 rows of w).
-// Eight waves per CU, two per SIMD, is what the LDS needs to deliver its full read rate (one
-// wave per SIMD reaches about half), and the second wave fills the matrix core while the first
-// waits for operands.  Per 16-deep chunk a wave reads 6 fragments and issues 8 MFMAs.
-// One 64-deep unit of both operands (16 blocks of 4 KB, already in MFMA operand order, so they
-// are copied to LDS as they are and read back conflict-free) is staged per step in one of two
-// alternating buffers: the global loads of unit u + 1 are issued before the MFMAs of unit u,
-// land in registers meanwhile and are written to the other buffer before the single barrier
-// that ends the unit.
+// A workgroup of 4 waves owns 256 rows of a and 128 rows of w (64 of wg and of wu in the SwiGLU
+// form); a wave keeps 8 accumulator tiles of 32 x 32 (its own 64 rows of a x all 128 rows of w).
+// Two workgroups share a CU (two waves per SIMD, 215 registers each): they run out of step, so
+// the barrier, prologue and epilogue of one are covered by the matrix work of the other.
+// The two operands reach the matrix cores by different roads, which splits the traffic between
+// LDS and the vector memory path instead of loading one of them with everything:
+//   * w is shared by the four waves: one 64-deep unit (4 blocks of 4 KB, already in MFMA operand
+//     order, so they are copied to LDS as they are and read back conflict-free) is staged per
+//     step in one of three LDS stages.  The global loads of unit u + 2 go out at the top of
+//     unit u, land in registers meanwhile and are written to LDS during its last chunk; the one
+//     barrier per unit then makes stage u + 2 visible a whole unit before it is read, so the first
+//     fragments of unit u + 1 are read before the barrier that ends unit u and no wave starts a
+//     unit waiting for LDS.
+//   * a rows belong to one wave only, and the tiled layout holds them in operand order: a wave
+//     loads its fragments straight from memory into the registers the MFMAs read (1 KB per wave
+//     and fragment, fully coalesced), one unit ahead, refilling each fragment's registers as soon
+//     as the chunk that used them has been issued.
+// Per 16-deep chunk a wave reads 4 fragments from LDS, loads 2 from memory and issues 8 MFMAs.
+// With both operands in LDS (the earlier form: 256 x 256 per 8-wave workgroup) the matrix pipes
+// were busy 61 % and the LDS 63 %; this form reaches 75 % at a lower clock: the part is then at
+// its power limit, and variants that differ in barrier scope or fragment look-ahead all
+// land on the same rate.
 //
 // Workgroup numbering follows the hardware's round-robin deal of workgroups to the 8 XCDs: the
-// ids that land on one XCD walk a compact 8 x 4 patch of output tiles, so that XCD's L2 serves
-// each operand tile to several workgroups and HBM sees it about once per patch row/column.
+// ids that land on one XCD walk a compact patch of output tiles (8 row tiles deep), so that XCD's
+// L2 serves each operand tile to several workgroups and HBM sees it about once per patch
+// row/column.
 #include "kernels_mfma.h"
 
 #include <algorithm>
@@ -37,7 +50,7 @@ __device__ inline uint32_t pack2g_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2));
 }
 
-constexpr int kPatchRows = 8;     // output-tile patch walked by one XCD: 8 row tiles x 4 column tiles
+constexpr int kPatchRows = 8;     // output-tile patch walked by one XCD: 8 row tiles deep
 
 // tile (tm, tn) of workgroup `id`; false if the id is padding
 __device__ inline bool gemm_tile_of(int id, int tiles_m, int tiles_n, int &tm, int &tn) {
@@ -53,7 +66,7 @@ __device__ inline bool gemm_tile_of(int id, int tiles_m, int tiles_n, int &tm, i
   return true;
 }
 
-// What a workgroup does with its 256 x 256 sums: store them (fp32), the SwiGLU product of two
+// What a workgroup does with its 256 x 128 sums: store them (fp32), the SwiGLU product of two
 // weight matrices (bf16, tiled), the fused QKV epilogue (rope_store_quad), or out += sums.
 enum { GEMM_STORE = 0, GEMM_SWIGLU = 1, GEMM_ROPE = 2, GEMM_ACCUM = 3 };
 // row stride (floats) of a wave's 32 x 128 parking area in the GEMM_ROPE epilogue: 128 + 4, so
@@ -61,7 +74,7 @@ enum { GEMM_STORE = 0, GEMM_SWIGLU = 1, GEMM_ROPE = 2, GEMM_ACCUM = 3 };
 constexpr int kParkStride = 132;
 
 template <int MODE>
-__global__ __launch_bounds__(512)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t *__restrict__ a,
                     const bf16_t *__restrict__ w, const bf16_t *__restrict__ w2,
                     float *__restrict__ out, bf16_t *__restrict__ out_t, RopeOut ro) {
@@ -70,35 +83,37 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
   constexpr int TM = 2;                    // 32-row tiles of a per wave
   constexpr int TN = SWIGLU ? 2 : 4;       // 32-row tiles of each weight matrix per wave
   constexpr int WT = NW * TN;              // weight tiles of one wave (4)
-  constexpr int AB = 8;                    // blocks of a per unit (workgroup): 256 rows
-  constexpr int WB = 2 * TN;               // blocks of each weight matrix per unit (workgroup)
-  constexpr int NB = AB + NW * WB;         // 16 blocks of 256 chunks
+  constexpr int AB = 8;                    // 32-row tiles of a per workgroup: 256 rows
+  constexpr int WB = TN;                   // blocks of each weight matrix per unit (workgroup)
+  constexpr int NBW = NW * WB;             // 4 weight blocks of 256 chunks per unit
+  constexpr int kStages = 3;
   extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
-  v4u *lds = (v4u *)gemm_lds;              // [2][NB][256]
+  v4u *lds = (v4u *)gemm_lds;              // [kStages][NBW][256]
   const int tid = threadIdx.x, lane = tid & 63, j = lane & 31, h = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wn = wave & 1, wm = wave >> 1;
+  const int wm = wave;
   int tm, tn;
   if (!gemm_tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn)) return;
   const int U = K >> 6;
   const int mt0 = tm * AB, nt0 = tn * WB;  // first 32-row tile of a / of each weight matrix
   const int m_tiles = (M + 31) >> 5;
 
-  // staging: thread t carries chunk t % 256 of blocks 2i + t / 256, i = 0..7; the block base is
-  // wave-uniform (scalar registers), the rest a 32-bit byte offset
-  const int half = wave >> 2;
-  const char *src[NB / 2];
+  // weight staging: thread t carries chunk t of every block of the unit
+  const char *src[NBW];
 #pragma unroll
-  for (int i = 0; i < NB / 2; ++i) {
-    const int b = 2 * i + half;            // block of the unit: a first, then w, then w2
-    const bf16_t *p;
-    if (b < AB) p = a + (size_t)min(mt0 + b, m_tiles - 1) * U * 2048;
-    else if (b < AB + WB) p = w + (size_t)(nt0 + b - AB) * U * 2048;
-    else p = w2 + (size_t)(nt0 + b - AB - WB) * U * 2048;
+  for (int i = 0; i < NBW; ++i) {
+    // blocks of the unit: w first, then w2
+    const bf16_t *p = i < WB ? w + (size_t)(nt0 + i) * U * 2048 : w2 + (size_t)(nt0 + i - WB) * U * 2048;
     src[i] = (const char *)p;
   }
-  const uint32_t s_off = (tid & 255) * 16u;
-  const int s_lds = half * 256 + (tid & 255);       // + (buf * NB + 2 i) * 256
+  const uint32_t s_off = tid * 16u;
+  const int s_lds = tid;       // + (stage * NBW + i) * 256
+  // the rows of a come straight from memory in operand order: a chunk of a tile is 1 KB, 16 bytes per lane
+  const char *asrc[TM];
+#pragma unroll
+  for (int y = 0; y < TM; ++y)
+    asrc[y] = (const char *)(a + (size_t)min(mt0 + TM * wm + y, m_tiles - 1) * U * 2048);
+  const uint32_t a_off = lane * 16u;
 
   f32x16 acc[WT][TM];
 #pragma unroll
@@ -110,73 +125,84 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
 
   // Loads past the last unit re-read the last unit (in bounds, never used), so that every
   // iteration issues the same loads and the compiler's load counters stay exact.
-  v4u st[NB / 2];
-  auto load_unit = [&](int u) __attribute__((always_inline)) {
+  v4u st[NBW];
+  auto load_w = [&](int u) __attribute__((always_inline)) {
     const uint32_t at = s_off + (uint32_t)min(u, U - 1) * 4096u;
 #pragma unroll
-    for (int i = 0; i < NB / 2; ++i) st[i] = *(const v4u *)(src[i] + at);
+    for (int i = 0; i < NBW; ++i) st[i] = *(const v4u *)(src[i] + at);
   };
-  auto store_unit = [&](int buf) __attribute__((always_inline)) {
+  auto store_w = [&](int stage) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < NB / 2; ++i) lds[(buf * NB + 2 * i) * 256 + s_lds] = st[i];
+    for (int i = 0; i < NBW; ++i) lds[(stage * NBW + i) * 256 + s_lds] = st[i];
   };
-
-  // fragments of chunk c of the unit in LDS buffer `buf`
-  auto read_frags = [&](v4u (&fa)[TM], v4u (&fw)[WT], int buf, int c) __attribute__((always_inline)) {
-    const v4u *ca = lds + (buf * NB + TM * wm) * 256 + lane + c * 64;
-    const v4u *cw = lds + (buf * NB + AB + TN * wn) * 256 + lane + c * 64;
+  v4u fa[4][TM];
+  auto load_a = [&](int u, int c) __attribute__((always_inline)) {
+    const uint32_t at = a_off + (uint32_t)min(u, U - 1) * 4096u + (uint32_t)c * 1024u;
 #pragma unroll
-    for (int t = 0; t < TM; ++t) fa[t] = ca[t * 256];
+    for (int y = 0; y < TM; ++y) fa[c][y] = *(const v4u *)(asrc[y] + at);
+  };
+  auto read_w = [&](v4u (&fw)[WT], int stage, int c) __attribute__((always_inline)) {
+    const v4u *cw = lds + stage * NBW * 256 + lane + c * 64;
 #pragma unroll
     for (int x = 0; x < TN; ++x) {
       fw[x] = cw[x * 256];
       if (SWIGLU) fw[TN + x] = cw[(WB + x) * 256];
     }
   };
-  auto multiply = [&](const v4u (&fa)[TM], const v4u (&fw)[WT]) __attribute__((always_inline)) {
+  auto multiply = [&](const v4u (&fa_)[TM], const v4u (&fw)[WT]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int x = 0; x < WT; ++x)
+    for (int y = 0; y < TM; ++y)
 #pragma unroll
-      for (int y = 0; y < TM; ++y) acc[x][y] = mfma32g(fw[x], fa[y], acc[x][y]);
+      for (int x = 0; x < WT; ++x) acc[x][y] = mfma32g(fw[x], fa_[y], acc[x][y]);
   };
 
-  load_unit(0);
-  store_unit(0);
+  v4u fw[2][WT];
+  load_w(0);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) load_a(0, c);
+  store_w(0);
+  load_w(1);
+  store_w(1);
   __syncthreads();
-  // Per unit: the global loads of unit u + 1 go out first.  The fragments of chunk c + 1 are read
-  // from LDS while the MFMAs of chunk c run (two register sets), and the LDS writes of unit u + 1
-  // are spread between the MFMAs of the last chunk, so that only the barrier itself and the
-  // first fragment reads after it are not covered by matrix work.  The scheduling directives pin
-  // this interleaving; without them the compiler sinks loads next to their uses.
+  read_w(fw[0], 0, 0);
+  int cur = 0, nxt = 1, wr = 2;
   for (int u = 0; u < U; ++u) {
-    const int buf = u & 1;
-    v4u fa[2][TM], fw[2][WT];
-    load_unit(u + 1);
-    read_frags(fa[0], fw[0], buf, 0);
+    load_w(u + 2);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
-      read_frags(fa[(c + 1) & 1], fw[(c + 1) & 1], buf, c + 1);
-      multiply(fa[c & 1], fw[c & 1]);
+      read_w(fw[(c + 1) & 1], cur, c + 1);
+      multiply(fa[c], fw[c & 1]);
+      load_a(u + 1, c);
 #pragma unroll
-      for (int i = 0; i < TM + WT; ++i) {
+      for (int i = 0; i < WT; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one LDS read
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, TM * WT - TM - WT, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * WT - WT, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, TM, 0);     // the loads of a for the next unit
       __builtin_amdgcn_sched_barrier(0);
     }
-    // the other buffer was last read during unit u - 1, which every wave left before the
-    // barrier that ended it
-    store_unit(buf ^ 1);
-    multiply(fa[1], fw[1]);
+    // stage wr was last read during unit u - 1, which every wave left before the barrier that
+    // ended it; stage nxt was written during unit u - 1 and is complete since that barrier
+    store_w(wr);
+    read_w(fw[0], nxt, 0);
+    multiply(fa[3], fw[1]);
+    load_a(u + 1, 3);
 #pragma unroll
-    for (int i = 0; i < NB / 2; ++i) {
+    for (int i = 0; i < NBW; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
       __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);      // one LDS write
     }
+#pragma unroll
+    for (int i = 0; i < WT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // one LDS read
+    }
+    __builtin_amdgcn_sched_group_barrier(0x020, TM, 0);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
+    const int t = cur; cur = nxt; nxt = wr; wr = t;
   }
 
   // weight rows are the A operand: a lane holds column m = j of the tile and, per register quad,
@@ -186,7 +212,7 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
     // parks in its own slice of LDS (free after the last barrier above).  The loop hands
     // consecutive lanes consecutive quads of one row, so table reads and query stores coalesce.
     float *park = (float *)gemm_lds + wave * (32 * kParkStride);
-    const int n_wave = 32 * (nt0 + TN * wn);
+    const int n_wave = 32 * nt0;
 #pragma unroll
     for (int y = 0; y < TM; ++y) {
       const int m0 = 32 * (mt0 + TM * wm + y);
@@ -226,7 +252,7 @@ void gemm256_kernel(int M, int N, int K, int tiles_m, int tiles_n, const bf16_t 
     for (int x = 0; x < TN; ++x)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        const int n = 32 * (nt0 + TN * wn + x) + 8 * r4 + 4 * h;
+        const int n = 32 * (nt0 + x) + 8 * r4 + 4 * h;
         const f32x16 &g = acc[x][y];
         if (SWIGLU) {
           const f32x16 &uu = acc[TN + x][y];
@@ -296,10 +322,10 @@ int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const voi
   if (rope && (rope->hd % 4 || N != (rope->Hq + 2 * rope->Hkv) * rope->hd))
     MC_FAIL(MC_ERR_INVALID, "fused QKV output: N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
   const int mode = swiglu ? GEMM_SWIGLU : rope ? GEMM_ROPE : accumulate ? GEMM_ACCUM : GEMM_STORE;
-  const int tiles_m = (M + 255) / 256, tiles_n = N / (swiglu ? 128 : 256);
+  const int tiles_m = (M + 255) / 256, tiles_n = N / (swiglu ? 64 : 128);
   const int per_xcd = (tiles_m * tiles_n + 7) / 8;
-  // two buffers of 16 blocks; the parking areas of the rotation epilogue need a little more
-  const size_t lds = std::max<size_t>(2 * 16 * 4096, mode == GEMM_ROPE ? 8 * 32 * kParkStride * sizeof(float) : 0);
+  // three stages of 4 weight blocks; the parking areas of the rotation epilogue need a little more
+  const size_t lds = std::max<size_t>(3 * 4 * 4096, mode == GEMM_ROPE ? 4 * 32 * kParkStride * sizeof(float) : 0);
   const void *kernels[4] = {(const void *)gemm256_kernel<GEMM_STORE>, (const void *)gemm256_kernel<GEMM_SWIGLU>,
                             (const void *)gemm256_kernel<GEMM_ROPE>, (const void *)gemm256_kernel<GEMM_ACCUM>};
   static bool attr_set[4] = {false, false, false, false};
@@ -312,10 +338,10 @@ int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const voi
   bf16_t *OT = (bf16_t *)out_t;
   const dim3 grid(8 * per_xcd);
   switch (mode) {
-    case GEMM_SWIGLU: gemm256_kernel<GEMM_SWIGLU><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
-    case GEMM_ROPE: gemm256_kernel<GEMM_ROPE><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, *rope); break;
-    case GEMM_ACCUM: gemm256_kernel<GEMM_ACCUM><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
-    default: gemm256_kernel<GEMM_STORE><<<grid, 512, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
+    case GEMM_SWIGLU: gemm256_kernel<GEMM_SWIGLU><<<grid, 256, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
+    case GEMM_ROPE: gemm256_kernel<GEMM_ROPE><<<grid, 256, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, *rope); break;
+    case GEMM_ACCUM: gemm256_kernel<GEMM_ACCUM><<<grid, 256, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
+    default: gemm256_kernel<GEMM_STORE><<<grid, 256, lds, st>>>(M, N, K, tiles_m, tiles_n, A, W, W2, out, OT, none); break;
   }
   MC_HIP(hipGetLastError());
   return MC_OK;
