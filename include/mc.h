@@ -293,8 +293,8 @@ int32_t mc_op_linear_splits(int32_t dtype, int32_t M, int32_t N, int32_t K, int3
  * 256-row-tile matrix-core GEMM (the residual update of the O and down projections in prefill and
  * scoring, section 3.1: the policy's forward pass).  x: fp32 [M][N] row-major, device, updated in
  * place; every element is read and written by exactly one lane, so the result does not depend on
- * scheduling.  MC_ERR_UNSUPPORTED unless N % 256 == 0, K % 256 == 0, M > 64 and
- * ceil(M / 256) * (N / 256) >= 160 (smaller products keep mc_op_linear + mc_op_add_rmsnorm). */
+ * scheduling.  MC_ERR_UNSUPPORTED unless N % 128 == 0, K % 256 == 0 and M > 64 (fewer rows keep
+ * mc_op_linear + mc_op_add_rmsnorm). */
 int mc_op_linear_accumulate(void *stream, int32_t M, int32_t N, int32_t K, const void *a,
                             const void *w, float *x);
 
@@ -303,8 +303,8 @@ int mc_op_linear_accumulate(void *stream, int32_t M, int32_t N, int32_t K, const
  * (row 2i of a head holds coordinate i, row 2i + 1 coordinate i + hd/2; value heads in natural
  * order).  table: device scratch of n_pos * hd/2 * 16 bytes, filled here with cos / sin (double)
  * of pos * base^(-2i/hd); every row_pos[r] must be < n_pos.  Outputs as mc_op_rope_kv_write
- * (bf16).  Covers rows <= 64 (weight-streaming kernel) and rows > 64 with
- * ceil(rows / 256) * (N / 256) >= 160, N % 256 == 0 (256-row-tile GEMM); else MC_ERR_UNSUPPORTED. */
+ * (bf16).  Covers rows <= 64 (weight-streaming kernel) and more rows (256-row-tile GEMM) when
+ * N % 128 == 0 and K % 256 == 0; else MC_ERR_UNSUPPORTED. */
 int mc_op_linear_qkv_rope(void *stream, int32_t rows, int32_t n_q_heads, int32_t n_kv_heads,
                           int32_t head_dim, int32_t page_tokens, int32_t K, float rope_base,
                           int32_t n_pos, const void *a, const void *wqkv, const int32_t *row_pos,

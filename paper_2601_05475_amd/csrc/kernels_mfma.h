@@ -91,13 +91,9 @@ __device__ inline void rope_store_quad(const RopeOut &ro, int m, int n, float4 s
   }
 }
 
-// Many-row GEMM: 1 split; fp32 out, or the SwiGLU form with bf16 out.
-bool gemm_supported(int M, int N, int K);
-int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                     const void *w2, float *out, void *out_t);
-
-// The same for shapes that fill 256-row tiles (N % 256 == 0, or N % 128 == 0 in the SwiGLU form):
-// 256 x 256 output tile per workgroup, double-buffered LDS, XCD-aware tile order.
+// Many-row GEMM (more than 64 rows): fp32 out, or the SwiGLU form with bf16 tiled out.  N % 128
+// == 0, K % 64 == 0.  256 x 128 output tile per workgroup (256 x 64 of each weight matrix in the
+// SwiGLU form), XCD-aware tile order.
 bool gemm256_supported(int M, int N, int K, bool swiglu);
 // rope != nullptr: the fused QKV layer as in launch_linear_skinny (N = (Hq + 2 Hkv) hd, hd % 4 == 0).
 // accumulate: out[m][n] += the product (the residual stream updated in place) instead of a store.

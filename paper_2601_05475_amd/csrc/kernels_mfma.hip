@@ -301,120 +301,4 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   return MC_OK;
 }
 
-// =====================================================================================
-// Many-row GEMM on tiled operands: out[m][n] = sum_k a[m][k] w[n][k].  128 x 128 tile per
-// workgroup, one 64-deep unit per step staged through LDS as whole 4 KB blocks (the block layout
-// is already the MFMA operand layout, so LDS reads are conflict-free without padding).  2 x 2
-// waves, each 64 x 64 (2 x 2 MFMA tiles).  Weight rows feed the A operand so that a lane ends up
-// with runs of 4 consecutive n for 16-byte stores.
-// =====================================================================================
-template <bool SWIGLU>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(
-    int M, int N, int K, const bf16_t *__restrict__ a, const bf16_t *__restrict__ w,
-    const bf16_t *__restrict__ w2, float *__restrict__ out, bf16_t *__restrict__ out_t) {
-  constexpr int NW = SWIGLU ? 2 : 1;
-  __shared__ v4u As[4 * 256];            // 4 row tiles x (4 chunks x 64 lanes)
-  __shared__ v4u Ws[NW][4 * 256];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 31, h = lane >> 5;
-  const int wn = wave & 1, wm = wave >> 1;
-  const int U = K >> 6;
-  const int nt0 = blockIdx.x * 4, mt0 = blockIdx.y * 4;
-  const int m_tiles = (M + 31) >> 5;
-  // staging: thread t copies chunk t of every block (4 blocks per operand)
-  const v4u *ag[4], *wg[4], *ug[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ag[i] = (const v4u *)(a + (size_t)min(mt0 + i, m_tiles - 1) * U * 2048) + tid;
-    wg[i] = (const v4u *)(w + (size_t)(nt0 + i) * U * 2048) + tid;
-    ug[i] = SWIGLU ? (const v4u *)(w2 + (size_t)(nt0 + i) * U * 2048) + tid : nullptr;
-  }
-  f32x16 acc[NW][2][2];
-#pragma unroll
-  for (int i = 0; i < NW; ++i)
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int y = 0; y < 2; ++y)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][x][y][r] = 0.f;
-  v4u pa[4], pw[4], pu[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    pa[i] = ag[i][0];
-    pw[i] = wg[i][0];
-    if (SWIGLU) pu[i] = ug[i][0];
-  }
-  for (int u = 0; u < U; ++u) {
-    __syncthreads();           // everyone is done reading the previous unit
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      As[i * 256 + tid] = pa[i];
-      Ws[0][i * 256 + tid] = pw[i];
-      if (SWIGLU) Ws[NW - 1][i * 256 + tid] = pu[i];
-    }
-    __syncthreads();
-    if (u + 1 < U) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        pa[i] = ag[i][(size_t)(u + 1) * 256];
-        pw[i] = wg[i][(size_t)(u + 1) * 256];
-        if (SWIGLU) pu[i] = ug[i][(size_t)(u + 1) * 256];
-      }
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      v4u fa[2], fw[NW][2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        fa[t] = As[(2 * wm + t) * 256 + c * 64 + lane];
-        fw[0][t] = Ws[0][(2 * wn + t) * 256 + c * 64 + lane];
-        if (SWIGLU) fw[NW - 1][t] = Ws[NW - 1][(2 * wn + t) * 256 + c * 64 + lane];
-      }
-#pragma unroll
-      for (int i = 0; i < NW; ++i)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-          for (int mt = 0; mt < 2; ++mt) acc[i][nt][mt] = mfma32(fw[i][nt], fa[mt], acc[i][nt][mt]);
-    }
-  }
-#pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
-    const int m = 32 * (mt0 + 2 * wm + mt) + j;
-    if (m >= M) continue;
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int n = 32 * (nt0 + 2 * wn + nt) + 8 * r4 + 4 * h;
-        const f32x16 &g = acc[0][nt][mt];
-        if (SWIGLU) {
-          const f32x16 &uu = acc[NW - 1][nt][mt];
-          *(uint2 *)(out_t + tiled_offset(m, n, N)) =
-              pack4_bf16(silu_f(g[4 * r4]) * uu[4 * r4], silu_f(g[4 * r4 + 1]) * uu[4 * r4 + 1],
-                         silu_f(g[4 * r4 + 2]) * uu[4 * r4 + 2], silu_f(g[4 * r4 + 3]) * uu[4 * r4 + 3]);
-        } else {
-          *(float4 *)(out + (size_t)m * N + n) =
-              make_float4(g[4 * r4], g[4 * r4 + 1], g[4 * r4 + 2], g[4 * r4 + 3]);
-        }
-      }
-  }
-}
-
-bool gemm_supported(int M, int N, int K) { return M >= 1 && N % 128 == 0 && K % 64 == 0; }
-
-int launch_gemm_mfma(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                     const void *w2, float *out, void *out_t) {
-  if (!gemm_supported(M, N, K)) MC_FAIL(MC_ERR_UNSUPPORTED, "GEMM: M=%d N=%d K=%d not covered", M, N, K);
-  dim3 grid(N / 128, (M + 127) / 128);
-  if (w2)
-    gemm_mfma_kernel<true><<<grid, 256, 0, st>>>(M, N, K, (const bf16_t *)a, (const bf16_t *)w,
-                                                 (const bf16_t *)w2, out, (bf16_t *)out_t);
-  else
-    gemm_mfma_kernel<false><<<grid, 256, 0, st>>>(M, N, K, (const bf16_t *)a, (const bf16_t *)w,
-                                                  nullptr, out, (bf16_t *)out_t);
-  MC_HIP(hipGetLastError());
-  return MC_OK;
-}
-
 }  // namespace mc

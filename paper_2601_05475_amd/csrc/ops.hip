@@ -32,13 +32,9 @@ bool tiled_shapes_ok(int M, int N, int K) {
   return N % 128 == 0 && K % 256 == 0;
 }
 
-// The 256-row-tile GEMM pays off once its tiles cover most of the 256 CUs; smaller products
-// keep the 128-row-tile kernel, which has four times as many workgroups.
-static bool use_gemm256(int M, int N, int K, bool swiglu) {
-  if (!gemm256_supported(M, N, K, swiglu)) return false;
-  const long tiles = (long)((M + 255) / 256) * (N / (swiglu ? 128 : 256));
-  return tiles >= 160;
-}
+// Many-row products on tiled operands all go to the one MFMA GEMM (it beats a 128 x 128-tile
+// kernel from 128 rows up, measured).
+static bool use_gemm256(int M, int N, int K, bool swiglu) { return M > 64 && gemm256_supported(M, N, K, swiglu); }
 
 int linear_auto_splits(int dtype, int M, int N, int K, int tiled) {
   if (tiled) return (dtype == MC_BF16 && M <= 64) ? skinny_linear_splits(M, N, K) : 1;
@@ -57,8 +53,7 @@ int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a,
     MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
   if (M <= 64) return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits);
   if (n_splits != 1) MC_FAIL(MC_ERR_UNSUPPORTED, "the many-row GEMM does not split K");
-  if (use_gemm256(M, N, K, false)) return launch_gemm256(st, M, N, K, a, w, nullptr, out, nullptr);
-  return launch_gemm_mfma(st, M, N, K, a, w, nullptr, out, nullptr);
+  return launch_gemm256(st, M, N, K, a, w, nullptr, out, nullptr);
 }
 
 bool linear_qkv_rope_fused(int M, int N, int K) {
@@ -87,8 +82,7 @@ int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const v
   if (dtype != MC_BF16 || !tiled_shapes_ok(M, N, K))
     MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
   if (M <= 64) return launch_linear_skinny(st, M, N, K, a, wg, wu, nullptr, out, 1);
-  if (use_gemm256(M, N, K, true)) return launch_gemm256(st, M, N, K, a, wg, wu, nullptr, out);
-  return launch_gemm_mfma(st, M, N, K, a, wg, wu, nullptr, out);
+  return launch_gemm256(st, M, N, K, a, wg, wu, nullptr, out);
 }
 
 // ---- decode attention: MFMA split-K kernel when the shape allows, else the generic kernel ---

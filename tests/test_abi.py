@@ -87,8 +87,9 @@ def test_invalid_configs_are_rejected(lib):
     fake = C.c_void_p(256)                     # never dereferenced: the checks come first
     assert lib.mc_op_linear_accumulate(None, 4096, 4096, 4096, None, None, None) == -1
     assert lib.mc_op_linear_accumulate(None, 0, 4096, 4096, fake, fake, fake) == -1
-    assert lib.mc_op_linear_accumulate(None, 100, 4096, 4096, fake, fake, fake) == -5      # too few rows for 256-row tiles
-    assert lib.mc_op_linear_accumulate(None, 8192, 4000, 4096, fake, fake, fake) == -5     # N not a multiple of 256
+    assert lib.mc_op_linear_accumulate(None, 64, 4096, 4096, fake, fake, fake) == -5       # few rows: the weight-streaming path
+    assert lib.mc_op_linear_accumulate(None, 8192, 4000, 4096, fake, fake, fake) == -5     # N not a multiple of 128
+    assert lib.mc_op_linear_accumulate(None, 8192, 4096, 4000, fake, fake, fake) == -5     # K not a multiple of 256
     args = [fake] * 9
     assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 128, 64, 4096, 5e5, 100, *([None] * 9)) == -1
     assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 126, 64, 4096, 5e5, 100, *args) == -1   # head_dim % 4

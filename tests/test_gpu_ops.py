@@ -331,7 +331,7 @@ def test_linear_tiled(M, N, K, S):
     np.testing.assert_allclose(out, want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
 
 
-@pytest.mark.parametrize("M,N,K", [(3000, 4096, 256), (2300, 5632, 512)])
+@pytest.mark.parametrize("M,N,K", [(3000, 4096, 256), (2300, 5632, 512), (70, 128, 256), (130, 384, 1024), (300, 640, 512)])
 def test_linear_accumulate_tiled(M, N, K):
     """x += a w^T in the GEMM's epilogue (ragged last row tile, padding workgroup ids)."""
     import torch
@@ -349,6 +349,8 @@ def test_linear_accumulate_tiled(M, N, K):
     (64, 8, 2, 128, 512),
     (2100, 32, 8, 128, 256),       # many rows: the 256-row-tile GEMM (ragged last tile)
     (6200, 12, 2, 128, 256),       # N = 2048
+    (100, 4, 2, 64, 256),          # one ragged row tile, N = 512
+    (300, 5, 1, 128, 512),         # N = 896: an odd number of 128-column workgroups
 ])
 def test_linear_qkv_rope_fused(rows, Hq, Hkv, hd, K):
     """QKV projection + rotation + query / key / value stores in one kernel, against the oracle's
@@ -386,7 +388,7 @@ def test_linear_qkv_rope_fused(rows, Hq, Hkv, hd, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512),
-                                   (3000, 2048, 512), (2070, 2944, 256)])
+                                   (3000, 2048, 512), (2070, 2944, 256), (65, 384, 256)])
 def test_linear_swiglu_tiled(M, N, K):
     a = rnd(62, (M, K)); wg = rnd(63, (N, K), 0.05); wu = rnd(64, (N, K), 0.05)
     ad, av = to_dev(a, "bf16"); gd, gv = to_dev(wg, "bf16"); ud, uv = to_dev(wu, "bf16")
