@@ -35,7 +35,7 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
 TRAFFIC_GATE_UP = {"fetch_kib": 115741.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "7fca7a842d1800bd7639513f480cda6ad376288bfb27c39e92c64351aadf300f"}
+                   "sha256": "be0709d9c83dc99af57e05d17747debc3cf71b07aa04147b844cb63acc9e033c"}
 
 
 def measured_traffic_bytes(workload):
