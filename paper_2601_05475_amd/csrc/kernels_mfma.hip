@@ -242,13 +242,146 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
   }
 }
 
+// =====================================================================================
+// The same layer for 33..64 rows (two 32-row activation tiles).  In the form above every wave
+// fetches its own activation units, and with two tiles per weight tile that is as many bytes
+// from L2 as the weights bring from HBM (twice as many in the plain form), all of them addressed
+// to the same few hundred kilobytes: the layer then runs at 3-5 TB/s.  Here the four waves of a
+// workgroup take four different weight tiles over one common K range and share the activation
+// units through LDS (staged four units at a time, two buffers, one barrier per four units), so
+// the activations cross the L2-to-CU path once per workgroup instead of once per wave, and each
+// wave ends with complete sums for its tile: nothing to reduce across waves.  Weights stream
+// straight into MFMA operand registers, four units per wave in flight (a unit's registers are
+// refilled as soon as its MFMAs have been issued).  K splits are separate workgroups
+// (gridDim.y), each writing its own fp32 partial.
+// =====================================================================================
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void skinny_shared_kernel(
+    int M, int N, int K, int units_per_split, const bf16_t *__restrict__ a,
+    const bf16_t *__restrict__ w, const bf16_t *__restrict__ w2, float *__restrict__ out,
+    bf16_t *__restrict__ out_t) {
+  constexpr int MB = 2, NW = SWIGLU ? 2 : 1, CH = 4;
+  __shared__ v4u act[2][CH][MB][256];                         // 64 KB
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
+  const int tiles = N >> 5, U = K >> 6;
+  // every XCD (workgroups are dealt to them round-robin) takes a contiguous range of tile groups
+  const int per_xcd = gridDim.x >> 3;
+  const int wt_raw = 4 * ((int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3)) + wave;
+  const bool live = wt_raw < tiles;                           // a wave past the last tile only helps staging
+  const int wt = live ? wt_raw : tiles - 1;
+  const int split = blockIdx.y, u0 = split * units_per_split, n_chunks = units_per_split / CH;
+  const bf16_t *wp = w + ((size_t)wt * U + u0) * 2048 + lane * 8;
+  const bf16_t *up = SWIGLU ? w2 + ((size_t)wt * U + u0) * 2048 + lane * 8 : nullptr;
+  const bf16_t *ap = a + (size_t)u0 * 2048 + tid * 8;         // tile mb, unit u: + (mb * U + u) * 2048
+  f32x16 acc[NW][MB];
+#pragma unroll
+  for (int i = 0; i < NW; ++i)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][mb][r] = 0.f;
+
+  v4u stg[CH][MB], wf[CH][4], uf[CH][4];
+  auto load_act = [&](int chunk) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        stg[j][mb] = *(const v4u *)(ap + ((size_t)mb * U + chunk * CH + j) * 2048);
+  };
+  auto store_act = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) act[buf][j][mb][tid] = stg[j][mb];
+  };
+  auto issue_w = [&](int j, int u) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      wf[j][c] = load_stream(wp + (size_t)u * 2048 + c * 512);
+      if (SWIGLU) uf[j][c] = load_stream(up + (size_t)u * 2048 + c * 512);
+    }
+  };
+  load_act(0);
+#pragma unroll
+  for (int j = 0; j < CH; ++j) issue_w(j, j);
+  store_act(0);
+  if (n_chunks > 1) load_act(1);
+  __syncthreads();
+  for (int i = 0; i < n_chunks; ++i) {
+    const int buf = i & 1;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      v4u af[MB][4];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) af[mb][c] = act[buf][j][mb][c * 64 + lane];
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+          acc[0][mb] = mfma32(wf[j][c], af[mb][c], acc[0][mb]);
+          if (SWIGLU) acc[NW - 1][mb] = mfma32(uf[j][c], af[mb][c], acc[NW - 1][mb]);
+        }
+      if (i + 1 < n_chunks) issue_w(j, (i + 1) * CH + j);
+    }
+    // the other buffer was last read during chunk i - 1, which every wave left before the barrier
+    // that ended it
+    if (i + 1 < n_chunks) {
+      store_act(buf ^ 1);
+      if (i + 2 < n_chunks) load_act(i + 2);
+    }
+    __syncthreads();
+  }
+  if (!live) return;
+  // the wave's own sums: lane (nl, h) holds row nl of each activation tile and, per register
+  // quad r4, columns 8 r4 + 4 h .. + 3 of the weight tile
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const int m = mb * 32 + nl;
+    if (m >= M) continue;
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int n = 32 * wt + 8 * r4 + 4 * h;
+      const f32x16 &g = acc[0][mb];
+      if (SWIGLU) {
+        const f32x16 &v = acc[NW - 1][mb];
+        *(uint2 *)(out_t + tiled_offset(m, n, N)) =
+            pack4_bf16(silu_f(g[4 * r4]) * v[4 * r4], silu_f(g[4 * r4 + 1]) * v[4 * r4 + 1],
+                       silu_f(g[4 * r4 + 2]) * v[4 * r4 + 2], silu_f(g[4 * r4 + 3]) * v[4 * r4 + 3]);
+      } else {
+        *(float4 *)(out + ((size_t)split * M + m) * N + n) =
+            make_float4(g[4 * r4], g[4 * r4 + 1], g[4 * r4 + 2], g[4 * r4 + 3]);
+      }
+    }
+  }
+}
+
 bool skinny_linear_supported(int M, int N, int K) {
   return M >= 1 && M <= 64 && N % 32 == 0 && K % 256 == 0;
 }
 
+// Two activation tiles: the shared-activation form, if its workgroups (four weight tiles each)
+// can fill the chip; fewer of them leave CUs idle and the one-tile-per-workgroup form is faster
+// (measured at 112 workgroups: 57 against 45 us).
+static bool skinny_shared_form(int M, int N, int n_splits, bool rope) {
+  return M > 32 && !rope && (N / 32 + 3) / 4 * n_splits >= 160;
+}
+
 int skinny_linear_splits(int M, int N, int K) {
-  (void)M;
   const int tiles = N / 32, units = K / 64;
+  if (M > 32) {
+    // any divisor of units / 4 will do there
+    const int groups = (tiles + 3) / 4;
+    int best = 1;
+    for (int s = 1; s <= 16; ++s) {
+      if (units % (4 * s)) continue;
+      best = s;
+      if (groups * s >= 192) break;
+    }
+    if (skinny_shared_form(M, N, best, false)) return best;
+  }
   int best = 1;
   for (int s = 1; s <= 16; s *= 2) {
     if (units % (4 * s)) break;
@@ -268,6 +401,23 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   if (rope && (w2 || n_splits != 1 || rope->hd % 4 || N != (rope->Hq + 2 * rope->Hkv) * rope->hd))
     MC_FAIL(MC_ERR_INVALID, "fused QKV output: one K split, N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
   const RopeOut none{};
+  if (skinny_shared_form(M, N, n_splits, rope != nullptr)) {
+    const int groups = (N / 32 + 3) / 4;
+    const dim3 grid2((groups + 7) / 8 * 8, n_splits);
+    const LaunchEvents ev2 = take_launch_events();
+    auto go2 = [&](auto kernel) {
+      if (ev2.start || ev2.stop)
+        hipExtLaunchKernelGGL(kernel, grid2, dim3(256), 0, st, ev2.start, ev2.stop, 0, M, N, K, units / n_splits,
+                              (const bf16_t *)a, (const bf16_t *)w, (const bf16_t *)w2, out, (bf16_t *)out_t);
+      else
+        kernel<<<grid2, 256, 0, st>>>(M, N, K, units / n_splits, (const bf16_t *)a, (const bf16_t *)w,
+                                      (const bf16_t *)w2, out, (bf16_t *)out_t);
+    };
+    if (w2) go2(skinny_shared_kernel<true>);
+    else go2(skinny_shared_kernel<false>);
+    MC_HIP(hipGetLastError());
+    return MC_OK;
+  }
   int upw = units / (4 * n_splits);
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
   bf16_t *OT = (bf16_t *)out_t;

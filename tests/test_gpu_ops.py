@@ -315,6 +315,8 @@ def test_pack_tiled_roundtrip():
     (64, 384, 768, 1), (5, 6144, 4096, 0), (32, 4096, 14336, 0),
     (32, 128256, 4096, 0),         # the LM head of the 8B shape (two weight tiles per workgroup)
     (40, 65664, 256, 1),           # the same form with two row tiles of activations
+    # 33..64 rows, enough weight tiles: four tiles per workgroup sharing the activations through LDS
+    (64, 5120, 1024, 0), (33, 25600, 256, 1), (64, 3200, 2304, 0), (50, 20480, 512, 2), (64, 5120, 5120, 0),
     (65, 128, 256, 1), (200, 256, 512, 1), (130, 384, 1024, 1), (4096, 128, 256, 1),
     # 256-row-tile GEMM: ragged last row tile, a last band of fewer than 8 row tiles, padding ids
     (3000, 4096, 256, 1), (2300, 5632, 512, 1),
@@ -388,7 +390,8 @@ def test_linear_qkv_rope_fused(rows, Hq, Hkv, hd, K):
 
 
 @pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512),
-                                   (3000, 2048, 512), (2070, 2944, 256), (65, 384, 256)])
+                                   (3000, 2048, 512), (2070, 2944, 256), (65, 384, 256),
+                                   (50, 27648, 512), (64, 20480, 256)])
 def test_linear_swiglu_tiled(M, N, K):
     a = rnd(62, (M, K)); wg = rnd(63, (N, K), 0.05); wu = rnd(64, (N, K), 0.05)
     ad, av = to_dev(a, "bf16"); gd, gv = to_dev(wg, "bf16"); ud, uv = to_dev(wu, "bf16")
