@@ -33,9 +33,9 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115741.9, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115742.2, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "be0709d9c83dc99af57e05d17747debc3cf71b07aa04147b844cb63acc9e033c"}
+                   "sha256": "7cfbe178efc61816ff285b7ce09cd98b0f344b10f3be73ef01922dfcf001c86c"}
 
 
 def measured_traffic_bytes(workload):
