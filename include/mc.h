@@ -335,9 +335,11 @@ int mc_op_rope_kv_write(void *stream, int32_t dtype, int32_t rows, int32_t n_q_h
                         const int32_t *row_pos, const int32_t *row_page,
                         const int32_t *row_off, void *q_out, void *k_pages, void *v_pages);
 
-/* Decode attention for n_cands candidates in lock-step: candidate b attends to the
- * prefix_len keys of the shared prefix (pages 0.. of k_prefix/v_prefix, in order) and
- * to its own suffix_len keys (pages page_table[b][0..] of k_suffix/v_suffix).
+/* Decode attention for n_cands candidates: candidate b attends to the prefix_len keys of the
+ * shared prefix (pages 0.. of k_prefix/v_prefix, in order) and to its own suffix keys (pages
+ * page_table[b][0..] of k_suffix/v_suffix): suffix_len of them, or, with row_len (device,
+ * [n_cands]) given, row_len[b] of them, 1 <= row_len[b] <= suffix_len (other values are
+ * clamped into that range) for candidates of different lengths.
  * q, out: (T)[n_cands][Hq][hd].  workspace: fp32 scratch of mc_op_attention_decode_ws
  * bytes.  prefix_splits: key-axis splits of the prefix (0 = automatic).  out_tiled = 1 stores
  * out as a tiled [n_cands][Hq*hd] matrix. */
@@ -349,8 +351,8 @@ int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t
                            int32_t prefix_len, int32_t suffix_len, const void *q,
                            const void *k_prefix, const void *v_prefix, const void *k_suffix,
                            const void *v_suffix, const int32_t *page_table,
-                           int32_t table_stride, int32_t prefix_splits, void *workspace,
-                           size_t workspace_bytes, void *out, int32_t out_tiled);
+                           int32_t table_stride, const int32_t *row_len, int32_t prefix_splits,
+                           void *workspace, size_t workspace_bytes, void *out, int32_t out_tiled);
 
 /* Host-only: the work-item plan mc_op_attention_decode would launch for these sizes on the bf16
  * MFMA path (MC_ERR_UNSUPPORTED for shapes that path does not cover).  out8 (host): prefix items

@@ -122,6 +122,9 @@ struct DecodeAttnArgs {
   const int32_t *row_cand = nullptr;   // device: page-table row of each candidate row (nullptr: row r uses table row r)
   int32_t n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens;
   int32_t prefix_len, suffix_len;
+  // device, or nullptr: suffix keys of each candidate row (values outside 1..suffix_len are
+  // clamped); nullptr = suffix_len for every row (lock-step)
+  const int32_t *row_len = nullptr;
   int32_t prefix_splits;         // 0 = automatic
   void *workspace;
   size_t workspace_bytes;

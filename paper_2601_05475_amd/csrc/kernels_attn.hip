@@ -99,8 +99,10 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     b_item = id / Hkv;
     part = ((a.prefix_len > 0) ? it.splits : 0) + ss;
     first_blk = ss * it.suffix_bps;
-    blk_end = min(first_blk + it.suffix_bps, it.n_suffix_blocks);
-    len = a.suffix_len;
+    // candidates of different lengths: the plan is laid out for the longest, an item past its
+    // candidate's last block has nothing to do and writes an empty partial state
+    len = a.row_len ? min(max(a.row_len[b_item], 1), a.suffix_len) : a.suffix_len;
+    blk_end = min(first_blk + it.suffix_bps, (len + 31) >> 5);
     kpool = (const bf16_t *)a.k_suffix; vpool = (const bf16_t *)a.v_suffix;
     table = a.page_table + (size_t)(a.row_cand ? a.row_cand[b_item] : b_item) * a.table_stride;
     col0 = 0;

@@ -86,11 +86,14 @@ int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const v
 }
 
 // ---- decode attention: MFMA split-K kernel when the shape allows, else the generic kernel ---
-__global__ void fill_decode_rows_kernel(int B, int pos, const int32_t *__restrict__ row_cand,
+__global__ void fill_decode_rows_kernel(int B, int prefix_len, int suffix_len,
+                                        const int32_t *__restrict__ row_len,
+                                        const int32_t *__restrict__ row_cand,
                                         int32_t *row_pos, int32_t *row_tab) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b < B) {
-    row_pos[b] = pos;
+    const int len = (row_len && suffix_len) ? min(max(row_len[b], 1), suffix_len) : suffix_len;
+    row_pos[b] = prefix_len + len - 1;          // the row sees the keys at positions <= this one
     row_tab[b] = row_cand ? row_cand[b] : b;
   }
 }
@@ -110,7 +113,7 @@ int launch_attention_decode(hipStream_t st, int dtype, const DecodeAttnArgs &a) 
     MC_FAIL(MC_ERR_INVALID, "attention workspace too small");
   int32_t *row_pos = (int32_t *)a.workspace, *row_tab = row_pos + a.n_cands;
   fill_decode_rows_kernel<<<(a.n_cands + 63) / 64, 64, 0, st>>>(
-      a.n_cands, a.prefix_len + a.suffix_len - 1, a.row_cand, row_pos, row_tab);
+      a.n_cands, a.prefix_len, a.suffix_len, a.row_len, a.row_cand, row_pos, row_tab);
   MC_HIP(hipGetLastError());
   AttnArgs g;
   g.q = a.q; g.k_prefix = a.k_prefix; g.v_prefix = a.v_prefix; g.k_suffix = a.k_suffix;
@@ -241,7 +244,7 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
                                       const void *q, const void *k_prefix, const void *v_prefix,
                                       const void *k_suffix, const void *v_suffix,
                                       const int32_t *page_table, int32_t table_stride,
-                                      int32_t prefix_splits, void *workspace,
+                                      const int32_t *row_len, int32_t prefix_splits, void *workspace,
                                       size_t workspace_bytes, void *out, int32_t out_tiled) {
   MC_TRY(check_dtype(dtype));
   if (n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || head_dim < 2 ||
@@ -261,6 +264,7 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   a.page_table = page_table; a.table_stride = table_stride; a.n_cands = n_cands;
   a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
   a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.suffix_len = suffix_len;
+  a.row_len = suffix_len ? row_len : nullptr;
   a.prefix_splits = prefix_splits; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
   a.out = out; a.out_tiled = out_tiled;
   return launch_attention_decode((hipStream_t)stream, dtype, a);

@@ -147,6 +147,47 @@ def test_attention_decode(dtype, B, Hq, Hkv, hd, pg, P, t):
     assert worst < (2e-5 if dtype == "f32" else 1.5e-2), worst
 
 
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,hd,pg,P,t", [
+    ("f32", 5, 4, 2, 64, 4, 30, 19), ("bf16", 6, 8, 2, 128, 64, 300, 200), ("bf16", 9, 32, 8, 128, 64, 1000, 333),
+    ("bf16", 4, 8, 4, 64, 64, 0, 130), ("bf16", 3, 8, 2, 96, 64, 100, 70),
+])
+def test_attention_decode_candidates_of_different_lengths(dtype, B, Hq, Hkv, hd, pg, P, t):
+    """row_len: every candidate attends to its own number of suffix keys (1 .. t; some end inside
+    the first block, some on a block or page edge, one is at the maximum), against the oracle's
+    attention on exactly those keys."""
+    import torch
+    n_pre = -(-P // pg) if P else 0
+    per = -(-t // pg)
+    kpd, vpd, kpv, vpv = make_pools(dtype, max(n_pre, 1), Hkv, pg, hd, 41)
+    ksd, vsd, ksv, vsv = make_pools(dtype, B * per, Hkv, pg, hd, 43)
+    rng = np.random.default_rng(44)
+    table = rng.permutation(B * per).astype(np.int32).reshape(B, per)
+    lens = rng.integers(1, t + 1, B).astype(np.int32)
+    lens[0], lens[1] = t, 1
+    if B > 2:
+        lens[2] = min(t, 32)
+    if B > 3:
+        lens[3] = min(t, pg)
+    q = rnd(45, (B, Hq, hd))
+    qd, qv = to_dev(q, dtype)
+    print("case: ragged attention", dtype, B, Hq, Hkv, hd, pg, P, t, lens.tolist(), flush=True)
+    out = binding.op_attention_decode(qd, kpd if P else None, vpd if P else None, ksd, vsd,
+                                      torch.from_numpy(table).cuda(), P, t, pg,
+                                      row_len=torch.from_numpy(lens).cuda()).float().cpu().numpy()
+    G = Hq // Hkv
+    worst = 0.0
+    for b in range(B):
+        for a in range(Hq):
+            c = a // G
+            keys = [kpv[:, c].reshape(-1, hd)[:P]] if P else []
+            vals = [vpv[:, c].reshape(-1, hd)[:P]] if P else []
+            keys.append(ksv[table[b], c].reshape(-1, hd)[:lens[b]])
+            vals.append(vsv[table[b], c].reshape(-1, hd)[:lens[b]])
+            want = otf.attention_one(qv[b, a], np.concatenate(keys), np.concatenate(vals))
+            worst = max(worst, np.abs(out[b, a] - want).max())
+    assert worst < (2e-5 if dtype == "f32" else 1.5e-2), worst
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,hd,P,t,stride", [
     (32, 32, 8, 128, 4096, 512, 7),      # 8B-shape headline workload at its last step
     (32, 32, 8, 128, 4096, 1, 7),        # ... and at its first
