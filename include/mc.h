@@ -144,6 +144,17 @@ int mc_promote_candidate(mc_session *s, int32_t cand);
  *    from.  Candidates stay in lock-step (one common len).  Errors: MC_ERR_STATE without a
  *    prefix, MC_ERR_OOM beyond max_suffix, MC_ERR_INVALID for a changed n_cands.  Asynchronous. */
 int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len);
+/*    The same with a length of its own for every candidate (the candidates and their feedback
+ *    differ in length): row r of suffix_tokens (host [n_cands][max_len]) holds lens[r] tokens,
+ *    1 <= lens[r] <= max_len, for the r-th candidate still decoding.  From then on the
+ *    candidates sit at different suffix positions: mc_decode_step appends each one's token at its
+ *    own position (own rotary angle, own page slot, attention over its own keys), a candidate
+ *    takes a new page when its own length reaches a page boundary (candidates in ascending order
+ *    at every token index, as a lock-step decode of the same tokens would), mc_promote_candidate
+ *    moves that candidate's own length, and MC_ERR_OOM is returned once any candidate would
+ *    exceed max_suffix (drop it to go on with the others). */
+int mc_prefill_suffix_ragged(mc_session *s, const int32_t *suffix_tokens, const int32_t *lens,
+                             int32_t n_cands, int32_t max_len);
 
 /* 1d. Candidates end at different lengths, and a value-guided search keeps only the promising
  *    ones (Sec. 3.3).  mc_drop_candidates removes the n candidates cands[.] (ids as numbered when

@@ -32,28 +32,50 @@ def slot_of(table: np.ndarray, b: int, j: int, page_tokens: int):
 
 
 class PagePool:
-    """The same rule with candidates that leave early: the free list is a queue.  A candidate
-    that is dropped gives its pages back to the tail of the queue (candidates in ascending index,
-    each one's pages in the order it took them); at a page boundary only the candidates still
-    decoding are visited.  Written event by event so that a test can replay a call sequence."""
+    """The same rule with candidates that leave early and candidates of different lengths: the
+    free list is a queue.  Appends happen token index by token index; at every index the
+    candidates that still have a token to append are visited in ascending order, and one whose
+    own suffix length is a multiple of the page size takes the page at the head of the queue.  A
+    candidate that is dropped gives its pages back to the tail of the queue (candidates in
+    ascending index, each one's pages in the order it took them).  Written event by event so
+    that a test can replay a call sequence."""
 
     def __init__(self, n_cands: int, page_tokens: int, free_list):
         self.free = list(free_list)
         self.page_tokens = page_tokens
         self.alive = list(range(n_cands))
         self.pages = {b: [] for b in range(n_cands)}
-        self.length = 0                                  # common suffix length
+        self.lens = {b: 0 for b in range(n_cands)}
+
+    @property
+    def length(self):
+        """Longest suffix among the candidates still decoding."""
+        return max(self.lens[b] for b in self.alive)
+
+    def append_each(self, counts):
+        """counts[i] tokens for the i-th candidate still decoding.  Raises MemoryError, with the
+        pool untouched, if the queue cannot serve the whole call."""
+        counts = list(counts)
+        assert len(counts) == len(self.alive)
+        free, lens, taken = list(self.free), dict(self.lens), {b: [] for b in self.alive}
+        for j in range(max(counts)):
+            for i, b in enumerate(self.alive):
+                if j >= counts[i]:
+                    continue
+                if lens[b] % self.page_tokens == 0:
+                    if not free:
+                        raise MemoryError("page pool exhausted")
+                    taken[b].append(free.pop(0))
+                lens[b] += 1
+        self.free, self.lens = free, lens
+        for b in self.alive:
+            self.pages[b].extend(taken[b])
 
     def append(self, n_tokens: int = 1):
-        """n_tokens lock-step appends; raises MemoryError (state untouched by the failing append)
-        if a boundary needs more pages than the queue holds."""
+        """n_tokens lock-step appends, one call each (a failing one leaves the pool as the last
+        successful one left it)."""
         for _ in range(n_tokens):
-            if self.length % self.page_tokens == 0:
-                if len(self.free) < len(self.alive):
-                    raise MemoryError("page pool exhausted")
-                for b in self.alive:
-                    self.pages[b].append(self.free.pop(0))
-            self.length += 1
+            self.append_each([1] * len(self.alive))
 
     def drop(self, ids):
         for b in sorted(ids):

@@ -70,6 +70,7 @@ SIGNATURES = {
     "mc_extend_shared": (C.c_int, [_vp, _vp, _i32]),
     "mc_promote_candidate": (C.c_int, [_vp, _i32]),
     "mc_prefill_suffix": (C.c_int, [_vp, _vp, _i32, _i32]),
+    "mc_prefill_suffix_ragged": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
     "mc_drop_candidates": (C.c_int, [_vp, _vp, _i32]),
     "mc_reward_bin": (_i32, [C.c_double, _i32, _vp]),
     "mc_best_so_far": (C.c_int, [_vp, _vp, _i32, C.c_double, _vp]),
@@ -239,6 +240,13 @@ class Session:
         """suffix_tokens: [n_cands, len] appended to every candidate in one pass."""
         t = np.ascontiguousarray(suffix_tokens, dtype=np.int32)
         _check(load_library().mc_prefill_suffix(self.handle, t.ctypes.data, t.shape[0], t.shape[1]))
+
+    def prefill_suffix_ragged(self, suffix_tokens: np.ndarray, lens):
+        """suffix_tokens: [n_cands, max_len]; row r holds lens[r] tokens."""
+        t = np.ascontiguousarray(suffix_tokens, dtype=np.int32)
+        ln = np.ascontiguousarray(lens, dtype=np.int32)
+        assert ln.shape == (t.shape[0],)
+        _check(load_library().mc_prefill_suffix_ragged(self.handle, t.ctypes.data, ln.ctypes.data, t.shape[0], t.shape[1]))
 
     def drop_candidates(self, cands):
         c = np.ascontiguousarray(cands, dtype=np.int32)

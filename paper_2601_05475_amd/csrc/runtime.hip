@@ -1,6 +1,7 @@
 // Host runtime behind the C ABI: models, sessions (shared-prefix KV block, suffix page pool,
 // page table), the four calls and the inspection hooks.  No device allocation happens here:
 // everything is carved out of the caller's arenas.
+#include <limits.h>
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -236,7 +237,7 @@ constexpr int kProfCap = 8192;
 struct SessionLayout {
   size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
       hlast, attn_ws, alive, rope_tab, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
-      page_new, score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
+      page_new, cand_len, row_len, score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
   size_t total;
   // derived sizes
   int rows_cap, n_prefix_pages, n_pool_pages, pages_per_cand, n_score_pages;
@@ -304,7 +305,9 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.row_tab = at(R * 4);
   o.last_idx = at((size_t)p.max_cands * 4);
   o.page_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
-  o.page_new = at((size_t)p.max_cands * 4);
+  o.page_new = at((size_t)p.max_cands * o.pages_per_cand * 8);     // table indices, then page ids
+  o.cand_len = at((size_t)p.max_cands * 4);
+  o.row_len = at((size_t)p.max_cands * 4);
   o.score_table = at((size_t)p.max_cands * o.pages_per_cand * 4);
   o.items = at((R / 32 + p.max_cands + 2) * 16);
   o.samp_tok = at((size_t)p.max_cands * 4);
@@ -341,6 +344,11 @@ struct mc_session {
   // of every per-candidate buffer belongs to candidate alive[r]
   std::vector<int32_t> alive;
   bool dropped_any = false;
+  // suffix tokens held by every started candidate (by id).  suffix_len is the longest among the
+  // candidates still decoding; ragged: they are not all that long (set by mc_prefill_suffix_ragged,
+  // cleared when the survivors of a drop are level again)
+  std::vector<int32_t> cand_len;
+  bool ragged = false;
   int prefix_splits = 0;
   // The pool's free pages are a queue: at a page boundary the candidates still decoding take
   // pages from its head in ascending candidate order; a dropped candidate's pages go to its tail.
@@ -514,6 +522,7 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
       a.n_cands = rows; a.n_q_heads = c.n_q_heads; a.n_kv_heads = c.n_kv_heads;
       a.head_dim = c.head_dim; a.page_tokens = s->p.page_tokens;
       a.prefix_len = s->prefix_len; a.suffix_len = s->suffix_len + 1;
+      a.row_len = s->ragged ? s->ptr<int32_t>(L.row_len) : nullptr;
       a.prefix_splits = s->prefix_splits;
       a.row_cand = s->dropped_any ? row_tab : nullptr;
       a.workspace = s->ptr<void>(L.attn_ws); a.workspace_bytes = L.attn_ws_bytes; a.out = ao;
@@ -684,6 +693,8 @@ extern "C" int mc_session_reset_candidates(mc_session *s) {
   s->sampled_on_device = false;
   s->free_q.assign(s->free_list.begin(), s->free_list.end());
   s->alive.clear();
+  s->cand_len.clear();
+  s->ragged = false;
   s->dropped_any = false;
   std::fill(s->host_table.begin(), s->host_table.end(), -1);
   if (s->prefix_len > 0) {
@@ -800,7 +811,8 @@ extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
   if (cand < 0 || cand >= s->n_cands) MC_FAIL(MC_ERR_INVALID, "candidate %d outside [0, %d)", cand, s->n_cands);
   const int ri = (int)(std::find(s->alive.begin(), s->alive.end(), cand) - s->alive.begin());
   if (ri >= (int)s->alive.size()) MC_FAIL(MC_ERR_INVALID, "candidate %d was dropped", cand);
-  const int t = s->suffix_len, P = s->prefix_len;
+  const int t = s->cand_len[cand], P = s->prefix_len;
+  if (t < 1) MC_FAIL(MC_ERR_STATE, "mc_promote_candidate: candidate %d holds no token", cand);
   if (t > s->p.max_prefix - P)
     MC_FAIL(MC_ERR_OOM, "prefix of %d + suffix of %d tokens exceeds max_prefix %d", P, t, s->p.max_prefix);
   MC_HIP(hipSetDevice(s->m->device));
@@ -844,52 +856,83 @@ static void fix_cands(mc_session *s, int n_cands) {
   s->n_cands = n_cands;
   s->alive.resize(n_cands);
   for (int b = 0; b < n_cands; ++b) s->alive[b] = b;
+  s->cand_len.assign(n_cands, 0);
+  s->ragged = false;
+}
+static void refresh_lengths(mc_session *s) {
+  int lo = INT32_MAX, hi = 0;
+  for (int b : s->alive) { lo = std::min(lo, s->cand_len[b]); hi = std::max(hi, s->cand_len[b]); }
+  s->suffix_len = hi;
+  s->ragged = lo != hi;
 }
 static void unfix_cands(mc_session *s, int saved_total) {
-  if (saved_total == 0) { s->n_cands = 0; s->alive.clear(); }
+  if (saved_total == 0) { s->n_cands = 0; s->alive.clear(); s->cand_len.clear(); }
 }
 
-__global__ void set_pages_kernel(int n, int slot, int stride, const int32_t *__restrict__ alive,
-                                 const int32_t *__restrict__ ids, int32_t *table) {
-  const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r < n) table[(size_t)(alive ? alive[r] : r) * stride + slot] = ids[r];
+__global__ void scatter_i32_kernel(int n, const int32_t *__restrict__ idx, const int32_t *__restrict__ val,
+                                   int32_t *dst) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[idx[i]] = val[i];
 }
 
-// Pages for the slots slot0 .. slot0 + n_slots - 1 of every candidate still decoding, read off
-// the head of the queue without removing them (slot by slot, candidates ascending within a slot:
-// fresh[i * n_alive + r]), and written into the device page table.  The queue and the host table
-// change only in commit_pages, once the step that needed the pages has been enqueued.
-static int stage_pages(mc_session *s, int slot0, int n_slots, std::vector<int32_t> &fresh) {
-  const SessionLayout &L = s->lay;
-  const int n_alive = (int)s->alive.size();
-  fresh.clear();
-  if (n_slots <= 0) return MC_OK;
-  if (slot0 + n_slots > L.pages_per_cand) MC_FAIL(MC_ERR_OOM, "suffix longer than max_suffix");
-  if ((size_t)n_slots * n_alive > s->free_q.size())
-    MC_FAIL(MC_ERR_OOM, "page pool exhausted: %d candidates need %d page(s) each, %zu of %d pages are free", n_alive,
-            n_slots, s->free_q.size(), L.n_pool_pages);
-  fresh.assign(s->free_q.begin(), s->free_q.begin() + (size_t)n_slots * n_alive);
-  for (int i = 0; i < n_slots; ++i) {
-    MC_TRY(upload(s, s->ptr<void>(L.page_new), fresh.data() + (size_t)i * n_alive, (size_t)n_alive * 4));
-    set_pages_kernel<<<(n_alive + 63) / 64, 64, 0, s->stream>>>(n_alive, slot0 + i, L.pages_per_cand,
-        s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.page_new), s->ptr<int32_t>(L.page_table));
-    MC_HIP(hipGetLastError());
-  }
+// host -> device for blocks that may exceed one staging slot
+static int upload_long(mc_session *s, void *dst, const void *src, size_t bytes) {
+  for (size_t at = 0; at < bytes; at += s->slot_bytes)
+    MC_TRY(upload(s, (char *)dst + at, (const char *)src + at, std::min(s->slot_bytes, bytes - at)));
   return MC_OK;
 }
-static void commit_pages(mc_session *s, int slot0, const std::vector<int32_t> &fresh) {
-  const int n_alive = (int)s->alive.size();
+
+// Pages for the table entries idx[.] (candidate * pages_per_cand + slot, in the order the
+// candidates take them), read off the head of the queue without removing them and written into
+// the device page table.  The queue and the host table change only in commit_pages, once the
+// step that needed the pages has been enqueued, so a refused or failed step leaves nothing behind.
+static int stage_pages(mc_session *s, const std::vector<int32_t> &idx, std::vector<int32_t> &fresh) {
+  const SessionLayout &L = s->lay;
+  fresh.clear();
+  const size_t n = idx.size();
+  if (n == 0) return MC_OK;
+  if (n > s->free_q.size())
+    MC_FAIL(MC_ERR_OOM, "page pool exhausted: %zu page(s) needed, %zu of %d pages are free", n, s->free_q.size(),
+            L.n_pool_pages);
+  if (n > (size_t)s->p.max_cands * L.pages_per_cand) MC_FAIL(MC_ERR_INVALID, "internal: page list too long");
+  fresh.assign(s->free_q.begin(), s->free_q.begin() + n);
+  int32_t *d_idx = s->ptr<int32_t>(L.page_new), *d_val = d_idx + (size_t)s->p.max_cands * L.pages_per_cand;
+  MC_TRY(upload_long(s, d_idx, idx.data(), n * 4));
+  MC_TRY(upload_long(s, d_val, fresh.data(), n * 4));
+  scatter_i32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s->stream>>>((int)n, d_idx, d_val, s->ptr<int32_t>(L.page_table));
+  MC_HIP(hipGetLastError());
+  return MC_OK;
+}
+static void commit_pages(mc_session *s, const std::vector<int32_t> &idx, const std::vector<int32_t> &fresh) {
   for (size_t i = 0; i < fresh.size(); ++i) {
-    s->host_table[(size_t)s->alive[i % n_alive] * s->lay.pages_per_cand + slot0 + i / n_alive] = fresh[i];
+    s->host_table[idx[i]] = fresh[i];
     s->free_q.pop_front();
   }
+}
+
+// rows of a decode step whose candidates differ in length: everything per row comes from the
+// candidate's own length (cand_len, by candidate id)
+__global__ void decode_rows_ragged_kernel(int B, int prefix_len, int pg, int table_stride,
+                                          const int32_t *__restrict__ table, const int32_t *__restrict__ alive,
+                                          const int32_t *__restrict__ cand_len, int32_t *row_pos,
+                                          int32_t *row_page, int32_t *row_off, int32_t *row_tab, int32_t *row_len) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int cand = alive ? alive[b] : b;
+  const int t = cand_len[cand];
+  row_pos[b] = prefix_len + t;
+  row_page[b] = table[(size_t)cand * table_stride + t / pg];
+  row_off[b] = t % pg;
+  row_tab[b] = cand;
+  row_len[b] = t + 1;
 }
 
 extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_cands) {
   if (!s) MC_FAIL(MC_ERR_INVALID, "session is NULL");
   if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_decode_step before mc_prefill_shared");
   MC_TRY(check_cand_count(s, n_cands));
-  if (s->suffix_len >= s->p.max_suffix) MC_FAIL(MC_ERR_OOM, "suffix is full (%d tokens): page pool exhausted", s->suffix_len);
+  if (s->suffix_len >= s->p.max_suffix)
+    MC_FAIL(MC_ERR_OOM, "suffix is full (%d tokens): a candidate has reached max_suffix", s->suffix_len);
   const mc_config &c = s->m->cfg;
   if (tokens) MC_TRY(check_tokens(c, tokens, n_cands));
   else if (!s->sampled_on_device) MC_FAIL(MC_ERR_STATE, "tokens is NULL but no mc_sample result is pending on the device");
@@ -898,20 +941,32 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   const int pg = s->p.page_tokens, t = s->suffix_len;
   const int saved_n = s->n_cands;
   fix_cands(s, n_cands);
-  std::vector<int32_t> fresh;
-  if (int rc0 = stage_pages(s, t / pg, t % pg == 0 ? 1 : 0, fresh)) { unfix_cands(s, saved_n); return rc0; }
+  // candidates at a page boundary take a page each, in ascending order
+  std::vector<int32_t> idx, fresh;
+  for (int b : s->alive)
+    if (s->cand_len[b] % pg == 0) idx.push_back(b * L.pages_per_cand + s->cand_len[b] / pg);
+  if (int rc0 = stage_pages(s, idx, fresh)) { unfix_cands(s, saved_n); return rc0; }
   if (tokens) MC_TRY(upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4));
   else MC_HIP(hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4, hipMemcpyDeviceToDevice, s->stream));
-  decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
-      n_cands, s->prefix_len + t, t / pg, t % pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
-      s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
-      s->ptr<int32_t>(L.row_tab));
+  if (s->ragged) {
+    MC_TRY(upload(s, s->ptr<void>(L.cand_len), s->cand_len.data(), (size_t)s->n_cands * 4));
+    decode_rows_ragged_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
+        n_cands, s->prefix_len, pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
+        s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.cand_len), s->ptr<int32_t>(L.row_pos),
+        s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off), s->ptr<int32_t>(L.row_tab), s->ptr<int32_t>(L.row_len));
+  } else {
+    decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
+        n_cands, s->prefix_len + t, t / pg, t % pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
+        s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
+        s->ptr<int32_t>(L.row_tab));
+  }
   MC_HIP(hipGetLastError());
   int tail = 0;
   int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, 0, &tail);
   if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
   if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
-  commit_pages(s, t / pg, fresh);
+  commit_pages(s, idx, fresh);
+  for (int b : s->alive) s->cand_len[b]++;
   s->suffix_len = t + 1;
   s->logits_state = LOGITS_CANDS;
   s->logits_rows = n_cands;
@@ -1088,51 +1143,78 @@ extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n
       }
   s->alive = new_alive;
   s->dropped_any = true;
+  refresh_lengths(s);
   if (s->logits_state == LOGITS_CANDS) s->logits_rows = new_n;
   return MC_OK;
 }
 
-extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len) {
+// lens == nullptr: every candidate gets max_len tokens.  Row r of suffix_tokens ([n_cands][max_len])
+// belongs to the r-th candidate still decoding.
+static int prefill_suffix_impl(mc_session *s, const int32_t *suffix_tokens, const int32_t *lens, int32_t n_cands,
+                               int32_t max_len, const char *who) {
   if (!s || !suffix_tokens) MC_FAIL(MC_ERR_INVALID, "session / suffix_tokens is NULL");
-  if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "mc_prefill_suffix before mc_prefill_shared");
+  if (s->prefix_len <= 0) MC_FAIL(MC_ERR_STATE, "%s before mc_prefill_shared", who);
   MC_TRY(check_cand_count(s, n_cands));
-  const int t = s->suffix_len;
-  if (len < 1) MC_FAIL(MC_ERR_INVALID, "len %d < 1", len);
-  if (len > s->p.max_suffix - t)
-    MC_FAIL(MC_ERR_OOM, "suffix of %d + %d tokens exceeds max_suffix %d: page pool exhausted", t, len, s->p.max_suffix);
+  if (max_len < 1) MC_FAIL(MC_ERR_INVALID, "len %d < 1", max_len);
   const mc_config &c = s->m->cfg;
-  MC_TRY(check_tokens(c, suffix_tokens, (size_t)n_cands * len));
-  MC_HIP(hipSetDevice(s->m->device));
   const SessionLayout &L = s->lay;
   const int pg = s->p.page_tokens;
+  auto len_of = [&](int r) { return lens ? lens[r] : max_len; };
+  for (int r = 0; r < n_cands; ++r) {
+    if (len_of(r) < 1 || len_of(r) > max_len) MC_FAIL(MC_ERR_INVALID, "lens[%d] = %d outside [1, %d]", r, len_of(r), max_len);
+    if (len_of(r) > s->chunk_rows) MC_FAIL(MC_ERR_INVALID, "lens[%d] = %d exceeds the chunk of %d rows", r, len_of(r), s->chunk_rows);
+    MC_TRY(check_tokens(c, suffix_tokens + (size_t)r * max_len, len_of(r)));
+  }
   const int saved_n = s->n_cands;
   fix_cands(s, n_cands);
-  // slots below slot0 are held already; the others come off the queue
-  const int slot0 = (t + pg - 1) / pg, n_new = (t + len - 1) / pg - slot0 + 1, n_alive = (int)s->alive.size();
-  std::vector<int32_t> fresh;
-  if (int rc0 = stage_pages(s, slot0, n_new, fresh)) { unfix_cands(s, saved_n); return rc0; }
-  auto page_of = [&](int row, int slot) {
-    return slot < slot0 ? s->host_table[(size_t)s->alive[row] * L.pages_per_cand + slot]
-                        : fresh[(size_t)(slot - slot0) * n_alive + row];
-  };
+  for (int r = 0; r < n_cands; ++r)
+    if (len_of(r) > s->p.max_suffix - s->cand_len[s->alive[r]]) {
+      const int have = s->cand_len[s->alive[r]];
+      unfix_cands(s, saved_n);
+      MC_FAIL(MC_ERR_OOM, "suffix of %d + %d tokens exceeds max_suffix %d", have, len_of(r), s->p.max_suffix);
+    }
+  MC_HIP(hipSetDevice(s->m->device));
+  // New pages in the order a lock-step decode of these tokens would take them: token by token,
+  // candidates ascending, a candidate stepping aside once its tokens are used up.
+  std::vector<int32_t> idx, fresh;
+  {
+    std::vector<int32_t> next(n_cands);           // first slot candidate r does not hold yet
+    for (int r = 0; r < n_cands; ++r) next[r] = (s->cand_len[s->alive[r]] + pg - 1) / pg;
+    for (;;) {
+      // the earliest token index at which some candidate opens its next slot
+      int j = INT32_MAX;
+      for (int r = 0; r < n_cands; ++r) {
+        const int at = next[r] * pg - s->cand_len[s->alive[r]];
+        if (at < len_of(r)) j = std::min(j, at);
+      }
+      if (j == INT32_MAX) break;
+      for (int r = 0; r < n_cands; ++r)
+        if (next[r] * pg - s->cand_len[s->alive[r]] == j && j < len_of(r))
+          idx.push_back(s->alive[r] * L.pages_per_cand + next[r]++);
+    }
+  }
+  if (int rc0 = stage_pages(s, idx, fresh)) { unfix_cands(s, saved_n); return rc0; }
+  std::vector<int32_t> now(s->host_table);       // the table with the staged pages in place
+  for (size_t i = 0; i < idx.size(); ++i) now[idx[i]] = fresh[i];
   std::vector<int32_t> tok, pos, page, off, tab, last, items;
-  const int per_chunk = std::max(1, s->chunk_rows / len);          // whole candidates per chunk
-  for (int b0 = 0; b0 < n_cands; b0 += per_chunk) {
-    const int nc = std::min(per_chunk, n_cands - b0), rows = nc * len;
+  for (int b0 = 0; b0 < n_cands;) {
+    int b1 = b0, rows = 0;                         // whole candidates per chunk
+    while (b1 < n_cands && rows + len_of(b1) <= s->chunk_rows) rows += len_of(b1++);
+    const int nc = b1 - b0;
     tok.resize(rows); pos.resize(rows); page.resize(rows); off.resize(rows); tab.resize(rows);
     last.resize(nc);
     items.clear();
     int r = 0;
-    for (int b = b0; b < b0 + nc; ++b) {         // b: row among the candidates still decoding
-      const int cand = s->alive[b];
+    for (int b = b0; b < b1; ++b) {               // b: row among the candidates still decoding
+      const int cand = s->alive[b], t = s->cand_len[cand], len = len_of(b);
       for (int j = 0; j < len; j += 64) {
         items.push_back(r + j); items.push_back(std::min(64, len - j));
         items.push_back(s->prefix_len + t + j); items.push_back(cand);
       }
       for (int j = 0; j < len; ++j, ++r) {
-        tok[r] = suffix_tokens[(size_t)b * len + j];
+        tok[r] = suffix_tokens[(size_t)b * max_len + j];
         pos[r] = s->prefix_len + t + j;
-        page[r] = page_of(b, (t + j) / pg);
+        page[r] = now[(size_t)cand * L.pages_per_cand + (t + j) / pg];
         off[r] = (t + j) % pg;
         tab[r] = cand;
       }
@@ -1149,13 +1231,25 @@ extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, in
     if (rc == MC_OK) rc = run_layers(s, rows, PASS_SUFFIX, s->prefix_len, (int)items.size() / 4, &tail);
     if (rc == MC_OK) rc = lm_head(s, rows, tail, nc, true, s->ptr<float>(L.logits) + (size_t)b0 * c.vocab);
     if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
+    b0 = b1;
   }
-  commit_pages(s, slot0, fresh);
-  s->suffix_len = t + len;
+  commit_pages(s, idx, fresh);
+  for (int r = 0; r < n_cands; ++r) s->cand_len[s->alive[r]] += len_of(r);
+  refresh_lengths(s);
   s->logits_state = LOGITS_CANDS;
   s->logits_rows = n_cands;
   s->sampled_on_device = false;
   return MC_OK;
+}
+
+extern "C" int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len) {
+  return prefill_suffix_impl(s, suffix_tokens, nullptr, n_cands, len, "mc_prefill_suffix");
+}
+
+extern "C" int mc_prefill_suffix_ragged(mc_session *s, const int32_t *suffix_tokens, const int32_t *lens,
+                                        int32_t n_cands, int32_t max_len) {
+  if (!lens) MC_FAIL(MC_ERR_INVALID, "lens is NULL");
+  return prefill_suffix_impl(s, suffix_tokens, lens, n_cands, max_len, "mc_prefill_suffix_ragged");
 }
 
 // ---- inspection hooks -----------------------------------------------------------------
@@ -1172,11 +1266,12 @@ extern "C" int mc_debug_copy_logits(mc_session *s, float *out, int32_t n_rows) {
 
 extern "C" int mc_debug_page_table(mc_session *s, int32_t *out, int32_t *n_pages, int32_t max_pages) {
   if (!s || !out || !n_pages) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
-  const int held = (s->suffix_len + s->p.page_tokens - 1) / s->p.page_tokens;
-  if (max_pages < held) MC_FAIL(MC_ERR_INVALID, "max_pages %d < %d pages held", max_pages, held);
+  const int most = (s->suffix_len + s->p.page_tokens - 1) / s->p.page_tokens;
+  if (max_pages < most) MC_FAIL(MC_ERR_INVALID, "max_pages %d < %d pages held", max_pages, most);
   for (int b = 0; b < s->p.max_cands; ++b) {
     const bool holds = std::find(s->alive.begin(), s->alive.end(), b) != s->alive.end();
-    n_pages[b] = holds ? held : 0;
+    const int held = holds ? (s->cand_len[b] + s->p.page_tokens - 1) / s->p.page_tokens : 0;
+    n_pages[b] = held;
     for (int p = 0; p < max_pages; ++p)
       out[(size_t)b * max_pages + p] = (holds && p < held) ? s->host_table[(size_t)b * s->lay.pages_per_cand + p] : -1;
   }

@@ -674,6 +674,85 @@ def test_small_page_pool_reuses_the_pages_of_dropped_candidates(kw, dtype):
                             None if fl2 is None else fl2[-1:])
 
 
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4, lens=[5, 1, 9, 4, 8], steps=9, drop_at=4, chunk=0), "f32"),
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64, lens=[70, 3, 130, 63, 65], steps=66, drop_at=40, chunk=160), "bf16"),
+    (dict(L=2, d=256, Hq=8, Hkv=2, hd=128, F=512, V=1024, pg=64, lens=[1, 127, 64, 33], steps=4, drop_at=2, chunk=0), "bf16"),
+])
+def test_candidates_of_different_lengths(kw, dtype):
+    """The critic's inputs differ in length per candidate (Sec. 3.3: each candidate's own code
+    and execution feedback).  After one lock-step step every candidate gets a stretch of its own
+    length in one pass, then all decode on from their own positions; one is dropped on the way and
+    one is promoted with its own length.  Every logits row equals the oracle's for that
+    candidate's own sequence; the page table is the reference pool's."""
+    s = small_shape("rag", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 84)
+    pg, lens, steps = kw["pg"], kw["lens"], kw["steps"]
+    P, B, E = 50, len(lens), 6
+    N = 1 + max(lens) + steps + 2
+    prefix = synth.tokens(13, 1, (P,), s.vocab)
+    suffix = synth.tokens(13, 2, (B, N), s.vocab)
+    extra = synth.tokens(13, 3, (E,), s.vocab)
+    print("case: ragged candidates", kw, dtype, flush=True)
+    want = oracle_shared(s, w, prefix, suffix)[1]                         # [N, B, V]: row j of b = after j + 1 tokens
+    fl = oracle_shared(s, w, prefix, suffix, exact=False)[1] if dtype == "bf16" else None
+
+    def check(sess, alive, cur, what):
+        got = sess.logits(len(alive))
+        ref = np.stack([want[cur[b] - 1, b] for b in alive])
+        flo = None if fl is None else np.stack([fl[cur[b] - 1, b] for b in alive])[None]
+        assert_logits_close(got[None], ref[None], dtype, what, flo)
+        return got
+
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P + N + E, B, N, pg, kw["chunk"])
+    pool = opaging.PagePool(B, pg, range(sess.pool_pages()))
+    sess.prefill_shared(prefix)
+    sess.decode_step(suffix[:, 0]); pool.append(1)
+    cur = {b: 1 for b in range(B)}
+    alive = list(range(B))
+    bulk = np.zeros((B, max(lens)), np.int32)
+    for b in range(B):
+        bulk[b, :lens[b]] = suffix[b, 1:1 + lens[b]]
+    with pytest.raises(binding.McError):
+        sess.prefill_suffix_ragged(bulk, [0] + lens[1:])                  # a length of 0 is refused
+    sess.prefill_suffix_ragged(bulk, lens); pool.append_each(lens)
+    for b in range(B):
+        cur[b] += lens[b]
+    check(sess, alive, cur, "after the ragged stretch")
+    gone = 1
+    for t in range(steps):
+        if t == kw["drop_at"]:
+            sess.drop_candidates([gone]); pool.drop([gone]); alive.remove(gone)
+        sess.decode_step(np.array([suffix[b, cur[b]] for b in alive])); pool.append(1)
+        for b in alive:
+            cur[b] += 1
+        if dtype == "f32" or t in (0, kw["drop_at"], steps - 1) or t % 16 == 0:
+            check(sess, alive, cur, f"step {t}")
+    got = sess.logits(len(alive))
+    tab, n = sess.page_table()
+    for b in range(B):
+        held = -(-cur[b] // pg) if b in alive else 0
+        assert int(n[b]) == held and tab[b, :held].tolist() == pool.table(b), (b, n[b], held)
+    # a lock-step stretch after the ragged one keeps everybody at their own positions
+    more = np.stack([suffix[b, cur[b]:cur[b] + 2] for b in alive])
+    if all(cur[b] + 2 <= N for b in alive):
+        sess.prefill_suffix(more); pool.append(2)
+        for b in alive:
+            cur[b] += 2
+        got = check(sess, alive, cur, "lock-step stretch on ragged candidates")
+    # promote a candidate that is not the longest: its own length moves into the prefix
+    keep = min(alive, key=lambda b: cur[b])
+    sess.promote_candidate(keep)
+    np.testing.assert_array_equal(sess.logits(1)[0], got[alive.index(keep)])
+    sess.extend_shared(extra)
+    grown = np.concatenate([prefix, suffix[keep, :cur[keep]], extra])
+    nxt = synth.tokens(13, 4, (2, 3), s.vocab)
+    pl = sess.logits(1)[0]
+    steps2 = _decode_all(sess, nxt)
+    check_against_oracle(s, w, grown, nxt, pl, steps2)
+
+
 def test_drop_candidates_with_tokens_pending_on_the_device(tiny):
     wl, w = tiny
     s = wl.shape

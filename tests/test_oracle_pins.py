@@ -310,6 +310,28 @@ def test_page_pool_with_drops_worked_example():
     assert pool.free == [0, 4, 3, 7]
 
 
+def test_page_pool_candidates_of_different_lengths_worked_example():
+    # worked by hand: pages of 2 tokens, pool 20, 21, ...; three candidates get 3, 1 and 4 tokens.
+    # index 0: all three open their first page (20, 21, 22).  index 1: nobody is at a boundary.
+    # index 2: candidate 0 (length 2) takes 23, candidate 1 has no token left, candidate 2 takes 24.
+    pool = paging.PagePool(3, 2, range(20, 40))
+    pool.append_each([3, 1, 4])
+    assert [pool.table(b) for b in range(3)] == [[20, 23], [21], [22, 24]]
+    assert pool.lens == {0: 3, 1: 1, 2: 4} and pool.length == 4
+    pool.append(1)                 # lengths 3, 1, 4: only candidate 2 is at a boundary
+    assert [pool.table(b) for b in range(3)] == [[20, 23], [21], [22, 24, 25]]
+    pool.append(1)                 # lengths 4, 2, 5: candidates 0 and 1 are
+    assert [pool.table(b) for b in range(3)] == [[20, 23, 26], [21, 27], [22, 24, 25]]
+    # a call the queue cannot serve as a whole changes nothing
+    pool = paging.PagePool(2, 2, [7, 8, 9])
+    pool.append_each([2, 1])
+    with pytest.raises(MemoryError):
+        pool.append_each([1, 3])   # candidate 0 needs one page, candidate 1 needs one: only one is left
+    assert pool.free == [9] and pool.lens == {0: 2, 1: 1}
+    pool.append_each([1, 1])       # candidate 0 opens its second page, candidate 1 fills its first
+    assert pool.table(0) == [7, 9] and pool.table(1) == [8] and pool.free == []
+
+
 # ---------------------------------------------------------------- bf16 activation mode
 def test_round_bf16_against_closed_forms_and_library():
     import torch
