@@ -477,7 +477,12 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
   auto splits_for = [&](int N, int K) {
     int sp = linear_auto_splits(dt, rows, N, K, tl);
     sp = std::min(sp, kMaxSplits);
-    while (sp > 1 && (size_t)sp * rows * N > L.part_floats) --sp;
+    // fewer splits if the partial sums would not fit; on the tiled few-row path a split count
+    // has to divide K / 256
+    auto fits = [&](int n) {
+      return (size_t)n * rows * N <= L.part_floats && !(tl && rows <= 64 && (K / 64) % (4 * n));
+    };
+    while (sp > 1 && !fits(sp)) --sp;
     return sp;
   };
   int pending = 0;   // partial sums waiting in `part` to be added to x
