@@ -68,7 +68,7 @@ def attention_bytes(s, n_cands, prefix_len, suffix_len):
     return prefix_len * kv_tok + n_cands * suffix_len * kv_tok + 2 * n_cands * s.n_q_heads * s.head_dim * 2
 
 
-def cpu_baseline(wl, weights, n_layers_sample=2, n_cands_sample=4):
+def cpu_baseline(wl, weights, n_layers_sample=4, n_cands_sample=16):
     """The oracle, as it stands, on a bounded sample of the same workload: one decode step at
     suffix length 1 for `n_cands_sample` of the B candidates through `n_layers_sample` layers
     (random bf16 prefix keys/values of the real shape) plus the final norm and LM head; times are
@@ -79,6 +79,7 @@ def cpu_baseline(wl, weights, n_layers_sample=2, n_cands_sample=4):
     cfg = otf.Config(s.n_layers, s.d_model, s.n_q_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab,
                      s.rope_base, s.rms_eps, "bf16")
     B, P = wl.n_cands, wl.prefix_len
+    n_cands_sample, n_layers_sample = min(n_cands_sample, B), min(n_layers_sample, s.n_layers)
     layers = [{k: synth.bf16_bits_to_f32(v) for k, v in weights["layers"][l].items()} for l in range(n_layers_sample)]
     head = {"final_norm": synth.bf16_bits_to_f32(weights["final_norm"]),
             "lm_head": synth.bf16_bits_to_f32(weights["lm_head"])}
