@@ -132,3 +132,15 @@ def test_decode_attention_plan_covers_every_block_and_fits_its_workspace(lib):
         assert p["n_parts"] == (p["splits"] if P else 0) + (p["suffix_splits"] if t else 0) <= 1024 or P > 100000
         ws = lib.mc_op_attention_decode_ws(B, Hq, Hkv, hd, P, t, 64)
         assert p["n_parts"] * B * Hq * (hd + 2) * 4 <= ws, (B, Hq, Hkv, hd, P, t, S, p, ws)
+
+
+def test_bench_refuses_more_than_one_gpu_and_bad_step_counts():
+    """bench.py is a one-GPU program: --gpus N > 1 ends with a message and a non-zero status before
+    anything touches a device; so do step counts outside the workload."""
+    import subprocess
+    import sys
+    bench = os.path.join(ROOT, "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+    r = subprocess.run([sys.executable, bench, "--gpus", "0"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0 and r.stdout.strip() == ""
