@@ -753,6 +753,40 @@ def test_candidates_of_different_lengths(kw, dtype):
     check_against_oracle(s, w, grown, nxt, pl, steps2)
 
 
+def test_ragged_candidates_sample_on_the_device_and_score(tiny):
+    """Candidates of different lengths: tokens drawn on the device feed the next step exactly as
+    tokens passed from the host do, and scoring leaves the ragged decode state alone."""
+    wl, w = tiny
+    s = wl.shape
+    prefix = synth.prefix_tokens(wl, 40)
+    model = binding.Model(s, w)
+    B = 4
+    lens = [3, 1, 6, 4]
+    bulk = synth.tokens(14, 1, (B, max(lens)), s.vocab)
+    us = synth.step_uniforms(wl, B, 3)
+    a = binding.Session(model, 40, B, 16, wl.page_tokens)
+    b = binding.Session(model, 40, B, 16, wl.page_tokens)
+    for sess in (a, b):
+        sess.prefill_shared(prefix)
+        sess.prefill_suffix_ragged(bulk, lens)
+    for t in range(3):
+        toks = a.sample(B, wl.temperature, wl.top_k, us[t])
+        b.sample(B, wl.temperature, wl.top_k, us[t], want_tokens=False)     # ids stay on the device
+        if t == 1:                                                          # scoring in between changes nothing
+            lp, sc, rk = b.score_candidates(synth.tokens(14, 2, (B, 5), s.vocab), np.array([5, 2, 4, 1], np.int32),
+                                            np.array([3, 7, 11], np.int32), np.array([0.0, 1.0, 2.0], np.float32), 1.0)
+            assert np.all(np.isfinite(lp)) and sorted(rk.tolist()) == list(range(B))
+            b.decode_step(toks)                                             # scoring consumed the pending logits' sample
+        else:
+            b.decode_step(None, B)
+        a.decode_step(toks)
+        np.testing.assert_array_equal(a.logits(B), b.logits(B))
+    ta, na = a.page_table()
+    tb, nb = b.page_table()
+    np.testing.assert_array_equal(ta, tb)
+    assert [int(x) for x in na[:B]] == [-(-(l + 3) // wl.page_tokens) for l in lens]
+
+
 def test_drop_candidates_with_tokens_pending_on_the_device(tiny):
     wl, w = tiny
     s = wl.shape
