@@ -138,10 +138,10 @@ int mc_promote_candidate(mc_session *s, int32_t cand);
 /* 1c. Several new tokens per candidate in one pass (the critic of Sec. 3.3 reads, per candidate,
  *    the candidate and its execution feedback after the shared trajectory, then writes its
  *    critique token by token).  suffix_tokens: host [n_cands][len]; every candidate gets len
- *    tokens at suffix positions suffix_len .. suffix_len + len - 1, attending causally to the
+ *    tokens after the suffix tokens it already holds, attending causally to the
  *    shared prefix and to its own suffix; their K/V go to the candidate's pages and stay, the
  *    logits of each candidate's last new token are left for mc_sample / mc_decode_step to go on
- *    from.  Candidates stay in lock-step (one common len).  Errors: MC_ERR_STATE without a
+ *    from.  One common len for all candidates here.  Errors: MC_ERR_STATE without a
  *    prefix, MC_ERR_OOM beyond max_suffix, MC_ERR_INVALID for a changed n_cands.  Asynchronous. */
 int mc_prefill_suffix(mc_session *s, const int32_t *suffix_tokens, int32_t n_cands, int32_t len);
 /*    The same with a length of its own for every candidate (the candidates and their feedback
