@@ -365,6 +365,23 @@ int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_cands, int32_t
                            int32_t table_stride, const int32_t *row_len, int32_t prefix_splits,
                            void *workspace, size_t workspace_bytes, void *out, int32_t out_tiled);
 
+/* mc_op_attention_decode for callers that cannot allocate device memory or bring a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and arguments, with the partial states kept in a buffer of MC_STATIC_SCRATCH_BYTES that
+ * the library holds in every GPU's memory from load to process exit.  The call allocates nothing.
+ * MC_ERR_UNSUPPORTED when mc_op_attention_decode_ws(...) for these sizes exceeds that buffer (the
+ * 1B and 8B decode shapes fit, a 16k-token prefix with 64 candidates does not).  All calls on one
+ * GPU share the buffer: calls that overlap on one GPU (two streams, two threads) race; calls on
+ * one stream are ordered and safe.  Nothing in the buffer has to survive between calls. */
+#define MC_STATIC_SCRATCH_BYTES (32u << 20)
+int mc_op_attention_decode_static(void *stream, int32_t dtype, int32_t n_cands, int32_t n_q_heads,
+                                  int32_t n_kv_heads, int32_t head_dim, int32_t page_tokens,
+                                  int32_t prefix_len, int32_t suffix_len, const void *q,
+                                  const void *k_prefix, const void *v_prefix, const void *k_suffix,
+                                  const void *v_suffix, const int32_t *page_table,
+                                  int32_t table_stride, const int32_t *row_len, int32_t prefix_splits,
+                                  void *out, int32_t out_tiled);
+
 /* Host-only: the work-item plan mc_op_attention_decode would launch for these sizes on the bf16
  * MFMA path (MC_ERR_UNSUPPORTED for shapes that path does not cover).  out8 (host): prefix items
  * incl. padding ids, suffix items, prefix key splits, 32-key blocks per prefix split, suffix key

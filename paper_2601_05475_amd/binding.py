@@ -100,6 +100,7 @@ SIGNATURES = {
     "mc_op_rope_kv_write": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mc_op_attention_decode_ws": (_sz, [_i32] * 7),
     "mc_op_attention_decode": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _sz, _vp, _i32]),
+    "mc_op_attention_decode_static": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp, _i32]),
     "mc_op_attention_decode_plan": (C.c_int, [_i32] * 8 + [_vp]),
     "mc_op_read_probe": (C.c_int, [_vp, _vp, _sz, _vp]),
     "mc_op_mfma_probe": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
@@ -556,21 +557,31 @@ def op_rope_kv_write(qkv, row_pos, row_page, row_off, n_q_heads, n_kv_heads, hea
 
 def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, prefix_len,
                         suffix_len, page_tokens, prefix_splits: int = 0, out_tiled: bool = False,
-                        row_len=None):
+                        row_len=None, out=None, static_scratch: bool = False):
     """q: [B, Hq, hd]; pools: [n_pages, Hkv, pg * hd] in the page layout (kv_pages_pack);
     page_table: int32 [B, stride]; row_len: optional int32 [B] device tensor of per-candidate
-    suffix lengths.  Returns out [B, Hq, hd] (or the flat tiled [B, Hq*hd])."""
+    suffix lengths.  Returns out [B, Hq, hd] (or the flat tiled [B, Hq*hd]); `out` may be passed
+    in.  static_scratch: call mc_op_attention_decode_static (the library's own scratch buffer; with
+    `out` given the call allocates nothing)."""
     import torch
     lib = load_library()
     B, Hq, hd = q.shape
     Hkv = (k_prefix if k_prefix is not None else k_suffix).shape[1]
+    if out is None:
+        if out_tiled:
+            out = torch.zeros(lib.mc_op_tiled_bytes(B, Hq * hd) // 2, dtype=q.dtype, device=q.device)
+        else:
+            out = torch.empty_like(q)
+    p = lambda t: None if t is None else t.data_ptr()
+    if static_scratch:
+        _check(lib.mc_op_attention_decode_static(
+            _stream(), _code_of(q), B, Hq, Hkv, hd, page_tokens, prefix_len, suffix_len, q.data_ptr(),
+            p(k_prefix), p(v_prefix), p(k_suffix), p(v_suffix), p(page_table),
+            0 if page_table is None else page_table.shape[1], p(row_len), prefix_splits,
+            out.data_ptr(), int(out_tiled)))
+        return out
     ws_bytes = lib.mc_op_attention_decode_ws(B, Hq, Hkv, hd, prefix_len, suffix_len, page_tokens)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=q.device)
-    if out_tiled:
-        out = torch.zeros(lib.mc_op_tiled_bytes(B, Hq * hd) // 2, dtype=q.dtype, device=q.device)
-    else:
-        out = torch.empty_like(q)
-    p = lambda t: None if t is None else t.data_ptr()
     _check(lib.mc_op_attention_decode(
         _stream(), _code_of(q), B, Hq, Hkv, hd, page_tokens, prefix_len, suffix_len, q.data_ptr(),
         p(k_prefix), p(v_prefix), p(k_suffix), p(v_suffix), p(page_table),

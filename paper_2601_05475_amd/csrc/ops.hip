@@ -3,6 +3,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "kernels_mfma.h"
@@ -268,6 +269,56 @@ extern "C" int mc_op_attention_decode(void *stream, int32_t dtype, int32_t n_can
   a.prefix_splits = prefix_splits; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
   a.out = out; a.out_tiled = out_tiled;
   return launch_attention_decode((hipStream_t)stream, dtype, a);
+}
+
+// ---- decode attention for callers that cannot allocate ---------------------------------------
+// The partial states of the split-K kernels live in a file-scope device array instead of a
+// caller's workspace.  The array's name is only a host-side stand-in: its device address is looked
+// up once per device (every GPU holds its own copy) and that pointer is what host code uses.
+static __device__ __align__(256) unsigned char scratch[MC_STATIC_SCRATCH_BYTES];
+
+namespace mc {
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+static int static_scratch(void **out) {
+  int dev = -1;
+  MC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) MC_FAIL(MC_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    MC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) MC_FAIL(MC_ERR_DEVICE, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MC_OK;
+}
+}  // namespace mc
+
+extern "C" int mc_op_attention_decode_static(void *stream, int32_t dtype, int32_t n_cands,
+                                             int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                             int32_t page_tokens, int32_t prefix_len, int32_t suffix_len,
+                                             const void *q, const void *k_prefix, const void *v_prefix,
+                                             const void *k_suffix, const void *v_suffix,
+                                             const int32_t *page_table, int32_t table_stride,
+                                             const int32_t *row_len, int32_t prefix_splits, void *out,
+                                             int32_t out_tiled) {
+  const size_t need = mc_op_attention_decode_ws(n_cands, n_q_heads, n_kv_heads, head_dim, prefix_len,
+                                                suffix_len, page_tokens);
+  if (need == 0) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (need > (size_t)MC_STATIC_SCRATCH_BYTES)
+    MC_FAIL(MC_ERR_UNSUPPORTED, "decode attention needs %zu bytes of scratch, the static buffer holds %zu: use "
+            "mc_op_attention_decode with a workspace", need, (size_t)MC_STATIC_SCRATCH_BYTES);
+  void *ws = nullptr;
+  MC_TRY(static_scratch(&ws));
+  return mc_op_attention_decode(stream, dtype, n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens,
+                                prefix_len, suffix_len, q, k_prefix, v_prefix, k_suffix, v_suffix, page_table,
+                                table_stride, row_len, prefix_splits, ws, (size_t)MC_STATIC_SCRATCH_BYTES, out,
+                                out_tiled);
 }
 
 extern "C" int mc_op_attention_decode_plan(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
