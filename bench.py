@@ -46,11 +46,12 @@ TRAFFIC_ATTN = {"fetch_kib": 27088.4, "merge_fetch_kib": 2614.0, "write_kib": 46
                 "sha256": "9c2a5acbf21e4424cdbe545b0624d41f8f94760575e01330a96f3738dea3a666"}
 
 
-def measured_attention_traffic_bytes(workload):
-    """HBM bytes of one layer-step's decode attention (both kernels) at the workload's average
-    suffix length; None off the headline workload or once the kernel source has changed."""
+def measured_attention_traffic_bytes(workload, mean_suffix_len):
+    """HBM bytes of one layer-step's decode attention (both kernels) from the counter runs; None
+    off the headline workload, once the kernel source has changed since the counters were taken,
+    or when this run's mean suffix length is not the one they were taken at."""
     import hashlib
-    if workload != "8b":
+    if workload != "8b" or abs(mean_suffix_len - TRAFFIC_ATTN["suffix_len"]) > 2.0:
         return None
     t = TRAFFIC_ATTN
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), t["source"])
@@ -92,6 +93,34 @@ def attention_bytes(s, n_cands, prefix_len, suffix_len):
     suffix K and V once, q in and o out (bf16)."""
     kv_tok = 2 * s.n_kv_heads * s.head_dim * 2
     return prefix_len * kv_tok + n_cands * suffix_len * kv_tok + 2 * n_cands * s.n_q_heads * s.head_dim * 2
+
+
+def step_bytes(s, n_cands, prefix_len, mean_suffix_len):
+    """Algorithmic HBM bytes of one decode step: every weight matrix once (bf16), the shared
+    prefix's keys and values once per layer, every candidate's suffix keys and values once."""
+    qd, kd = s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim
+    weights = 2 * (s.n_layers * ((qd + 2 * kd) * s.d_model + s.d_model * qd + 3 * s.d_ffn * s.d_model) + s.vocab * s.d_model)
+    kv = s.n_layers * (prefix_len + n_cands * mean_suffix_len) * 2 * kd * 2
+    return weights + kv
+
+
+def matmul_yardstick_tflops(torch):
+    """An independent yardstick for the matrix-core figures: the vendor library's bf16 GEMM behind
+    torch.matmul on the gate/up shape of one 8B-shape scoring chunk (8192 x 28672 x 4096), N(0, 1)
+    operands.  Reported only; the library never calls it."""
+    M, N, K = 8192, 28672, 4096
+    a = torch.randn(M, K, device="cuda").to(torch.bfloat16)
+    b = torch.randn(N, K, device="cuda").to(torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a, b.t())
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        torch.matmul(a, b.t())
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * M * N * K * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
 
 def cpu_baseline(wl, weights, n_layers_sample=4, n_cands_sample=16):
@@ -283,7 +312,10 @@ def bench_rerank(args, torch, binding, synth):
                        "achieved_tflops": (layer_flops + attn_flops) * s.n_layers / (elapsed / K) / 1e12,
                        "attention_ms_per_pass": ms_at, "attention_tflops": attn_flops * s.n_layers / (ms_at * 1e-3) / 1e12},
         "prefill_s": t_prefill, "setup_s": {"generate_weights": t_gen},
-        "measured_copy_gbs": measured_copy_gbs(torch),
+        "yardsticks": {"hbm_copy_gbs": measured_copy_gbs(torch), "mfma_matmul_tflops": matmul_yardstick_tflops(torch),
+                       "mfma_probe_tflops": mfma_meas,
+                       "note": "torch.matmul bf16 8192x28672x4096 (the vendor library's GEMM on the gate/up shape of "
+                               "one chunk) and the library's own MFMA-only probe: reported only"},
     }
     if args.layers:
         out["invalid"] = "layer count overridden"
@@ -303,10 +335,10 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (diagnosis only; marks the line invalid)")
     ap.add_argument("--chunk-rows", type=int, default=0, help="rows per prefill / scoring chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--suffix-start", type=int, default=0,
-                    help="decode workloads: write this many tokens per candidate in one pass before the steps, "
-                         "so a short counter run sees the kernels at a representative suffix length "
-                         "(marks the line invalid)")
+    ap.add_argument("--suffix-start", type=int, default=None,
+                    help="decode workloads: write this many tokens per candidate in one untimed pass before the "
+                         "steps (default: (workload steps - timed steps) / 2, which centres the timed steps on "
+                         "the workload's mean suffix length)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (a kernel of known traffic "
                          "that hardware-counter readings are scaled by)")
@@ -322,29 +354,35 @@ def main():
     if args.workload == "8b-rerank":
         return bench_rerank(args, torch, binding, synth)
     wl = synth.WORKLOADS[args.workload]
+    N = wl.n_steps
     if args.steps is None:
-        args.steps = wl.n_steps
+        args.steps = N
     if args.warmup is None:
         args.warmup = 8
     s = wl.shape if not args.layers else wl.shape.with_layers(args.layers)
     B, P = wl.n_cands, wl.prefix_len
     K, W = args.steps, args.warmup
-    S0 = args.suffix_start
-    if S0 < 0 or K < 1 or K + S0 > wl.n_steps or W < 0 or W + S0 > wl.n_steps:
-        print(f"bench.py: steps (+ suffix start) must be in [1, {wl.n_steps}] and warmup in [0, {wl.n_steps}]", file=sys.stderr)
+    # Fewer timed steps than the workload has: they sit in the middle of the workload, at suffix
+    # lengths S0 + 1 .. S0 + K, so that their mean length (and hence the per-step cost, which is
+    # linear in the suffix length) is the whole workload's.  The S0 tokens before them are written
+    # in one untimed pass.
+    S0 = args.suffix_start if args.suffix_start is not None else (N - K) // 2
+    if K < 1 or K > N or W < 0 or S0 < 0 or K + S0 > N or W + S0 > N:
+        print(f"bench.py: steps (+ suffix start) must be in [1, {N}] and warmup in [0, {N}]", file=sys.stderr)
         sys.exit(2)
+    mean_len = S0 + (K + 1) / 2.0
 
     t0 = time.perf_counter()
     weights = synth.make_weights(s, wl.seed_weights)
     t_gen = time.perf_counter() - t0
     t0 = time.perf_counter()
     model = binding.Model(s, weights)
-    sess = binding.Session(model, P, B, wl.n_steps, wl.page_tokens, chunk_rows=args.chunk_rows or 4096)
+    sess = binding.Session(model, P, B, N, wl.page_tokens, chunk_rows=args.chunk_rows or 4096)
     torch.cuda.synchronize()
     t_upload = time.perf_counter() - t0
 
     prefix = synth.prefix_tokens(wl)
-    us = synth.step_uniforms(wl, B, wl.n_steps)
+    us = synth.step_uniforms(wl, B, N)
     t0 = time.perf_counter()
     sess.prefill_shared(prefix)
     sess.sync()
@@ -358,7 +396,7 @@ def main():
 
     def run_steps(n):
         for t in range(n):
-            sess.sample(B, wl.temperature, wl.top_k, us[t], want_tokens=False)
+            sess.sample(B, wl.temperature, wl.top_k, us[S0 + t], want_tokens=False)
             sess.decode_step(None, B)
 
     start_candidates()
@@ -373,9 +411,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # timed region; a sample of the gate/up launches is bracketed by HIP events on the session stream
-    # (the events of a bracket keep the stream idle for about 12 us around the launch, so only
-    # about 256 launches of the run are bracketed: every 64th at the default sizes)
+    # timed region; a sample of the gate/up launches carries HIP events of its own (attached to the
+    # launch: begin and end of that dispatch on the session stream), about 256 launches of the run
     stride = max(1, (s.n_layers * K) // 256)
     sess.profile_begin("linear_gate_up", stride)
     torch.cuda.synchronize()
@@ -385,7 +422,7 @@ def main():
     elapsed = time.perf_counter() - t0
     n_gu, ms_gu = sess.profile_end()
 
-    # second pass (untimed): the decode-attention kernel, averaged over the same K steps
+    # second pass (untimed): the decode-attention kernels over the same K steps
     sess.reset_candidates()
     start_candidates()
     sess.profile_begin("attn_decode", stride)
@@ -395,11 +432,11 @@ def main():
         if t + 1 in marks:                       # wall time of this one step, bracketed by syncs
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-        sess.sample(B, wl.temperature, wl.top_k, us[t], want_tokens=False)
+        sess.sample(B, wl.temperature, wl.top_k, us[S0 + t], want_tokens=False)
         sess.decode_step(None, B)
         if t + 1 in marks:
             torch.cuda.synchronize()
-            step_ms[str(t + 1)] = (time.perf_counter() - t1) * 1e3
+            step_ms[str(S0 + t + 1)] = (time.perf_counter() - t1) * 1e3
     n_at, ms_at = sess.profile_end()
     at_bytes = float(np.mean([attention_bytes(s, B, P, S0 + t + 1) for t in range(K)]))
 
@@ -408,33 +445,43 @@ def main():
     at_us = ms_at * 1e3 / max(n_at, 1)
     gu_gbs = gate_up_bytes(s, B) / gu_us / 1e3
     at_gbs = at_bytes / at_us / 1e3
+    ms_step = elapsed / K * 1e3
+    sb = step_bytes(s, B, P, mean_len)
     out = {
         "metric": f"generated tokens/s at B candidates ({args.workload.upper()}-shape decode); % HBM roofline attn",
         "value": B * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}-shape decode: {s.n_layers} layers, d {s.d_model}, "
                                f"{s.n_q_heads}/{s.n_kv_heads} heads of {s.head_dim}, FFN {s.d_ffn}, vocab {s.vocab}; "
-                               f"B={B} candidates, shared prefix {P}, suffix 0..{K}, T={wl.temperature}, top-k {wl.top_k}",
-                   "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens},
+                               f"B={B} candidates, shared prefix {P}, {N}-step workload, timed steps at suffix lengths "
+                               f"{S0 + 1}..{S0 + K} (mean {mean_len:g}; the workload's mean is {(N + 1) / 2:g}), "
+                               f"T={wl.temperature}, top-k {wl.top_k}",
+                   "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens, "suffix_start": S0},
         "roofline": {"bound": "hbm", "kernel": "skinny_linear_kernel (gate/up + SwiGLU)",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
                      "peak_measured": read_gbs, "frac_of_measured": gu_gbs / read_gbs,
                      "traffic": measured_traffic_bytes(args.workload), "algorithmic_bytes": gate_up_bytes(s, B),
-                     "launches_timed": n_gu, "avg_us": gu_us},
-        "roofline_attn": {"bound": "hbm", "kernel": "decode attention (all launches of one layer-step)",
-                          "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
-                          "traffic": measured_attention_traffic_bytes(args.workload) if not S0 else None,
-                          "traffic_at_suffix_len": TRAFFIC_ATTN["suffix_len"],
-                          "algorithmic_bytes": at_bytes, "launches_timed": n_at, "avg_us": at_us},
+                     "launches_timed": n_gu, "avg_us": gu_us,
+                     # decode attention, the kernel the metric's second half names: both launches of one layer-step
+                     "attn": {"bound": "hbm", "kernel": "decode_attention_kernel + decode_attention_merge_kernel",
+                              "achieved": at_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": at_gbs / HBM_PEAK_GBS,
+                              "traffic": measured_attention_traffic_bytes(args.workload, mean_len),
+                              "algorithmic_bytes": at_bytes, "mean_suffix_len": mean_len,
+                              "launches_timed": n_at, "avg_us": at_us},
+                     # the whole step against the HBM roofline: algorithmic bytes of one step / its time / peak
+                     "step": {"algorithmic_bytes": sb, "achieved": sb / ms_step / 1e6, "unit": "GB/s",
+                              "frac": sb / ms_step / 1e6 / HBM_PEAK_GBS}},
+        "step_frac": sb / ms_step / 1e6 / HBM_PEAK_GBS,
         "step_ms_at_suffix_len": step_ms,
         "prefill_s": t_prefill, "setup_s": {"generate_weights": t_gen, "upload_and_pack": t_upload},
-        "measured_copy_gbs": measured_copy_gbs(torch),
+        "yardsticks": {"hbm_copy_gbs": measured_copy_gbs(torch), "hbm_read_probe_gbs": read_gbs,
+                       "mfma_matmul_tflops": matmul_yardstick_tflops(torch),
+                       "note": "torch device copy (read + write) and torch.matmul bf16 8192x28672x4096: "
+                               "independent of the library, reported only"},
     }
     if args.layers:
         out["invalid"] = "layer count overridden"
-    if S0:
-        out["invalid"] = "steps start at suffix length %d" % S0
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, weights)
     print(json.dumps(out))

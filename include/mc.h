@@ -302,7 +302,7 @@ int32_t mc_op_linear_splits(int32_t dtype, int32_t M, int32_t N, int32_t K, int3
 
 /* bf16 tiled operands, many rows: x[m][n] += sum_k a[m][k] w[n][k] in the epilogue of the
  * 256-row-tile matrix-core GEMM (the residual update of the O and down projections in prefill and
- * scoring, section 3.1: the policy's forward pass).  x: fp32 [M][N] row-major, device, updated in
+ * scoring).  x: fp32 [M][N] row-major, device, updated in
  * place; every element is read and written by exactly one lane, so the result does not depend on
  * scheduling.  MC_ERR_UNSUPPORTED unless N % 128 == 0, K % 256 == 0 and M > 64 (fewer rows keep
  * mc_op_linear + mc_op_add_rmsnorm). */

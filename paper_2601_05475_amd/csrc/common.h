@@ -55,6 +55,10 @@ void set_error(const char *fmt, ...);
     if (s__ != MC_OK) return s__;     \
   } while (0)
 
+// Raise a kernel's limit of dynamic LDS to `bytes`, once per (kernel, device); safe to call from
+// several threads and with several devices in one process.
+int raise_dynamic_lds_limit(const void *kernel, int bytes);
+
 // ---- geometry of one KV page ---------------------------------------------------------
 // A page holds page_tokens keys of every KV head; head kvh owns elements
 // [kvh * page_tokens * hd, (kvh + 1) * page_tokens * hd) of the K page and of the V page.

@@ -15,7 +15,8 @@
 //     8 XCDs, so they share one L2 and the keys come from HBM once.
 //   suffix item (candidate b, kv head, key split): columns are b's G query heads.
 // Every item leaves an un-normalised partial (max m, sum l, weighted values o) per query head;
-// a second small kernel merges the partials of each (candidate, head) and writes bf16.
+// a second small kernel merges the partials of each (candidate, head) and writes bf16.  (An item
+// that holds the only partial of its rows normalises and writes them itself.)
 //
 // Scores are computed transposed, S^T = K Q^T, so that a lane owns ONE query column: the softmax
 // reductions are 16 in-lane steps plus one cross-half shuffle, the running rescale of O^T is a
@@ -61,7 +62,7 @@ struct AttnItems {
 template <int HD>
 __global__ __launch_bounds__(256, 2)
 void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__ part_o,
-                             float *__restrict__ part_ml) {
+                             float *__restrict__ part_ml, int n_parts) {
   constexpr int NF = HD / 16;                // 1 KB fragments per 32-key block, K and V alike
   constexpr int BLK = 32 * HD;               // elements of one block
   constexpr int SOLD = HD + 4;               // row stride of the merge buffer (floats)
@@ -148,25 +149,33 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   // pieces of the window's first block (never used): with no branch around the loads the
   // compiler's load counters stay exact, so waiting for the keys of a block leaves its values,
   // issued later, in flight, and the other way round.
-  auto block_base = [&](int w0, int j, int wn, uint32_t &voff) __attribute__((always_inline)) -> size_t {
+  // A lane all of whose keys lie past the end of the sequence (only in the sequence's last block)
+  // reads the fragment's first 16 bytes instead of its own: finite values of valid keys, which
+  // meet a masked score (keys) or a zero probability (values), and no memory traffic of their own.
+  auto block_base = [&](int w0, int j, int wn, uint32_t &voff, int &n_valid) __attribute__((always_inline)) -> size_t {
     const bool real = j < wn;
     const int jj = real ? j : 0;
     const int g = blk_begin + (w0 + jj) * 4;
     const int page = __builtin_amdgcn_readlane(my_pid, jj);
     voff = real ? lane * 16u : 0u;
+    n_valid = len - 32 * g;
     return ((size_t)page * page_stride + head_off + (size_t)(g & 1) * BLK) * sizeof(bf16_t);
   };
   auto issue_k = [&](int w0, int j, int wn) __attribute__((always_inline)) {
     uint32_t voff;
-    const char *kb = (const char *)kpool + block_base(w0, j, wn, voff);
+    int n_valid;
+    const char *kb = (const char *)kpool + block_base(w0, j, wn, voff, n_valid);
+    if (col >= n_valid) voff = 0u;                               // lane (col, h) holds key col
 #pragma unroll
     for (int c = 0; c < NF; ++c) kf[c] = *(const v4u *)(kb + voff + 1024 * c);
   };
   auto issue_v = [&](int w0, int j, int wn) __attribute__((always_inline)) {
     uint32_t voff;
-    const char *vb = (const char *)vpool + block_base(w0, j, wn, voff);
+    int n_valid;
+    const char *vb = (const char *)vpool + block_base(w0, j, wn, voff, n_valid);
 #pragma unroll
-    for (int c = 0; c < NF; ++c) vf[c] = *(const v4u *)(vb + voff + 1024 * c);
+    for (int c = 0; c < NF; ++c)                                 // fragment c: keys 16 (c & 1) + 4 h + {0..3, 8..11}
+      vf[c] = *(const v4u *)(vb + ((16 * (c & 1) + 4 * h >= n_valid) ? 0u : voff) + 1024 * c);
   };
 
   // Windows of 64 blocks (the page ids one wave register holds).  Inside a window: scores of
@@ -277,10 +286,9 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     }
     const int rc = col0 + c;
     const int bc = (b_item >= 0) ? b_item : rc / G;
-    const size_t row = ((size_t)part * B + bc) * Hq + kvh * G + rc % G;
-    *(float4 *)(part_o + row * HD + d) = v;
-    if (d == 0) {
-      float mg = sm[c], lg = 0.f;
+    const int hq = kvh * G + rc % G;
+    float mg = sm[c], lg = 0.f;
+    if (d == 0 || n_parts == 1) {
 #pragma unroll
       for (int w = 1; w < 4; ++w) mg = fmaxf(mg, sm[w * 32 + c]);
 #pragma unroll
@@ -288,6 +296,19 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
         const float mw = sm[w * 32 + c];
         lg += (mw == -INFINITY) ? 0.f : sm[128 + w * 32 + c] * __builtin_amdgcn_exp2f(mw - mg);
       }
+    }
+    if (n_parts == 1) {
+      // the only partial state of its (candidate, head): normalise and store the output here
+      const size_t at = a.out_tiled ? tiled_offset(bc, hq * HD + d, Hq * HD) : ((size_t)bc * Hq + hq) * HD + d;
+      uint2 pk;
+      pk.x = pack2_bf16(v.x / lg, v.y / lg);
+      pk.y = pack2_bf16(v.z / lg, v.w / lg);
+      *(uint2 *)((bf16_t *)a.out + at) = pk;
+      continue;
+    }
+    const size_t row = ((size_t)part * B + bc) * Hq + hq;
+    *(float4 *)(part_o + row * HD + d) = v;
+    if (d == 0) {
       part_ml[row * 2] = mg;
       part_ml[row * 2 + 1] = lg;
     }
@@ -404,20 +425,17 @@ static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, co
   const int max_cols = (a.prefix_len > 0) ? std::min(32, a.n_cands * G) : G;
   const size_t lds = std::max((size_t)4 * (HD / 16) * 1024, (size_t)(256 + 4 * max_cols * (HD + 4)) * sizeof(float));
   const AttnItems &it = it_in;
-  static bool attr_set = false;          // per template instance
-  if (!attr_set) {
-    MC_HIP(hipFuncSetAttribute((const void *)decode_attention_kernel<HD>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024));
-    attr_set = true;
-  }
-  // events offered by a profiling scope: begin of the first kernel, end of the second
+  MC_TRY(raise_dynamic_lds_limit((const void *)decode_attention_kernel<HD>, 160 * 1024 - 1024));
+  // events offered by a profiling scope: begin of the first kernel, end of the last
   const LaunchEvents ev = take_launch_events();
-  if (ev.start)
+  hipEvent_t stop1 = n_parts == 1 ? ev.stop : nullptr;
+  if (ev.start || stop1)
     hipExtLaunchKernelGGL(decode_attention_kernel<HD>, dim3(it.n_prefix_items + it.n_suffix_items), dim3(256),
-                          (uint32_t)lds, st, ev.start, nullptr, 0, a, it, part_o, part_ml);
+                          (uint32_t)lds, st, ev.start, stop1, 0, a, it, part_o, part_ml, n_parts);
   else
-    decode_attention_kernel<HD><<<it.n_prefix_items + it.n_suffix_items, 256, lds, st>>>(a, it, part_o, part_ml);
+    decode_attention_kernel<HD><<<it.n_prefix_items + it.n_suffix_items, 256, lds, st>>>(a, it, part_o, part_ml, n_parts);
   MC_HIP(hipGetLastError());
+  if (n_parts == 1) return MC_OK;          // every item finished its own outputs
   if (ev.stop)
     hipExtLaunchKernelGGL(decode_attention_merge_kernel<HD>, dim3((unsigned)rows), dim3(HD), 0, st, nullptr, ev.stop, 0,
                           n_parts, a.n_cands, a.n_q_heads, (const float *)part_o, (const float *)part_ml,

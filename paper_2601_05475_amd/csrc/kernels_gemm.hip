@@ -329,11 +329,8 @@ int launch_gemm256(hipStream_t st, int M, int N, int K, const void *a, const voi
   const size_t lds = std::max<size_t>(3 * 4 * 4096, mode == GEMM_ROPE ? 4 * 32 * kParkStride * sizeof(float) : 0);
   const void *kernels[4] = {(const void *)gemm256_kernel<GEMM_STORE>, (const void *)gemm256_kernel<GEMM_SWIGLU>,
                             (const void *)gemm256_kernel<GEMM_ROPE>, (const void *)gemm256_kernel<GEMM_ACCUM>};
-  static bool attr_set[4] = {false, false, false, false};
-  if (!attr_set[mode]) {
-    MC_HIP(hipFuncSetAttribute(kernels[mode], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set[mode] = true;
-  }
+  // the largest request of this mode (the rotation epilogue's parking areas included)
+  MC_TRY(raise_dynamic_lds_limit(kernels[mode], (int)lds));
   const RopeOut none{};
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
   bf16_t *OT = (bf16_t *)out_t;

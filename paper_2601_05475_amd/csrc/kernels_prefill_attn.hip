@@ -245,12 +245,7 @@ static int launch_prefill_t(hipStream_t st, const PrefillAttnArgs &a) {
   using TL = PTile<HD>;
   const int G = a.n_q_heads / a.n_kv_heads, HG = (G + 3) / 4;
   const size_t lds = TL::LDS_BYTES + kPrefillMaxPids * sizeof(int);
-  static bool attr_set = false;
-  if (!attr_set) {
-    MC_HIP(hipFuncSetAttribute((const void *)prefill_attention_kernel<HD>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024));
-    attr_set = true;
-  }
+  MC_TRY(raise_dynamic_lds_limit((const void *)prefill_attention_kernel<HD>, 160 * 1024 - 1024));
   const unsigned grid = (unsigned)a.n_items * a.n_kv_heads * HG;
   prefill_attention_kernel<HD><<<grid, 512, lds, st>>>(a);
   MC_HIP(hipGetLastError());

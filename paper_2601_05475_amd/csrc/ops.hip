@@ -4,6 +4,8 @@
 
 #include <algorithm>
 #include <mutex>
+#include <set>
+#include <utility>
 
 #include "common.h"
 #include "kernels_mfma.h"
@@ -26,6 +28,18 @@ LaunchEvents take_launch_events() {
   const LaunchEvents e = tl_launch_events;
   tl_launch_events = LaunchEvents{};
   return e;
+}
+
+int raise_dynamic_lds_limit(const void *kernel, int bytes) {
+  static std::mutex mu;
+  static std::set<std::pair<const void *, int>> done;
+  int dev = 0;
+  MC_HIP(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(mu);
+  if (done.count({kernel, dev})) return MC_OK;
+  MC_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  done.insert({kernel, dev});
+  return MC_OK;
 }
 
 bool tiled_shapes_ok(int M, int N, int K) {

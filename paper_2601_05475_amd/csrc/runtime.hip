@@ -86,8 +86,6 @@ struct ModelLayout {
 // bf16 models whose every matrix fits the tiled MFMA kernels run entirely on them
 static int model_is_tiled(const mc_config &c) {
   const int qd = c.n_q_heads * c.head_dim, kd = c.n_kv_heads * c.head_dim;
-  const char *force = getenv("MC_FORCE_GENERIC");      // diagnosis: run bf16 on the ALU kernels
-  if (force && force[0] == '1') return 0;
   return c.dtype == MC_BF16 && kd % 32 == 0 && tiled_shapes_ok(0, qd + 2 * kd, c.d_model) &&
          tiled_shapes_ok(0, c.d_model, qd) && tiled_shapes_ok(0, c.d_ffn, c.d_model) &&
          tiled_shapes_ok(0, c.d_model, c.d_ffn) && tiled_shapes_ok(0, c.vocab, c.d_model);
@@ -951,10 +949,17 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   for (int b : s->alive)
     if (s->cand_len[b] % pg == 0) idx.push_back(b * L.pages_per_cand + s->cand_len[b] / pg);
   if (int rc0 = stage_pages(s, idx, fresh)) { unfix_cands(s, saved_n); return rc0; }
-  if (tokens) MC_TRY(upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4));
-  else MC_HIP(hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4, hipMemcpyDeviceToDevice, s->stream));
+  // from here on every failure leaves through `fail`, which forgets candidates that this call started
+  auto fail = [&](int code) { unfix_cands(s, saved_n); return code; };
+  if (tokens) {
+    if (int rc1 = upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4)) return fail(rc1);
+  } else if (hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4,
+                            hipMemcpyDeviceToDevice, s->stream) != hipSuccess) {
+    set_error("copy of the sampled tokens failed");
+    return fail(MC_ERR_DEVICE);
+  }
   if (s->ragged) {
-    MC_TRY(upload(s, s->ptr<void>(L.cand_len), s->cand_len.data(), (size_t)s->n_cands * 4));
+    if (int rc1 = upload(s, s->ptr<void>(L.cand_len), s->cand_len.data(), (size_t)s->n_cands * 4)) return fail(rc1);
     decode_rows_ragged_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
         n_cands, s->prefix_len, pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
         s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.cand_len), s->ptr<int32_t>(L.row_pos),
@@ -965,11 +970,14 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
         s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
         s->ptr<int32_t>(L.row_tab));
   }
-  MC_HIP(hipGetLastError());
+  if (hipGetLastError() != hipSuccess) {
+    set_error("launch of the decode-row kernel failed");
+    return fail(MC_ERR_DEVICE);
+  }
   int tail = 0;
   int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, 0, &tail);
   if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
-  if (rc != MC_OK) { unfix_cands(s, saved_n); return rc; }
+  if (rc != MC_OK) return fail(rc);
   commit_pages(s, idx, fresh);
   for (int b : s->alive) s->cand_len[b]++;
   s->suffix_len = t + 1;
@@ -1081,8 +1089,7 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
     MC_TRY(upload(s, s->ptr<void>(L.row_off), off.data(), (size_t)rows * 4));
     MC_TRY(upload(s, s->ptr<void>(L.row_tab), tab.data(), (size_t)rows * 4));
     MC_TRY(upload(s, s->ptr<void>(L.last_idx), last.data(), (size_t)nc * 4));
-    MC_HIP(hipMemcpyAsync(s->ptr<void>(L.score_table), table.data(), table.size() * 4, hipMemcpyHostToDevice, s->stream));
-    MC_HIP(hipStreamSynchronize(s->stream));   // `table` is pageable host memory reused below
+    MC_TRY(upload_long(s, s->ptr<void>(L.score_table), table.data(), table.size() * 4));   // through the pinned ring: no host stall
     int tail = 0;
     MC_TRY(upload(s, s->ptr<void>(L.items), items.data(), items.size() * 4));
     MC_TRY(run_layers(s, rows, PASS_SCORE, s->prefix_len, (int)items.size() / 4, &tail));

@@ -25,3 +25,29 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """bf16 parity comparisons of this run as a table (gpurun_out/parity_bf16.md): per comparison
+    the device's and the noise floor's distance from the exact oracle, the bound that applied and
+    the statistics with power."""
+    try:
+        import gpu_common
+    except Exception:
+        return
+    recs = gpu_common.PARITY_RECORDS
+    if not recs:
+        return
+    out_dir = os.path.join(ROOT, "gpurun_out")
+    try:
+        os.makedirs(out_dir, exist_ok=True)
+        with open(os.path.join(out_dir, "parity_bf16.md"), "w") as f:
+            f.write("| comparison | rows x cols | max-abs | floor max-abs | rel L2 | floor rel L2 | bound used | "
+                    "RMS / floor RMS | worst row | bias / RMS | frac > 2e-2 | floor frac > 2e-2 | floor frac > 1.6e-2 |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|---|---|---|---|\n")
+            for r in recs:
+                f.write(f"| {r['what']} | {r['rows']} x {r['cols']} | {r['err']:.2e} | {r['floor_err']:.2e} | {r['rel']:.2e} | "
+                        f"{r['floor_rel']:.2e} | {r['which']} | {r['rms_ratio']:.2f} | {r['rms_ratio_row']:.2f} | "
+                        f"{r['bias']:.3f} | {r['frac']:.1e} | {r['floor_frac']:.1e} | {r['floor_frac_scaled']:.1e} |\n")
+    except OSError:
+        pass

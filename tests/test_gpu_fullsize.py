@@ -1,0 +1,237 @@
+"""The bf16 workloads at their full sizes against the oracle, end to end through the C ABI.
+
+The float64 oracle needs minutes to hours per workload at these sizes, so it is not run here:
+tests/golden/make_fullsize_golden.py (which calls only oracle/ and the seeded input generator)
+ran it once and stored, for a seeded subset of (candidate, step) pairs, the exact logits and the
+oracle's own bf16-activation logits at a sample of vocabulary columns, plus the exact top-64,
+the log-sum-exp and the reward-token log-probs over the whole vocabulary.  Every workload comes
+twice: at full depth (the 32B one with a shortened prefix and the reranking one with 4 of its 64
+suffixes, see the script), and as a two-layer twin with prefix length, candidates, steps, page
+size and vocabulary all at full size.
+
+Each test builds the model from the same seeds, runs the workload teacher-forced in the launch
+configuration the benchmark uses (session sized for the whole workload, 64-token pages, automatic
+key splits, default chunking) and compares the stored rows: logits to the bar of
+gpu_common.assert_logits_close (stated tolerance or 1.5 x the bf16 noise floor, RMS ratio, bias,
+tail fraction), the largest logits and the log-sum-exp over the whole vocabulary, the sampler and
+the ranker bit-exactly on the device's own logits, and the page table against the reference
+allocator.
+"""
+import gc
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import paging as opaging
+from oracle import sampling as osamp
+from paper_2601_05475_amd import binding, synth
+
+from gpu_common import FLOOR_SLACK, TOL, assert_logits_close, check_sampler_on_logits
+
+pytestmark = pytest.mark.gpu
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def load_golden(variant):
+    path = os.path.join(GOLDEN, f"fullsize_{variant}.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} has not been generated (python tests/golden/make_fullsize_golden.py {variant})")
+    z = np.load(path, allow_pickle=False)
+    g = {k: z[k] for k in z.files if k != "meta"}
+    g["meta"] = json.loads(str(z["meta"]))
+    g["rows"] = [tuple(r) for r in g["meta"]["rows"]]
+    return g
+
+
+def free_gpu(*objs):
+    import torch
+    for o in objs:
+        o.close()
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def compare_rows(g, got_rows, what):
+    """got_rows: {(cand, step): fp32 logits [V]} for every stored row.  Logits at the sampled
+    columns to the parity bar; the exact top entries and the log-sum-exp over the whole vocabulary."""
+    rows = g["rows"]
+    got = np.stack([got_rows[r] for r in rows])
+    cols = g["cols"]
+    assert_logits_close(got[:, cols], g["exact"], "bf16", what, floor=g["floor"])
+    # whole-vocabulary figures: the bound is the one that applied above (stated, or 1.5 x floor)
+    bound = max(TOL["bf16"][0], FLOOR_SLACK * float(g["floor_err"].max()))
+    top_ids, top_vals = g["top_ids"], g["top_vals"]
+    at_top = np.take_along_axis(got, top_ids.astype(np.int64), axis=1)
+    assert np.abs(at_top - top_vals).max() <= bound, (what, np.abs(at_top - top_vals).max(), bound)
+    m = got.max(axis=1, keepdims=True).astype(np.float64)
+    lse = (m + np.log(np.sum(np.exp(got.astype(np.float64) - m), axis=1, keepdims=True)))[:, 0]
+    assert np.abs(lse - g["lse"]).max() <= bound, (what, np.abs(lse - g["lse"]).max())
+    # arg max: equal wherever the oracle's top-2 gap is clear of the bound; the device's top 50
+    # lie among the oracle's top 64 apart from entries within the bound of the cut
+    excused = 0
+    for i in range(len(rows)):
+        if top_vals[i, 0] - top_vals[i, 1] > 2 * bound:
+            assert int(np.argmax(got[i])) == int(top_ids[i, 0]), (what, rows[i])
+        else:
+            excused += 1
+        mine = np.argsort(-got[i], kind="stable")[:50]
+        outside = [v for v in mine if v not in set(top_ids[i].tolist())]
+        for v in outside:
+            assert got[i, v] <= top_vals[i, 49] + 2 * bound, (what, rows[i], v)
+    print(f"{what}: arg max compared on {len(rows) - excused} of {len(rows)} rows", flush=True)
+
+
+def run_decode_workload(variant, s, wl, g, what, chunk_rows=4096):
+    """Prefill the golden's prefix, decode teacher-forced up to the last stored step in a session
+    sized for the whole workload, collect the stored rows; sampler and page table on the way."""
+    P = g["meta"]["prefix_len"]
+    rows = g["rows"]
+    last = max(t for _, t in rows)
+    steps_wanted = sorted({t for b, t in rows if b >= 0})
+    B = wl.n_cands
+    print(f"case: full size {variant}: {s.n_layers} layers, prefix {P}, {B} candidates, {last} steps", flush=True)
+    w = synth.make_weights(s, wl.seed_weights)
+    model = binding.Model(s, w)
+    del w
+    gc.collect()
+    sess = binding.Session(model, wl.prefix_len, B, wl.n_steps, wl.page_tokens, chunk_rows=chunk_rows)
+    prefix = synth.prefix_tokens(wl)[:P]
+    suffix = synth.suffix_tokens(wl)
+    us = synth.step_uniforms(wl)
+    sess.prefill_shared(prefix)
+    got = {(-1, 0): sess.logits(1)[0]}
+    exact_picks = 0
+    for t in range(1, last + 1):
+        sess.decode_step(suffix[:, t - 1])
+        if t in steps_wanted:
+            lg = sess.logits(B)
+            for b, tt in rows:
+                if tt == t and b >= 0:
+                    got[(b, t)] = lg[b].copy()
+            # the sampler on these very logits: ids and top-k lists bit-exact
+            toks, topk = sess.sample(B, wl.temperature, wl.top_k, us[t % us.shape[0]], want_topk=True)
+            for b in range(0, B, max(1, B // 8)):
+                exact_picks += check_sampler_on_logits(lg[b], wl.temperature, wl.top_k, us[t % us.shape[0]][b], toks[b], topk[b])
+    tab, n = sess.page_table()
+    ref = opaging.page_tables(B, last, wl.page_tokens, range(sess.pool_pages()))
+    assert list(n) == [ref.shape[1]] * B
+    np.testing.assert_array_equal(tab[:, :ref.shape[1]], ref)
+    free_gpu(sess, model)
+    assert exact_picks >= 1
+    compare_rows(g, got, what)
+
+
+@pytest.mark.timeout(900)
+def test_1b_workload_full_depth():
+    """Workload 2 as specified: 16 layers, 2048-token prefix, 16 candidates, 256 steps; all
+    candidates at steps 1, 2, 64, 65 (a page boundary) and three of them at steps 255, 256."""
+    g = load_golden("1b")
+    wl = synth.WORKLOADS["1b"]
+    run_decode_workload("1b", wl.shape, wl, g, "1b full depth")
+
+
+@pytest.mark.timeout(900)
+def test_8b_workload_full_depth():
+    """Workload 3 (the headline) as specified: 32 layers, vocabulary 128256, 4096-token prefix, 32
+    candidates; the prefix logits, all candidates at steps 1 and 2, four of them at steps 64, 65,
+    511 and 512."""
+    g = load_golden("8b")
+    wl = synth.WORKLOADS["8b"]
+    run_decode_workload("8b", wl.shape, wl, g, "8b full depth")
+
+
+@pytest.mark.timeout(900)
+def test_8b_workload_two_layer_twin():
+    """Two layers, everything else of workload 3 at full size: every candidate at steps 1, 2, 63,
+    64, 65, 128, 129, 256, 257, 511, 512, so every page boundary kind, split plan and merge path
+    of the real shapes meets the oracle."""
+    g = load_golden("8b-twin")
+    wl = synth.WORKLOADS["8b"]
+    run_decode_workload("8b-twin", wl.shape.with_layers(2), wl, g, "8b two-layer twin")
+
+
+def run_rerank_workload(variant, s, wl, g, what):
+    P = g["meta"]["prefix_len"]
+    B, Ls = wl.n_cands, wl.n_steps
+    print(f"case: full size {variant}: {s.n_layers} layers, prefix {P}, {B} suffixes of {Ls}", flush=True)
+    w = synth.make_weights(s, wl.seed_weights)
+    model = binding.Model(s, w)
+    del w
+    gc.collect()
+    sess = binding.Session(model, wl.prefix_len, B, Ls, wl.page_tokens, chunk_rows=8192)
+    sess.prefill_shared(synth.prefix_tokens(wl)[:P])
+    ids = np.asarray(g["meta"]["reward_ids"], np.int32)
+    assert list(ids) == list(synth.reward_token_ids(wl, 8))
+    vals = np.arange(8, dtype=np.float32)
+    lp, sc, rk = sess.score_candidates(synth.suffix_tokens(wl), np.full(B, Ls, np.int32), ids, vals, 1.0)
+    lg = sess.logits(B)
+    free_gpu(sess, model)
+    # the device's read-out from its own logits: log-probs, scores and ranks follow the oracle's rules
+    want_lp = np.stack([osamp.reward_logprobs(lg[b], ids) for b in range(B)])
+    np.testing.assert_allclose(lp, want_lp, rtol=0, atol=1e-4)
+    want_sc = np.array([osamp.expected_value(want_lp[b], vals, 1.0) for b in range(B)])
+    np.testing.assert_allclose(sc, want_sc, rtol=0, atol=1e-4)
+    assert list(rk) == list(osamp.rank(sc))
+    rows = g["rows"]
+    got = {(b, t): lg[b] for b, t in rows if b >= 0}
+    stored = [i for i, (b, _) in enumerate(rows) if b >= 0]
+    sub = {k: (v[stored] if isinstance(v, np.ndarray) and v.shape[:1] == (len(rows),) else v) for k, v in g.items()}
+    sub["rows"] = [rows[i] for i in stored]
+    compare_rows(sub, got, what)
+    # log-probs against the oracle's: a logit error and a log-sum-exp error each within the bound
+    bound = max(TOL["bf16"][0], FLOOR_SLACK * float(sub["floor_err"].max()))
+    cands = [b for b, _ in sub["rows"]]
+    assert np.abs(lp[cands] - sub["lp_exact"]).max() <= 2 * bound
+    # ranking among the stored candidates: pairs whose oracle scores differ by more than the noise
+    # (the oracle's own bf16-mode scores move by that much) are in the oracle's order
+    sc_exact = np.array([osamp.expected_value(sub["lp_exact"][i], vals, 1.0) for i in range(len(cands))])
+    sc_floor = np.array([osamp.expected_value(sub["lp_floor"][i], vals, 1.0) for i in range(len(cands))])
+    noise = FLOOR_SLACK * np.abs(sc_floor - sc_exact).max() + 1e-6
+    checked = 0
+    for i in range(len(cands)):
+        for j in range(len(cands)):
+            if sc_exact[i] - sc_exact[j] > 2 * noise:
+                assert sc[cands[i]] > sc[cands[j]], (what, cands[i], cands[j])
+                checked += 1
+    print(f"{what}: {checked} candidate pairs ranked as the oracle ranks them (score noise {noise:.2e})", flush=True)
+
+
+@pytest.mark.timeout(900)
+def test_8b_rerank_workload_full_depth():
+    """Workload 4 as specified: all 64 suffixes of 1024 tokens are scored on the 4096-token
+    prefix at 32 layers; four of them are compared with the oracle (final-position logits, reward
+    log-probs, relative order)."""
+    g = load_golden("8b-rerank")
+    wl = synth.WORKLOADS["8b-rerank"]
+    run_rerank_workload("8b-rerank", wl.shape, wl, g, "8b rerank full depth")
+
+
+@pytest.mark.timeout(900)
+def test_8b_rerank_workload_two_layer_twin():
+    """Two layers, everything else of workload 4 at full size: all 64 candidates compared."""
+    g = load_golden("8b-rerank-twin")
+    wl = synth.WORKLOADS["8b-rerank"]
+    run_rerank_workload("8b-rerank-twin", wl.shape.with_layers(2), wl, g, "8b rerank two-layer twin")
+
+
+@pytest.mark.timeout(1500)
+def test_32b_workload_full_depth_on_a_shortened_prefix():
+    """Workload 5 at full depth (64 layers, vocabulary 152064, 64 candidates, session sized for the
+    16384-token prefix and 1024 steps) on the first 2048 prefix tokens, the length the oracle
+    could be run at: eight candidates at steps 1 and 2, two across a page boundary."""
+    g = load_golden("32b")
+    wl = synth.WORKLOADS["32b"]
+    run_decode_workload("32b", wl.shape, wl, g, "32b full depth, prefix 2048")
+
+
+@pytest.mark.timeout(1500)
+def test_32b_workload_two_layer_twin():
+    """Two layers, everything else of workload 5 at full size: 16384-token prefix, 64 candidates,
+    1024 steps; every candidate at steps 1, 2, 63, 64, 65 and eight of them at steps 128, 129, 512,
+    513, 1023, 1024."""
+    g = load_golden("32b-twin")
+    wl = synth.WORKLOADS["32b"]
+    run_decode_workload("32b-twin", wl.shape.with_layers(2), wl, g, "32b two-layer twin")

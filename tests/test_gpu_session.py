@@ -557,6 +557,7 @@ def test_drop_candidates_midway(kw, dtype):
     alive = list(range(B))
     drops = {3: [1, 4], 66: [0]}
     tol = 0 if dtype == "f32" else 3e-2
+    rows_of = {b: [] for b in range(B)}                              # every logits row a candidate produced
     for t in range(N):
         if t in drops:
             before = sess.logits(len(alive))
@@ -570,10 +571,19 @@ def test_drop_candidates_midway(kw, dtype):
                 sess.drop_candidates(drops[t][:1])                  # already gone
         sess.decode_step(suffix[alive, t])
         got = sess.logits(len(alive))
+        for i, b in enumerate(alive):
+            rows_of[b].append(got[i])
+        # an extra: the undisturbed run (its key splits are planned for six candidates, so bf16 rounds differently)
         np.testing.assert_allclose(got, full[t][alive], rtol=0, atol=tol * np.abs(full[t]).max() + 0.0)
-    want_pl, want = oracle_shared(s, w, prefix, suffix[alive][:, :N])
-    fl = oracle_shared(s, w, prefix, suffix[alive], exact=False)[1] if dtype == "bf16" else None
-    assert_logits_close(got[None], want[-1:], dtype, "survivors, last step", None if fl is None else fl[-1:])
+    # the main evidence: every row of every candidate, up to its drop, against the oracle on that
+    # candidate's own sequence
+    want_pl, want = oracle_shared(s, w, prefix, suffix)              # [N, B, V]
+    fl = oracle_shared(s, w, prefix, suffix, exact=False)[1] if dtype == "bf16" else None
+    for b in range(B):
+        n_b = len(rows_of[b])
+        assert n_b == (N if b in alive else min(t for t, ds in drops.items() if b in ds))
+        assert_logits_close(np.stack(rows_of[b]), want[:n_b, b], dtype, f"dropping candidates, candidate {b}: {n_b} steps",
+                            None if fl is None else fl[:n_b, b])
     tab, n = sess.page_table()
     held = -(-N // kw["pg"])
     assert [int(x) for x in n[:B]] == [held if b in alive else 0 for b in range(B)]
@@ -811,3 +821,4 @@ def test_drop_candidates_with_tokens_pending_on_the_device(tiny):
     np.testing.assert_array_equal(a.logits(2), b.logits(2))
     with pytest.raises(binding.McError):
         a.drop_candidates([1, 3])                                     # one candidate must stay
+

@@ -364,3 +364,88 @@ def test_bf16_activation_mode_rounds_only_activation_tensors():
     cfg = oracle_config(s)
     plast, shared = otf.forward_shared(cfg, w, toks[:7], toks[7:][None])
     np.testing.assert_allclose(shared[0], rounded[7:], rtol=0, atol=1e-12)
+
+
+def test_layerwise_driver_of_the_fullsize_golden_script_equals_forward_shared():
+    """tests/golden/make_fullsize_golden.py walks the layers in the outer loop and the sequences in
+    the inner one (weights are generated once per layer).  Same arithmetic as forward_shared: the
+    logits agree to float64 rounding (the matrix library sums a one-row product in another order
+    than a many-row one), in both activation precisions, for suffixes of different lengths."""
+    import importlib.util
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "make_fullsize_golden.py")
+    spec = importlib.util.spec_from_file_location("make_fullsize_golden", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    s = small_shape(L=3, d=32, Hq=4, Hkv=2, hd=8, F=40, V=64, dtype="bf16")
+    seed = 21
+    w = synth.weights_as_f32(synth.make_weights(s, seed))
+    prefix = synth.tokens(5, 1, (9,), s.vocab)
+    suf = synth.tokens(5, 2, (3, 5), s.vocab)
+    suffixes = {0: suf[0, :5], 2: suf[2, :2]}
+    cfgs = [oracle_config(s, exact=True), oracle_config(s, exact=False)]
+    res = mod.forward_many(cfgs, s, seed, prefix, suffixes, log=lambda *a, **k: None)
+    for cfg, (plast, xs, head) in zip(cfgs, res):
+        want_p, want = otf.forward_shared(cfg, w, prefix, suf)
+        np.testing.assert_allclose(plast, want_p, rtol=0, atol=1e-13)
+        for b, toks in suffixes.items():
+            got = otf.lm_logits(cfg, head, xs[b])
+            np.testing.assert_allclose(got, want[b, :len(toks)], rtol=0, atol=1e-13)
+
+
+def test_attention_parity_bound_sees_a_lost_key_block():
+    """The bound the GPU attention tests use (relative L2 per row and head) against planted
+    mistakes, on the oracle itself at the headline shape's key count (4096 prefix + 512 suffix keys
+    of dimension 128, N(0, 1)): an output computed without one 32-key block, without one 64-key
+    page, or with one split's partial state weighted twice fails it; bf16 rounding of the output
+    passes.  (The absolute bound of 1.5e-2 used before passed all four.)"""
+    from gpu_common import ATT_REL, rel_l2
+    rng = np.random.default_rng(5)
+    S, hd = 4608, 128
+    q, k, v = rng.standard_normal(hd), rng.standard_normal((S, hd)), rng.standard_normal((S, hd))
+    want = otf.attention_one(q, k, v)
+    keep = np.ones(S, bool); keep[2048:2080] = False
+    lost_block = otf.attention_one(q, k[keep], v[keep])
+    keep = np.ones(S, bool); keep[4544:4608] = False
+    lost_page = otf.attention_one(q, k[keep], v[keep])
+    twice = otf.attention_one(q, np.concatenate([k, k[512:1024]]), np.concatenate([v, v[512:1024]]))
+    rounded = otf.round_bf16(want)
+    assert rel_l2(rounded, want) < ATT_REL["bf16"] / 3
+    for wrong in (lost_block, lost_page, twice):
+        assert rel_l2(wrong, want) > 2 * ATT_REL["bf16"]
+        assert np.abs(wrong - want).max() < 1.5e-2          # what the old bound could not see
+
+
+def test_logits_parity_statistics_see_mistakes_the_widened_bound_accepts(monkeypatch):
+    """gpu_common.assert_logits_close on planted mistakes, CPU only.  The 'device' is the oracle's
+    bf16-tensor mode with a fault planted in the oracle: (a) bf16 conversion by truncation instead
+    of round-to-nearest, (b) a constant 1e-3 added to every logit.  Both stay inside the max-abs /
+    relative bounds (stated tolerance or 1.5 x noise floor); the first is caught by the RMS ratio,
+    the second by the mean signed error.  The unfaulted mode passes against itself."""
+    import gpu_common
+    s = small_shape(L=6, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, dtype="bf16")
+    w = synth.weights_as_f32(synth.make_weights(s, 31))
+    prefix, suf = synth.tokens(8, 1, (40,), s.vocab), synth.tokens(8, 2, (2, 3), s.vocab)
+    exact = otf.forward_shared(oracle_config(s, exact=True), w, prefix, suf)[1]
+    floor = otf.forward_shared(oracle_config(s, exact=False), w, prefix, suf)[1]
+    gpu_common.assert_logits_close(floor, exact, "bf16", "floor against itself", floor=floor)
+
+    def truncate(x):
+        f = np.ascontiguousarray(x, np.float32)
+        return (f.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32).reshape(f.shape).astype(np.float64)
+
+    real_lm_logits = otf.lm_logits
+    faults = {"truncation": lambda m: m.setattr(otf, "round_bf16", truncate),
+              "logit offset": lambda m: m.setattr(otf, "lm_logits", lambda cfg, w_, x: real_lm_logits(cfg, w_, x) + 1e-3)}
+    for name, plant in faults.items():
+        with monkeypatch.context() as m:
+            plant(m)
+            wrong = otf.forward_shared(oracle_config(s, exact=False), w, prefix, suf)[1]
+        err, rel = gpu_common._errs(wrong, exact)
+        ferr, frel = gpu_common._errs(floor, exact)
+        a_bound = max(gpu_common.TOL["bf16"][0], gpu_common.FLOOR_SLACK * ferr)
+        r_bound = max(gpu_common.TOL["bf16"][1], gpu_common.FLOOR_SLACK * frel)
+        assert err <= a_bound and rel <= r_bound, (name, err, a_bound, rel, r_bound)     # the old rule accepts it
+        with pytest.raises(AssertionError):
+            gpu_common.assert_logits_close(wrong, exact, "bf16", name, floor=floor)
+    del gpu_common.PARITY_RECORDS[:]
