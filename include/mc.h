@@ -424,6 +424,24 @@ int mc_op_sample(void *stream, int32_t n_cands, int32_t vocab, const float *logi
                  size_t row_stride, float temperature, int32_t top_k, const float *uniforms,
                  int32_t *out_tokens, int32_t *out_topk);
 
+/* The LM head's share of sampling (bf16 tiled operands; at most 32 rows, N % 128 == 0, N >= 65536,
+ * K % 256 == 0, else MC_ERR_UNSUPPORTED): logits[m][n] = sum_k a[m][k] w[n][k] (fp32 [M][N]) and,
+ * beside them, for every row and every group of 64 consecutive ids the four largest (logit, id)
+ * pairs under (logit descending, id ascending): top_lists[(m * N / 64 + g) * 4 + t] = {float bits,
+ * int32 id}, mc_op_top_list_bytes(M, N) bytes.  mc_op_sample_lists is mc_op_sample reading those
+ * lists (1 / 16 of a row) instead of the rows wherever that yields the rule's result: for
+ * top_k <= 64 it selects from the lists and checks that no group's fourth entry reaches the k-th
+ * selected value after the division by the temperature (an unlisted id of that group could then
+ * belong to the top k or tie with its last member); a row that fails the check is selected from
+ * the whole row, so ids and top-k lists are the rule's in every case.  row_stride 0 = every
+ * candidate reads row 0 of both. */
+size_t mc_op_top_list_bytes(int32_t rows, int32_t N);
+int mc_op_lm_head(void *stream, int32_t M, int32_t N, int32_t K, const void *a, const void *w,
+                  float *logits, void *top_lists);
+int mc_op_sample_lists(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
+                       size_t row_stride, const void *top_lists, float temperature, int32_t top_k,
+                       const float *uniforms, int32_t *out_tokens, int32_t *out_topk);
+
 /* Reward log-probs, expected-value scores and ranking from fp32 logits [n_cands][vocab].
  * reward_ids, reward_values: device [n_reward].  Outputs: device. */
 int mc_op_reward_score(void *stream, int32_t n_cands, int32_t vocab, const float *logits,

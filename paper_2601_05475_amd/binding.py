@@ -105,6 +105,9 @@ SIGNATURES = {
     "mc_op_read_probe": (C.c_int, [_vp, _vp, _sz, _vp]),
     "mc_op_mfma_probe": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
     "mc_op_attention_prefill": (C.c_int, [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32]),
+    "mc_op_top_list_bytes": (_sz, [_i32, _i32]),
+    "mc_op_lm_head": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp]),
+    "mc_op_sample_lists": (C.c_int, [_vp, _i32, _i32, _vp, _sz, _vp, _f32, _i32, _vp, _vp, _vp]),
     "mc_op_sample": (C.c_int, [_vp, _i32, _i32, _vp, _sz, _f32, _i32, _vp, _vp, _vp]),
     "mc_op_reward_score": (C.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _vp]),
 }
@@ -650,6 +653,37 @@ def op_sample(logits, temperature: float, top_k: int, uniforms, shared_row: bool
     _check(load_library().mc_op_sample(_stream(), B, V, logits.data_ptr(), 0 if shared_row else V,
                                        temperature, top_k, uniforms.data_ptr(), toks.data_ptr(),
                                        None if topk is None else topk.data_ptr()))
+    return (toks, topk) if want_topk else toks
+
+
+def op_lm_head(a, w, tiled_shape):
+    """a, w: flat tiled bf16 buffers.  Returns (logits fp32 [M, N], top lists int32 [M, N / 64, 4, 2]:
+    {float bits, id} of the four largest logits of every group of 64 ids)."""
+    import torch
+    M, N, K = tiled_shape
+    lib = load_library()
+    logits = torch.empty((M, N), dtype=torch.float32, device=a.device)
+    nbytes = lib.mc_op_top_list_bytes(M, N)
+    if nbytes == 0:
+        raise McError(-1, "N must be a positive multiple of 64")
+    lists = torch.zeros((M, N // 64, 4, 2), dtype=torch.int32, device=a.device)
+    _check(lib.mc_op_lm_head(_stream(), M, N, K, a.data_ptr(), w.data_ptr(), logits.data_ptr(), lists.data_ptr()))
+    return logits, lists
+
+
+def op_sample_lists(logits, lists, temperature: float, top_k: int, uniforms, shared_row: bool = False,
+                    want_topk: bool = False):
+    """op_sample reading the LM head's per-group top lists (see op_lm_head) where they suffice."""
+    import torch
+    B = uniforms.shape[0]
+    V = logits.shape[1]
+    greedy = temperature <= 0 or top_k == 1
+    k = 1 if greedy else (V if (top_k <= 0 or top_k >= V) else top_k)
+    toks = torch.empty(B, dtype=torch.int32, device=logits.device)
+    topk = torch.empty((B, k), dtype=torch.int32, device=logits.device) if want_topk else None
+    _check(load_library().mc_op_sample_lists(_stream(), B, V, logits.data_ptr(), 0 if shared_row else V,
+                                             lists.data_ptr(), temperature, top_k, uniforms.data_ptr(),
+                                             toks.data_ptr(), None if topk is None else topk.data_ptr()))
     return (toks, topk) if want_topk else toks
 
 

@@ -143,8 +143,11 @@ int launch_add_rmsnorm(hipStream_t st, int dtype, int rows, int d, float *x, con
 int launch_gather_rows(hipStream_t st, int rows, int d, const float *x, const int32_t *idx,
                        float *out);
 // tiled != 0: a, w (and the SwiGLU output) are in the tiled layout; bf16 only
+// top_out != nullptr (tiled few-row layers with >= 2048 weight tiles only, see
+// linear_top_lists_supported): also leave per-group top lists of every output row
+bool linear_top_lists_supported(int dtype, int M, int N, int K, int tiled);
 int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a, const void *w,
-                  float *out, int n_splits, int tiled);
+                  float *out, int n_splits, int tiled, void *top_out = nullptr);
 int launch_linear_swiglu(hipStream_t st, int dtype, int M, int N, int K, const void *a,
                          const void *wg, const void *wu, void *out, int tiled);
 // interleave_hd > 0: within every group of interleave_hd rows, destination row 2i takes source
@@ -188,9 +191,13 @@ int launch_attention_generic(hipStream_t st, int dtype, const AttnArgs &a);
 size_t decode_attention_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int prefix_len,
                                  int suffix_len, int page_tokens);
 int launch_attention_decode(hipStream_t st, int dtype, const DecodeAttnArgs &a);
+// top_lists != nullptr: the LM head's per-group top lists of the same rows ([row][n_groups][4]
+// pairs of {float bits, id}, row stride top_stride pairs; 0 = every candidate reads row 0), which
+// the selection uses instead of the rows where that is conclusive (see sample_kernel)
 int launch_sample(hipStream_t st, int n_cands, int vocab, const float *logits, size_t row_stride,
                   float temperature, int top_k, const float *uniforms, int32_t *out_tokens,
-                  int32_t *out_topk);
+                  int32_t *out_topk, const void *top_lists = nullptr, size_t top_stride = 0,
+                  int n_groups = 0);
 int launch_reward_score(hipStream_t st, int n_cands, int vocab, const float *logits,
                         const int32_t *reward_ids, const float *reward_values, int n_reward,
                         float score_temperature, float *out_logprobs, float *out_scores,

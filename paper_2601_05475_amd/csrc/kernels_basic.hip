@@ -572,40 +572,267 @@ __device__ inline void scan_row(const float *row, int V, F f) {
   }
 }
 
+// The same walk over a list of (value bits, id) pairs: the per-group top lists the LM head leaves
+// beside the logits (n even).
+template <typename F>
+__device__ inline void scan_pairs(const uint2 *list, int n, F f) {
+  constexpr int NB = 4;
+  const int tid = threadIdx.x;
+  const int n2 = n / 2;
+  const uint4 *l4 = (const uint4 *)list;
+  for (int g0 = 0; g0 < n2; g0 += NB * 1024) {
+    uint4 e[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int g = g0 + j * 1024 + tid;
+      e[j] = (g < n2) ? l4[g] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const bool ok = g0 + j * 1024 + tid < n2;
+      f(ok, __uint_as_float(e[j].x), (int)e[j].y);
+      f(ok, __uint_as_float(e[j].z), (int)e[j].w);
+    }
+  }
+}
+
+// LDS of the sampling kernel
+struct SampleShared {
+  unsigned long long sel[MC_MAX_TOP_K];
+  float ev[MC_MAX_TOP_K];
+  unsigned int hist[2048];
+  unsigned long long scratch64[16];
+  unsigned int scratch32[16];
+  unsigned int s_bin, s_above, s_cnt, s_cnt2;
+};
+
+// Threshold selection of the k largest keys of the elements `scan` walks (k <= 1024, at least
+// 4096 elements, every thread sees some and no two threads see the same): pass 1 takes every
+// thread's largest value; the threads form n_g >= k groups (n_g the next power of two), and the
+// smallest of the n_g group maxima, L, is a lower bound of the k-th largest value (n_g >= k
+// distinct elements are >= L); M is the overall maximum.  Pass 2 looks only at elements >= L (a
+// fraction of a percent of a row for k = 50): they are kept in an LDS list and counted in a
+// histogram over (M - value) in order-preserving integer units, 2047 bins.  The bin B in which the
+// count reaches k bounds the top k from below, the list is cut down to bins <= B (k plus a few).
+// Returns the number of keys left in sh.sel (>= k, the top k among them), or 0 if the list or the
+// cut overflowed (many equal values).  Division by T > 0, correctly rounded, never reverses an
+// order, so maxima are taken on the values themselves and only candidates are divided.
+template <typename Scan>
+__device__ inline int threshold_select(Scan scan, float temperature, int k, SampleShared &sh) {
+  const int tid = threadIdx.x;
+  unsigned int mine = 0;
+  scan([&](bool ok, float z, int) {
+    if (ok) mine = max(mine, float_order_bits(z));
+  });
+  const unsigned int M = float_order_bits(
+      __fdiv_rn(float_from_order_bits(block_reduce_u32(mine, true, sh.scratch32)), temperature));
+  int n_g = 1;
+  while (n_g < k) n_g <<= 1;
+  sh.hist[tid] = mine;
+  __syncthreads();
+  unsigned int gmax = 0xFFFFFFFFu;
+  if (tid < n_g) {
+    const int per = 1024 / n_g;
+    gmax = 0;
+    for (int i = 0; i < per; ++i) gmax = max(gmax, sh.hist[tid * per + i]);
+  }
+  const float z_l = float_from_order_bits(block_reduce_u32(gmax, false, sh.scratch32));
+  const unsigned int L = float_order_bits(__fdiv_rn(z_l, temperature));
+  // a value below z_low cannot reach L after the division (its quotient is smaller by dozens of
+  // ulps): a cheap test that spares the division for nearly every element
+  const float z_low = z_l - fabsf(z_l) * 3.8147e-06f - 1e-30f;
+  const unsigned int range = M - L;
+  int shift = 0;
+  while ((range >> shift) > 2046u) ++shift;
+  for (int i = tid; i < 2048; i += 1024) sh.hist[i] = 0;
+  if (tid == 0) { sh.s_cnt = 0; sh.s_cnt2 = 0; }
+  __syncthreads();
+  scan([&](bool ok, float z, int v) {
+    const bool maybe = ok && z >= z_low;
+    if (__ballot(maybe) == 0) return;             // wave-uniform: most batches hold no candidate
+    const unsigned int ob = maybe ? float_order_bits(__fdiv_rn(z, temperature)) : 0u;
+    const bool keep = maybe && ob >= L;
+    const unsigned int slot = wave_claim(keep, &sh.s_cnt);
+    if (keep) {
+      atomicAdd(&sh.hist[(M - ob) >> shift], 1u);
+      if (slot < MC_MAX_TOP_K) sh.sel[slot] = ((unsigned long long)ob << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)v);
+    }
+  });
+  __syncthreads();
+  const unsigned int n_cand = sh.s_cnt;
+  if (tid < 64) {
+    // lane L owns bins [32L, 32L + 32): find the bin in which the running count reaches k
+    unsigned int own = 0;
+    for (int i = 0; i < 32; ++i) own += sh.hist[32 * tid + i];
+    unsigned int incl = own;
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned int t = __shfl_up(incl, o, 64);
+      if (tid >= o) incl += t;
+    }
+    const unsigned int excl = incl - own;
+    if (excl < (unsigned int)k && incl >= (unsigned int)k) {   // exactly one lane (count >= n_g >= k)
+      unsigned int run = excl;
+      for (int i = 0; i < 32; ++i) {
+        run += sh.hist[32 * tid + i];
+        if (run >= (unsigned int)k) {
+          sh.s_bin = (unsigned int)(32 * tid + i);
+          sh.s_above = run;                          // elements in bins <= s_bin
+          break;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const unsigned int B = sh.s_bin, G = sh.s_above;
+  int n_sel = 0;
+  if (n_cand <= MC_MAX_TOP_K && G <= MC_MAX_TOP_K) {
+    // cut the list down to bins <= B: read everything, then write the survivors back
+    unsigned long long mykeys[MC_MAX_TOP_K / 1024];
+#pragma unroll
+    for (int j = 0; j < MC_MAX_TOP_K / 1024; ++j) {
+      const unsigned int i = tid + 1024 * j;
+      mykeys[j] = (i < n_cand) ? sh.sel[i] : 0ull;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < MC_MAX_TOP_K / 1024; ++j) {
+      const unsigned int i = tid + 1024 * j;
+      const bool keep = i < n_cand && ((M - (unsigned int)(mykeys[j] >> 32)) >> shift) <= B;
+      const unsigned int slot = wave_claim(keep, &sh.s_cnt2);
+      if (keep) sh.sel[slot] = mykeys[j];
+    }
+    __syncthreads();
+    n_sel = (int)sh.s_cnt2;                           // == G
+  }
+  __syncthreads();
+  return n_sel;
+}
+
+// Radix selection of the k largest keys of a row: up to six passes on the 64-bit key (11/11/10-bit
+// digits), exact for any input and any k.  Leaves exactly k keys in sh.sel.
+__device__ inline int radix_select(const float *row, int V, float temperature, int k, SampleShared &sh) {
+  const int tid = threadIdx.x;
+  unsigned long long prefix = 0, pmask = 0;
+  unsigned int need = (unsigned int)k;
+  const int shifts[6] = {53, 42, 32, 21, 10, 0};
+  const int nbits[6] = {11, 11, 10, 11, 11, 10};
+  for (int pass = 0; pass < 6; ++pass) {
+    const int shift = shifts[pass];
+    const unsigned int bmask = (1u << nbits[pass]) - 1u;
+    for (int i = tid; i < 2048; i += 1024) sh.hist[i] = 0;
+    __syncthreads();
+    for (int v = tid; v < V; v += 1024) {
+      const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
+      if ((key & pmask) == prefix) atomicAdd(&sh.hist[(unsigned int)(key >> shift) & bmask], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {
+      // lane L owns bins [2048-32(L+1), 2048-32L): walk from the top bin down
+      const int hi = 2048 - 32 * tid;
+      unsigned int mine = 0;
+      for (int i = 1; i <= 32; ++i) mine += sh.hist[hi - i];
+      unsigned int incl = mine;                   // inclusive scan over lanes 0..L
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned int t = __shfl_up(incl, o, 64);
+        if (tid >= o) incl += t;
+      }
+      const unsigned int excl = incl - mine;
+      if (excl < need && incl >= need) {          // exactly one lane
+        unsigned int above = excl;
+        for (int i = 1; i <= 32; ++i) {
+          const unsigned int c = sh.hist[hi - i];
+          if (above + c >= need) {
+            sh.s_bin = (unsigned int)(hi - i);
+            sh.s_above = above;
+            sh.s_cnt = c;
+            break;
+          }
+          above += c;
+        }
+      }
+    }
+    __syncthreads();
+    prefix |= (unsigned long long)sh.s_bin << shift;
+    pmask |= (unsigned long long)bmask << shift;
+    need -= sh.s_above;
+    const bool done = (sh.s_cnt == need);            // the whole bin belongs to the top k
+    __syncthreads();
+    if (done) break;
+  }
+  // every key >= prefix (low bits zero) is selected: exactly k of them
+  if (tid == 0) sh.s_cnt = 0;
+  __syncthreads();
+  for (int v = tid; v < V; v += 1024) {
+    const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
+    if (key >= prefix) {
+      const unsigned int slot = atomicAdd(&sh.s_cnt, 1u);
+      if (slot < MC_MAX_TOP_K) sh.sel[slot] = key;
+    }
+  }
+  return k;
+}
+
+// Bitonic sort of sh.sel[0 .. n_sel), descending: the first k entries are the top k in order.
+__device__ inline void sort_selected(int n_sel, SampleShared &sh) {
+  const int tid = threadIdx.x;
+  int kp = 1;
+  while (kp < n_sel) kp <<= 1;
+  __syncthreads();
+  for (int i = n_sel + tid; i < kp; i += 1024) sh.sel[i] = 0ull;
+  __syncthreads();
+  for (int size = 2; size <= kp; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int i = tid; i < kp; i += 1024) {
+        const int j = i ^ stride;
+        if (j > i) {
+          const unsigned long long x = sh.sel[i], y = sh.sel[j];
+          const bool desc = ((i & size) == 0);
+          if ((x < y) == desc) { sh.sel[i] = y; sh.sel[j] = x; }
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
 // One block of 1024 threads per candidate: exact top-k of z / T under the order (value
 // descending, id ascending), a bitonic sort of the survivors in LDS, then the softmax and the
 // cumulative walk done left to right by one thread, as the rule demands.
 //
-// Selection, fast path (k <= 1024, V >= 4096): pass 1 takes every thread's largest value; the
-// threads form n_g >= k groups (n_g the next power of two), and the smallest of the n_g group
-// maxima, L, is a lower bound of the k-th largest value (n_g >= k distinct elements are >= L);
-// M is the row maximum.  Pass 2 looks only at elements >= L (a fraction of a percent of the row
-// for k = 50): they are kept in an LDS list and counted in a histogram over (M - value) in
-// order-preserving integer units, 2047 bins.  The bin B in which the count reaches k bounds the
-// top k from below, the list is cut down to bins <= B (k plus a few) and sorted.  Two passes over
-// the row and hardly any contended atomics.  If the list or the cut overflows (many equal
-// values), or k > 1024, the radix selection below does the job: up to six passes on the 64-bit
-// key (11/11/10-bit digits), exact for any input.
+// Where the LM head left per-group top lists beside the logits (top != nullptr: for every group
+// of 64 consecutive ids its kTopListLen largest (value, id) pairs in order) and k <= kTopListMaxK,
+// the selection runs on those lists, 1 / 16 of a row.  The result is the row's top k provided
+// no group's last listed entry reaches the k-th selected value after the division (then an
+// unlisted element of that group could belong to the top k, or tie with its last member): that
+// is checked, and such a row is selected from the whole row instead, so the ids are the rule's
+// in every case.  Selection from a row: threshold selection (two passes, k <= 1024, V >= 4096),
+// else radix selection.
+constexpr int kTopListLen = 4, kTopListMaxK = 64;
 __global__ __launch_bounds__(1024) void sample_kernel(
-    int V, const float *__restrict__ logits, size_t row_stride, float temperature, int top_k,
+    int V, const float *__restrict__ logits, size_t row_stride, const uint2 *__restrict__ top,
+    size_t top_stride, int n_groups, float temperature, int top_k,
     const float *__restrict__ uniforms, int32_t *__restrict__ out_tokens,
     int32_t *__restrict__ out_topk) {
-  __shared__ unsigned long long sel[MC_MAX_TOP_K];
-  __shared__ float ev[MC_MAX_TOP_K];
-  __shared__ unsigned int hist[2048];
-  __shared__ unsigned long long scratch64[16];
-  __shared__ unsigned int scratch32[16];
-  __shared__ unsigned int s_bin, s_above, s_cnt, s_cnt2;
+  __shared__ SampleShared sh;
   const int b = blockIdx.x, tid = threadIdx.x;
   const float *row = logits + (size_t)b * row_stride;
+  const uint2 *list = top ? top + (size_t)b * top_stride : nullptr;
 
   if (temperature <= 0.f || top_k == 1) {
     unsigned long long best = 0;
-    for (int v = tid; v < V; v += 1024) {
-      const unsigned long long key = sample_key(row[v], v);
-      best = key > best ? key : best;
+    if (list) {                                    // the arg max is the best of the groups' first entries
+      for (int g = tid; g < n_groups; g += 1024) {
+        const uint2 e = list[(size_t)g * kTopListLen];
+        const unsigned long long key = sample_key(__uint_as_float(e.x), (int)e.y);
+        best = key > best ? key : best;
+      }
+    } else {
+      for (int v = tid; v < V; v += 1024) {
+        const unsigned long long key = sample_key(row[v], v);
+        best = key > best ? key : best;
+      }
     }
-    best = block_max_u64(best, scratch64);
+    best = block_max_u64(best, sh.scratch64);
     if (tid == 0) {
       const int tok = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
       out_tokens[b] = tok;
@@ -616,205 +843,54 @@ __global__ __launch_bounds__(1024) void sample_kernel(
   const int k = (top_k <= 0 || top_k >= V) ? V : top_k;
   int n_sel = 0;                                   // keys in sel[] (>= k; the top k are among them)
 
-  // ---- fast path
-  if (k <= 1024 && V >= 4096) {
-    // Division by T > 0, correctly rounded, never reverses an order, so maxima are taken on the
-    // logits themselves and only they are divided.
-    unsigned int mine = 0;
-    scan_row(row, V, [&](bool ok, float z, int) {
-      if (ok) mine = max(mine, float_order_bits(z));
-    });
-    const unsigned int M = float_order_bits(
-        __fdiv_rn(float_from_order_bits(block_reduce_u32(mine, true, scratch32)), temperature));
-    // group maxima: n_g groups of 1024 / n_g consecutive threads (V >= 4096: every thread has
-    // seen elements, and different threads see different elements)
-    int n_g = 1;
-    while (n_g < k) n_g <<= 1;
-    hist[tid] = mine;
-    __syncthreads();
-    unsigned int gmax = 0xFFFFFFFFu;
-    if (tid < n_g) {
-      const int per = 1024 / n_g;
-      gmax = 0;
-      for (int i = 0; i < per; ++i) gmax = max(gmax, hist[tid * per + i]);
-    }
-    const float z_l = float_from_order_bits(block_reduce_u32(gmax, false, scratch32));
-    const unsigned int L = float_order_bits(__fdiv_rn(z_l, temperature));
-    // a logit below z_low cannot reach L after the division (its quotient is smaller by dozens
-    // of ulps): a cheap test that spares the division for nearly every element
-    const float z_low = z_l - fabsf(z_l) * 3.8147e-06f - 1e-30f;
-    const unsigned int range = M - L;
-    int shift = 0;
-    while ((range >> shift) > 2046u) ++shift;
-    for (int i = tid; i < 2048; i += 1024) hist[i] = 0;
-    if (tid == 0) { s_cnt = 0; s_cnt2 = 0; }
-    __syncthreads();
-    scan_row(row, V, [&](bool ok, float z, int v) {
-      const bool maybe = ok && z >= z_low;
-      if (__ballot(maybe) == 0) return;             // wave-uniform: most batches hold no candidate
-      const unsigned int ob = maybe ? float_order_bits(__fdiv_rn(z, temperature)) : 0u;
-      const bool keep = maybe && ob >= L;
-      const unsigned int slot = wave_claim(keep, &s_cnt);
-      if (keep) {
-        atomicAdd(&hist[(M - ob) >> shift], 1u);
-        if (slot < MC_MAX_TOP_K) sel[slot] = ((unsigned long long)ob << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)v);
+  if (list && k <= kTopListMaxK && n_groups * kTopListLen >= 4096) {
+    n_sel = threshold_select([&](auto f) { scan_pairs(list, n_groups * kTopListLen, f); }, temperature, k, sh);
+    if (n_sel) {
+      sort_selected(n_sel, sh);
+      // conclusive only if every group's last listed entry stays below the k-th selected value
+      const unsigned int z_k = (unsigned int)(sh.sel[k - 1] >> 32);
+      unsigned int open = 0;
+      for (int g = tid; g < n_groups; g += 1024) {
+        const uint2 e = list[(size_t)g * kTopListLen + kTopListLen - 1];
+        open |= float_order_bits(__fdiv_rn(__uint_as_float(e.x), temperature)) >= z_k ? 1u : 0u;
       }
-    });
-    __syncthreads();
-    const unsigned int n_cand = s_cnt;
-    if (tid < 64) {
-      // lane L owns bins [32L, 32L + 32): find the bin in which the running count reaches k
-      unsigned int own = 0;
-      for (int i = 0; i < 32; ++i) own += hist[32 * tid + i];
-      unsigned int incl = own;
-      for (int o = 1; o < 64; o <<= 1) {
-        const unsigned int t = __shfl_up(incl, o, 64);
-        if (tid >= o) incl += t;
-      }
-      const unsigned int excl = incl - own;
-      if (excl < (unsigned int)k && incl >= (unsigned int)k) {   // exactly one lane (count >= 1024 >= k)
-        unsigned int run = excl;
-        for (int i = 0; i < 32; ++i) {
-          run += hist[32 * tid + i];
-          if (run >= (unsigned int)k) {
-            s_bin = (unsigned int)(32 * tid + i);
-            s_above = run;                          // elements in bins <= s_bin
-            break;
-          }
-        }
-      }
-    }
-    __syncthreads();
-    const unsigned int B = s_bin, G = s_above;
-    if (n_cand <= MC_MAX_TOP_K && G <= MC_MAX_TOP_K) {
-      // cut the list down to bins <= B: read everything, then write the survivors back
-      unsigned long long mykeys[MC_MAX_TOP_K / 1024];
-#pragma unroll
-      for (int j = 0; j < MC_MAX_TOP_K / 1024; ++j) {
-        const unsigned int i = tid + 1024 * j;
-        mykeys[j] = (i < n_cand) ? sel[i] : 0ull;
-      }
+      if (block_reduce_u32(open, true, sh.scratch32)) n_sel = 0;
       __syncthreads();
-#pragma unroll
-      for (int j = 0; j < MC_MAX_TOP_K / 1024; ++j) {
-        const unsigned int i = tid + 1024 * j;
-        const bool keep = i < n_cand && ((M - (unsigned int)(mykeys[j] >> 32)) >> shift) <= B;
-        const unsigned int slot = wave_claim(keep, &s_cnt2);
-        if (keep) sel[slot] = mykeys[j];
-      }
-      __syncthreads();
-      n_sel = (int)s_cnt2;                           // == G
     }
-    __syncthreads();
   }
-
-  // ---- general path: radix selection of the k-th largest key
   if (n_sel == 0) {
-    unsigned long long prefix = 0, pmask = 0;
-    unsigned int need = (unsigned int)k;
-    const int shifts[6] = {53, 42, 32, 21, 10, 0};
-    const int nbits[6] = {11, 11, 10, 11, 11, 10};
-    for (int pass = 0; pass < 6; ++pass) {
-      const int shift = shifts[pass];
-      const unsigned int bmask = (1u << nbits[pass]) - 1u;
-      for (int i = tid; i < 2048; i += 1024) hist[i] = 0;
-      __syncthreads();
-      for (int v = tid; v < V; v += 1024) {
-        const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
-        if ((key & pmask) == prefix) atomicAdd(&hist[(unsigned int)(key >> shift) & bmask], 1u);
-      }
-      __syncthreads();
-      if (tid < 64) {
-        // lane L owns bins [2048-32(L+1), 2048-32L): walk from the top bin down
-        const int hi = 2048 - 32 * tid;
-        unsigned int mine = 0;
-        for (int i = 1; i <= 32; ++i) mine += hist[hi - i];
-        unsigned int incl = mine;                   // inclusive scan over lanes 0..L
-        for (int o = 1; o < 64; o <<= 1) {
-          const unsigned int t = __shfl_up(incl, o, 64);
-          if (tid >= o) incl += t;
-        }
-        const unsigned int excl = incl - mine;
-        if (excl < need && incl >= need) {          // exactly one lane
-          unsigned int above = excl;
-          for (int i = 1; i <= 32; ++i) {
-            const unsigned int c = hist[hi - i];
-            if (above + c >= need) {
-              s_bin = (unsigned int)(hi - i);
-              s_above = above;
-              s_cnt = c;
-              break;
-            }
-            above += c;
-          }
-        }
-      }
-      __syncthreads();
-      prefix |= (unsigned long long)s_bin << shift;
-      pmask |= (unsigned long long)bmask << shift;
-      need -= s_above;
-      const bool done = (s_cnt == need);            // the whole bin belongs to the top k
-      __syncthreads();
-      if (done) break;
-    }
-    // every key >= prefix (low bits zero) is selected: exactly k of them
-    if (tid == 0) s_cnt = 0;
-    __syncthreads();
-    for (int v = tid; v < V; v += 1024) {
-      const unsigned long long key = sample_key(__fdiv_rn(row[v], temperature), v);
-      if (key >= prefix) {
-        const unsigned int slot = atomicAdd(&s_cnt, 1u);
-        if (slot < MC_MAX_TOP_K) sel[slot] = key;
-      }
-    }
-    n_sel = k;
+    if (k <= 1024 && V >= 4096)
+      n_sel = threshold_select([&](auto f) { scan_row(row, V, f); }, temperature, k, sh);
+    if (n_sel == 0) n_sel = radix_select(row, V, temperature, k, sh);
+    sort_selected(n_sel, sh);
   }
-  int kp = 1;
-  while (kp < n_sel) kp <<= 1;
-  __syncthreads();
-  for (int i = n_sel + tid; i < kp; i += 1024) sel[i] = 0ull;
-  __syncthreads();
-  // ---- bitonic sort, descending; the first k entries are the top k in order
-  for (int size = 2; size <= kp; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int i = tid; i < kp; i += 1024) {
-        const int j = i ^ stride;
-        if (j > i) {
-          const unsigned long long x = sel[i], y = sel[j];
-          const bool desc = ((i & size) == 0);
-          if ((x < y) == desc) { sel[i] = y; sel[j] = x; }
-        }
-      }
-      __syncthreads();
-    }
-  }
-  const float z0 = float_from_order_bits((uint32_t)(sel[0] >> 32));
+  const float z0 = float_from_order_bits((uint32_t)(sh.sel[0] >> 32));
   for (int i = tid; i < k; i += 1024)
-    ev[i] = expf(float_from_order_bits((uint32_t)(sel[i] >> 32)) - z0);
+    sh.ev[i] = expf(float_from_order_bits((uint32_t)(sh.sel[i] >> 32)) - z0);
   if (out_topk)
     for (int i = tid; i < k; i += 1024)
-      out_topk[(size_t)b * k + i] = (int)(0xFFFFFFFFu - (uint32_t)(sel[i] & 0xFFFFFFFFull));
+      out_topk[(size_t)b * k + i] = (int)(0xFFFFFFFFu - (uint32_t)(sh.sel[i] & 0xFFFFFFFFull));
   __syncthreads();
   if (tid == 0) {
     float total = 0.f;
-    for (int i = 0; i < k; ++i) total += ev[i];
+    for (int i = 0; i < k; ++i) total += sh.ev[i];
     const float u = uniforms[b];
     float run = 0.f;
     int pick = k - 1;
     for (int i = 0; i < k; ++i) {
-      run += ev[i];
+      run += sh.ev[i];
       if (__fdiv_rn(run, total) > u) { pick = i; break; }
     }
-    out_tokens[b] = (int)(0xFFFFFFFFu - (uint32_t)(sel[pick] & 0xFFFFFFFFull));
+    out_tokens[b] = (int)(0xFFFFFFFFu - (uint32_t)(sh.sel[pick] & 0xFFFFFFFFull));
   }
 }
 
 int launch_sample(hipStream_t st, int n_cands, int vocab, const float *logits, size_t row_stride,
                   float temperature, int top_k, const float *uniforms, int32_t *out_tokens,
-                  int32_t *out_topk) {
+                  int32_t *out_topk, const void *top_lists, size_t top_stride, int n_groups) {
   if (n_cands <= 0) return MC_OK;
-  sample_kernel<<<n_cands, 1024, 0, st>>>(vocab, logits, row_stride, temperature, top_k, uniforms,
-                                          out_tokens, out_topk);
+  sample_kernel<<<n_cands, 1024, 0, st>>>(vocab, logits, row_stride, (const uint2 *)top_lists, top_stride, n_groups,
+                                          temperature, top_k, uniforms, out_tokens, out_topk);
   MC_HIP(hipGetLastError());
   return MC_OK;
 }

@@ -33,9 +33,15 @@ bool skinny_linear_supported(int M, int N, int K);
 int skinny_linear_splits(int M, int N, int K);
 // rope != nullptr: the fused QKV layer (one K split): w has the rows of every query / key head
 // interleaved (launch_pack_tiled), and the result goes where *rope says instead of to `out`.
+// top_out != nullptr (plain sums of a layer with >= 2048 weight tiles, the LM head): besides the
+// sums, for every row m and every group g of 64 consecutive outputs the kTopPerGroup largest
+// (value, id) pairs under (value descending, id ascending), top_out[(m * N / 64 + g) * kTopPerGroup
+// + t] = {float bits, id}: what the sampler needs of a row, 1 / 16 of its size.
+constexpr int kTopPerGroup = 4;
+bool skinny_top_lists_supported(int M, int N, int K);
 int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, const void *w,
                          const void *w2, float *out, void *out_t, int n_splits,
-                         const RopeOut *rope = nullptr);
+                         const RopeOut *rope = nullptr, void *top_out = nullptr);
 
 // Epilogue of the fused QKV layer for one row m and four consecutive outputs n .. n + 3 of the
 // interleaved weight layout, i.e. coordinates (i, i + hd/2, i + 1, i + 1 + hd/2) of one query or

@@ -122,12 +122,36 @@ int launch_read_probe(hipStream_t st, const void *buf, size_t bytes, uint32_t *o
 // one) over the whole K range, so an activation fragment serves two weight tiles, the four waves
 // of a workgroup fetch the same activation units at about the same time (L1), and there is
 // nothing to reduce across waves: each wave stores its own 64 output columns.
+// Sorted list of the kTopPerGroup best (value, id) pairs under the order (value descending, id
+// ascending), kept in registers.  insert() takes `first` = "the new pair ranks before entry s".
+struct Top4 {
+  float v[kTopPerGroup];
+  int id[kTopPerGroup];
+  __device__ inline void clear() {
+#pragma unroll
+    for (int s = 0; s < kTopPerGroup; ++s) { v[s] = -INFINITY; id[s] = 0x7FFFFFFF; }
+  }
+  template <typename Before>
+  __device__ inline void insert(float x, int xi, Before before) {
+    bool c[kTopPerGroup];
+#pragma unroll
+    for (int s = 0; s < kTopPerGroup; ++s) c[s] = before(x, xi, v[s], id[s]);      // c[s] implies c[s + 1]
+#pragma unroll
+    for (int s = kTopPerGroup - 1; s > 0; --s) {
+      v[s] = c[s - 1] ? v[s - 1] : (c[s] ? x : v[s]);
+      id[s] = c[s - 1] ? id[s - 1] : (c[s] ? xi : id[s]);
+    }
+    v[0] = c[0] ? x : v[0];
+    id[0] = c[0] ? xi : id[0];
+  }
+};
+
 enum { SKINNY_PLAIN = 0, SKINNY_SWIGLU = 1, SKINNY_PAIR = 2 };
 template <int MB, int MODE, bool ROPE>
 __global__ __launch_bounds__(256) void skinny_linear_kernel(
     int M, int N, int K, int units_per_wave, const bf16_t *__restrict__ a,
     const bf16_t *__restrict__ w, const bf16_t *__restrict__ w2, float *__restrict__ out,
-    bf16_t *__restrict__ out_t, RopeOut ro) {
+    bf16_t *__restrict__ out_t, RopeOut ro, uint2 *__restrict__ top_out) {
   constexpr bool SWIGLU = MODE == SKINNY_SWIGLU, PAIR = MODE == SKINNY_PAIR;
   constexpr int NW = MODE != SKINNY_PLAIN ? 2 : 1;
   __shared__ float4 red[4][NW][MB][4][64];
@@ -200,6 +224,40 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
           *(float4 *)(out + (size_t)m * N + 32 * (wt + i) + 8 * r4 + 4 * h) =
               make_float4(acc[i][mb][4 * r4], acc[i][mb][4 * r4 + 1], acc[i][mb][4 * r4 + 2], acc[i][mb][4 * r4 + 3]);
       }
+    if (!top_out) return;
+    // The LM head's share of sampling: the kTopPerGroup largest of this wave's 64 outputs of every
+    // row, under (value descending, id ascending), so that the sampler reads 2004 short lists
+    // instead of 128256 logits per row.  A lane walks its 32 outputs in ascending id (a later equal
+    // value never displaces an earlier one), then the two half-waves merge their lists.
+    const int swap_addr = (lane ^ 32) << 2;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      Top4 t;
+      t.clear();
+#pragma unroll
+      for (int i = 0; i < NW; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          t.insert(acc[i][mb][r] + 0.0f, 32 * (wt + i) + 8 * (r >> 2) + 4 * h + (r & 3),
+                   [](float x, int, float y, int) { return x > y; });
+      float pv[kTopPerGroup];
+      int pi[kTopPerGroup];
+#pragma unroll
+      for (int s = 0; s < kTopPerGroup; ++s) {
+        pv[s] = swap_halves(t.v[s], swap_addr);
+        pi[s] = __builtin_amdgcn_ds_bpermute(swap_addr, t.id[s]);
+      }
+#pragma unroll
+      for (int s = 0; s < kTopPerGroup; ++s)
+        t.insert(pv[s], pi[s], [](float x, int xi, float y, int yi) { return x > y || (x == y && xi < yi); });
+      const int m = mb * 32 + nl;
+      if (h == 0 && m < M) {
+        uint2 *dst = top_out + ((size_t)m * (N / 64) + rt) * kTopPerGroup;
+#pragma unroll
+        for (int s = 0; s < kTopPerGroup; s += 2)
+          *(uint4 *)(dst + s) = make_uint4(__float_as_uint(t.v[s]), (uint32_t)t.id[s], __float_as_uint(t.v[s + 1]), (uint32_t)t.id[s + 1]);
+      }
+    }
     return;
   }
 #pragma unroll
@@ -391,8 +449,19 @@ int skinny_linear_splits(int M, int N, int K) {
   return best;
 }
 
+// many more tiles than CUs, plain sums: every wave takes a pair of weight tiles (SKINNY_PAIR)
+static bool skinny_pair_form(int N, int n_splits, bool rope, bool swiglu) {
+  return !rope && !swiglu && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
+}
+
+bool skinny_top_lists_supported(int M, int N, int K) {
+  return skinny_linear_supported(M, N, K) && N % 64 == 0 && skinny_pair_form(N, 1, false, false) &&
+         !skinny_shared_form(M, N, 1, false);
+}
+
 int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, const void *w,
-                         const void *w2, float *out, void *out_t, int n_splits, const RopeOut *rope) {
+                         const void *w2, float *out, void *out_t, int n_splits, const RopeOut *rope,
+                         void *top_out) {
   const int units = K / 64;
   if (!skinny_linear_supported(M, N, K) || n_splits < 1 || units % (4 * n_splits))
     MC_FAIL(MC_ERR_UNSUPPORTED, "few-row linear: M=%d N=%d K=%d splits=%d not covered", M, N, K, n_splits);
@@ -401,6 +470,8 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   if (rope && (w2 || n_splits != 1 || rope->hd % 4 || N != (rope->Hq + 2 * rope->Hkv) * rope->hd))
     MC_FAIL(MC_ERR_INVALID, "fused QKV output: one K split, N = (Hq + 2 Hkv) hd, hd %% 4 == 0");
   const RopeOut none{};
+  if (top_out && !(n_splits == 1 && !rope && !w2 && skinny_top_lists_supported(M, N, K)))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "per-group top lists: M=%d N=%d K=%d not covered", M, N, K);
   if (skinny_shared_form(M, N, n_splits, rope != nullptr)) {
     const int groups = (N / 32 + 3) / 4;
     const dim3 grid2((groups + 7) / 8 * 8, n_splits);
@@ -421,8 +492,7 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   int upw = units / (4 * n_splits);
   const bf16_t *A = (const bf16_t *)a, *W = (const bf16_t *)w, *W2 = (const bf16_t *)w2;
   bf16_t *OT = (bf16_t *)out_t;
-  // many more tiles than CUs, plain sums: two weight tiles per workgroup
-  const bool pair = !rope && !w2 && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
+  const bool pair = skinny_pair_form(N, n_splits, rope != nullptr, w2 != nullptr);
   dim3 grid(pair ? ((N / 64 + 3) / 4 + 7) / 8 * 8 : N / 32, n_splits);
   if (pair) {
     W2 = W + (size_t)units * 2048;                             // the tile after w's
@@ -432,9 +502,9 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   const LaunchEvents ev = take_launch_events();
   auto go = [&](auto kernel, const RopeOut &ro) {
     if (ev.start || ev.stop)
-      hipExtLaunchKernelGGL(kernel, grid, dim3(256), 0, st, ev.start, ev.stop, 0, M, N, K, upw, A, W, W2, out, OT, ro);
+      hipExtLaunchKernelGGL(kernel, grid, dim3(256), 0, st, ev.start, ev.stop, 0, M, N, K, upw, A, W, W2, out, OT, ro, (uint2 *)top_out);
     else
-      kernel<<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, ro);
+      kernel<<<grid, 256, 0, st>>>(M, N, K, upw, A, W, W2, out, OT, ro, (uint2 *)top_out);
   };
   if (M <= 32) {
     if (rope) go(skinny_linear_kernel<1, SKINNY_PLAIN, true>, *rope);

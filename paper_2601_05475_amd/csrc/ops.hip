@@ -61,12 +61,18 @@ int linear_auto_splits(int dtype, int M, int N, int K, int tiled) {
   return s;
 }
 
+bool linear_top_lists_supported(int dtype, int M, int N, int K, int tiled) {
+  return tiled && dtype == MC_BF16 && M <= 64 && tiled_shapes_ok(M, N, K) && skinny_top_lists_supported(M, N, K);
+}
+
 int launch_linear(hipStream_t st, int dtype, int M, int N, int K, const void *a, const void *w,
-                  float *out, int n_splits, int tiled) {
+                  float *out, int n_splits, int tiled, void *top_out) {
+  if (top_out && !(n_splits == 1 && linear_top_lists_supported(dtype, M, N, K, tiled)))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "per-group top lists: M=%d N=%d K=%d not covered", M, N, K);
   if (!tiled) return launch_linear_generic(st, dtype, M, N, K, a, w, out, n_splits);
   if (dtype != MC_BF16 || !tiled_shapes_ok(M, N, K))
     MC_FAIL(MC_ERR_UNSUPPORTED, "tiled linear layer: bf16 with N %% 128 == 0 and K %% 256 == 0 only");
-  if (M <= 64) return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits);
+  if (M <= 64) return launch_linear_skinny(st, M, N, K, a, w, nullptr, out, nullptr, n_splits, nullptr, top_out);
   if (n_splits != 1) MC_FAIL(MC_ERR_UNSUPPORTED, "the many-row GEMM does not split K");
   return launch_gemm256(st, M, N, K, a, w, nullptr, out, nullptr);
 }
@@ -380,6 +386,35 @@ extern "C" int mc_op_attention_prefill(void *stream, int32_t n_items, const int3
   a.head_dim = head_dim; a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.out = out;
   a.out_tiled = out_tiled;
   return launch_attention_prefill_mfma((hipStream_t)stream, a);
+}
+
+extern "C" size_t mc_op_top_list_bytes(int32_t rows, int32_t N) {
+  if (rows < 1 || N < 64 || N % 64) return 0;
+  return (size_t)rows * (N / 64) * kTopPerGroup * 8;
+}
+
+extern "C" int mc_op_lm_head(void *stream, int32_t M, int32_t N, int32_t K, const void *a, const void *w,
+                             float *logits, void *top_lists) {
+  if (M < 1 || N < 1 || K < 1) MC_FAIL(MC_ERR_INVALID, "bad sizes");
+  if (!a || !w || !logits || !top_lists) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  if (!linear_top_lists_supported(MC_BF16, M, N, K, 1))
+    MC_FAIL(MC_ERR_UNSUPPORTED, "LM head with top lists: at most 32 rows, N %% 128 == 0, N >= 65536, K %% 256 == 0");
+  return launch_linear((hipStream_t)stream, MC_BF16, M, N, K, a, w, logits, 1, 1, top_lists);
+}
+
+extern "C" int mc_op_sample_lists(void *stream, int32_t n_cands, int32_t vocab, const float *logits,
+                                  size_t row_stride, const void *top_lists, float temperature,
+                                  int32_t top_k, const float *uniforms, int32_t *out_tokens,
+                                  int32_t *out_topk) {
+  if (n_cands < 1 || vocab < 64 || vocab % 64) MC_FAIL(MC_ERR_INVALID, "bad sizes (vocab must be a multiple of 64)");
+  if (!logits || !top_lists || !uniforms || !out_tokens) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
+  if (!isfinite(temperature)) MC_FAIL(MC_ERR_INVALID, "temperature is not finite");
+  const bool greedy = temperature <= 0.f || top_k == 1;
+  const int k = greedy ? 1 : ((top_k <= 0 || top_k >= vocab) ? vocab : top_k);
+  if (k > MC_MAX_TOP_K) MC_FAIL(MC_ERR_UNSUPPORTED, "top_k %d exceeds the supported %d", k, MC_MAX_TOP_K);
+  const int n_groups = vocab / 64;
+  return launch_sample((hipStream_t)stream, n_cands, vocab, logits, row_stride, temperature, top_k, uniforms,
+                       out_tokens, out_topk, top_lists, row_stride ? (size_t)n_groups * kTopPerGroup : 0, n_groups);
 }
 
 extern "C" int mc_op_sample(void *stream, int32_t n_cands, int32_t vocab, const float *logits,

@@ -235,7 +235,8 @@ constexpr int kProfCap = 8192;
 struct SessionLayout {
   size_t kpool, vpool, kscr, vscr, x, h, part, q, attn_out, act, logits, prefix_logits, xlast,
       hlast, attn_ws, alive, rope_tab, row_tok, row_pos, row_page, row_off, row_tab, last_idx, page_table,
-      page_new, cand_len, row_len, score_table, items, samp_tok, samp_u, topk, rw_ids, rw_vals, rw_lp, rw_scores, rw_rank;
+      page_new, cand_len, row_len, score_table, items, samp_tok, samp_u, topk, top_lists, top_lists_prefix, rw_ids, rw_vals,
+      rw_lp, rw_scores, rw_rank;
   size_t total;
   // derived sizes
   int rows_cap, n_prefix_pages, n_pool_pages, pages_per_cand, n_score_pages;
@@ -311,6 +312,10 @@ static void session_layout(const mc_config &c, const mc_session_params &p, Sessi
   o.samp_tok = at((size_t)p.max_cands * 4);
   o.samp_u = at((size_t)p.max_cands * 4);
   o.topk = at((size_t)p.max_cands * MC_MAX_TOP_K * 4);
+  // per-group top lists the LM head leaves beside the logits (candidates' rows, prefix row)
+  const size_t list_row = (size_t)(c.vocab / 64 + 1) * kTopPerGroup * 8;
+  o.top_lists = at((size_t)p.max_cands * list_row);
+  o.top_lists_prefix = at(list_row);
   o.rw_ids = at(MC_MAX_REWARD * 4);
   o.rw_vals = at(MC_MAX_REWARD * 4);
   o.rw_lp = at((size_t)p.max_cands * MC_MAX_REWARD * 4);
@@ -338,6 +343,8 @@ struct mc_session {
   // state
   int prefix_len = 0, n_cands = 0, suffix_len = 0, logits_state = LOGITS_NONE, logits_rows = 0;
   bool sampled_on_device = false;
+  // the LM head left per-group top lists beside the pending logits (candidates' rows / prefix row)
+  bool lists_cands = false, lists_prefix = false;
   // candidates still decoding, ascending ids (all of 0..n_cands-1 until some are dropped); row r
   // of every per-candidate buffer belongs to candidate alive[r]
   std::vector<int32_t> alive;
@@ -590,7 +597,10 @@ static int run_layers(mc_session *s, int rows, int pass, int prefix_visible, int
 
 // Final norm + LM head on n_rows rows gathered from x (indices on device in last_idx, or the
 // rows 0..n_rows-1 when idx_on_device is false); logits go to `dst`.
-static int lm_head(mc_session *s, int rows_in_x, int tail_splits, int n_rows, bool gather, float *dst) {
+// top_out: per-group top lists of the n_rows logits rows for the sampler, or nullptr; *lists_written
+// tells whether the layer's form could leave them.
+static int lm_head(mc_session *s, int rows_in_x, int tail_splits, int n_rows, bool gather, float *dst,
+                   void *top_out = nullptr, bool *lists_written = nullptr) {
   const mc_model *m = s->m;
   const mc_config &c = m->cfg;
   const SessionLayout &L = s->lay;
@@ -615,8 +625,10 @@ static int lm_head(mc_session *s, int rows_in_x, int tail_splits, int n_rows, bo
                               tail_splits, m->final_norm, c.rms_eps, s->ptr<void>(L.h), m->tiled));
     hin = s->ptr<void>(L.h);
   }
+  const bool lists = top_out && linear_top_lists_supported(c.dtype, n_rows, c.vocab, c.d_model, m->tiled);
+  if (lists_written) *lists_written = lists;
   ProfScope ps(s, MC_K_LINEAR_LM_HEAD);
-  MC_TRY(launch_linear(st, c.dtype, n_rows, c.vocab, c.d_model, hin, m->lm_head, dst, 1, m->tiled));
+  MC_TRY(launch_linear(st, c.dtype, n_rows, c.vocab, c.d_model, hin, m->lm_head, dst, 1, m->tiled, lists ? top_out : nullptr));
   return MC_OK;
 }
 
@@ -744,7 +756,10 @@ static int prefill_range(mc_session *s, const int32_t *tokens, int n_tokens, int
   // logits of the last position only
   const int32_t last = rows - 1;
   MC_TRY(upload(s, s->ptr<void>(L.last_idx), &last, 4));
-  MC_TRY(lm_head(s, rows, tail, 1, true, s->ptr<float>(L.prefix_logits)));
+  s->lists_prefix = false;
+  bool lists = false;
+  MC_TRY(lm_head(s, rows, tail, 1, true, s->ptr<float>(L.prefix_logits), s->ptr<void>(L.top_lists_prefix), &lists));
+  s->lists_prefix = lists;
   return MC_OK;
 }
 
@@ -832,6 +847,7 @@ extern "C" int mc_promote_candidate(mc_session *s, int32_t cand) {
   MC_HIP(hipGetLastError());
   // the candidate's last logits become the logits of the last prefix position
   const bool have_logits = s->logits_state == LOGITS_CANDS && s->logits_rows == (int)s->alive.size();
+  s->lists_prefix = false;                      // the prefix row changes: its top lists are not copied along
   if (have_logits)
     MC_HIP(hipMemcpyAsync(s->ptr<void>(L.prefix_logits), s->ptr<float>(L.logits) + (size_t)ri * c.vocab,
                           (size_t)c.vocab * 4, hipMemcpyDeviceToDevice, s->stream));
@@ -976,8 +992,11 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   }
   int tail = 0;
   int rc = run_layers(s, n_cands, PASS_DECODE, s->prefix_len, 0, &tail);
-  if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits));
+  bool lists = false;
+  s->lists_cands = false;
+  if (rc == MC_OK) rc = lm_head(s, n_cands, tail, n_cands, false, s->ptr<float>(L.logits), s->ptr<void>(L.top_lists), &lists);
   if (rc != MC_OK) return fail(rc);
+  s->lists_cands = lists;
   commit_pages(s, idx, fresh);
   for (int b : s->alive) s->cand_len[b]++;
   s->suffix_len = t + 1;
@@ -1005,11 +1024,15 @@ extern "C" int mc_sample(mc_session *s, int32_t n_cands, float temperature, int3
   MC_TRY(upload(s, s->ptr<void>(L.samp_u), uniforms, (size_t)n_cands * 4));
   const bool shared_row = s->logits_state == LOGITS_PREFIX;
   const float *lg = shared_row ? s->ptr<float>(L.prefix_logits) : s->ptr<float>(L.logits);
+  const int n_groups = c.vocab / 64;
+  const void *lists = shared_row ? (s->lists_prefix ? s->ptr<void>(L.top_lists_prefix) : nullptr)
+                                 : (s->lists_cands ? s->ptr<void>(L.top_lists) : nullptr);
   {
     ProfScope ps(s, MC_K_SAMPLE);
     MC_TRY(launch_sample(s->stream, n_cands, c.vocab, lg, shared_row ? 0 : (size_t)c.vocab,
                          temperature, top_k, s->ptr<float>(L.samp_u), s->ptr<int32_t>(L.samp_tok),
-                         out_topk_ids ? s->ptr<int32_t>(L.topk) : nullptr));
+                         out_topk_ids ? s->ptr<int32_t>(L.topk) : nullptr, lists,
+                         shared_row ? 0 : (size_t)n_groups * kTopPerGroup, n_groups));
   }
   s->sampled_on_device = true;
   fix_cands(s, n_cands);
@@ -1052,6 +1075,7 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
   MC_HIP(hipSetDevice(s->m->device));
   const SessionLayout &L = s->lay;
   const int pg = s->p.page_tokens;
+  s->lists_cands = false;                       // the candidates' logits rows are overwritten below
   MC_TRY(upload(s, s->ptr<void>(L.rw_ids), reward_ids, (size_t)n_reward * 4));
   MC_TRY(upload(s, s->ptr<void>(L.rw_vals), reward_values, (size_t)n_reward * 4));
   std::vector<int32_t> tok, pos, page, off, tab, last, table, items;
@@ -1132,6 +1156,7 @@ extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n
   for (int r = 0; r < old_n; ++r)
     if (!gone[s->alive[r]]) { keep_rows.push_back(r); new_alive.push_back(s->alive[r]); }
   const int new_n = (int)new_alive.size();
+  s->lists_cands = false;                       // rows move: the sampler reads whole rows until the next step
   // pending per-candidate results move up to the rows of the survivors (ascending, so a row is
   // never overwritten before it has been copied)
   if (s->logits_state == LOGITS_CANDS && s->logits_rows == old_n)
@@ -1206,6 +1231,7 @@ static int prefill_suffix_impl(mc_session *s, const int32_t *suffix_tokens, cons
     }
   }
   if (int rc0 = stage_pages(s, idx, fresh)) { unfix_cands(s, saved_n); return rc0; }
+  s->lists_cands = false;                       // this pass writes logits rows without top lists
   std::vector<int32_t> now(s->host_table);       // the table with the staged pages in place
   for (size_t i = 0; i < idx.size(); ++i) now[idx[i]] = fresh[i];
   std::vector<int32_t> tok, pos, page, off, tab, last, items;

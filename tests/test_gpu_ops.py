@@ -369,6 +369,78 @@ def test_sample_selection_paths(V, k, T, scale):
         check_sampler_on_logits(lg[b], T, k, us[b], toks[b], topk[b])
 
 
+def _top4_per_group(row):
+    """Reference for the LM head's lists: ids of the four largest of every 64 consecutive logits
+    under (value descending, id ascending)."""
+    g = row.reshape(-1, 64).astype(np.float64)
+    order = np.lexsort((np.broadcast_to(np.arange(64), g.shape), -g), axis=1)[:, :4]
+    return order + 64 * np.arange(g.shape[0])[:, None]
+
+
+@pytest.mark.parametrize("M,N,K", [(32, 65536, 256), (5, 131072, 512), (1, 65664, 256)])
+def test_lm_head_top_lists(M, N, K):
+    """The LM head's logits against the oracle's linear layer, and its per-group top lists against
+    a plain selection on the device's own logits (ids and values bit-exact, ties by lower id:
+    the weights are coarse so that equal logits are common)."""
+    a = rnd(270, (M, K)); w = np.round(rnd(271, (N, K), 0.05) * 64) / 64
+    ad, av = to_dev(a, "bf16"); wd, wv = to_dev(w, "bf16")
+    if M == 5:                                     # rows of few distinct values: many ties inside a group
+        av = np.sign(av); ad, av = to_dev(av, "bf16")
+    print("case: lm head lists", M, N, K, flush=True)
+    logits, lists = binding.op_lm_head(binding.op_pack_tiled(ad), binding.op_pack_tiled(wd), (M, N, K))
+    logits, lists = logits.cpu().numpy(), lists.cpu().numpy()
+    want = otf.linear(av, wv)
+    np.testing.assert_allclose(logits, want, rtol=0, atol=2e-5 * np.abs(want).max() + 1e-6)
+    for m in range(M):
+        ids = _top4_per_group(logits[m])
+        np.testing.assert_array_equal(lists[m, :, :, 1], ids)
+        np.testing.assert_array_equal(lists[m, :, :, 0].view(np.float32) + 0.0, logits[m][ids] + 0.0)
+
+
+def test_sample_with_top_lists():
+    """Sampling from the LM head's lists instead of whole rows, on rows built to order (one-hot
+    activations, so a row of logits is a row of bf16 weights, exactly): random rows at three
+    scales (bf16 values tie often), a row whose largest values all sit in one group of 64 (the lists
+    are inconclusive and the kernel must select from the whole row), a row of equal values, a row
+    where exactly four of the top k share a group.  Ids and top-k lists equal the oracle sampler's
+    on the device's logits for every temperature / k pair, with and without the lists in use."""
+    import torch
+    V, K, B = 65536, 256, 8
+    rng = np.random.default_rng(272)
+    rows = np.zeros((B, V), np.float32)
+    rows[0] = rng.standard_normal(V) * 1.28
+    rows[1] = rng.standard_normal(V) * 8.0
+    rows[2] = rng.standard_normal(V) * 0.05
+    rows[3] = rng.standard_normal(V); rows[3, 64 * 5: 64 * 5 + 40] += 9.0          # 40 of the top 50 in group 5
+    rows[4] = 0.5                                                                    # all equal
+    rows[5] = rng.standard_normal(V); rows[5, [700, 701, 702, 703]] = [9.0, 8.5, 8.0, 7.5]   # four of one group on top
+    rows[6] = np.round(rng.standard_normal(V) * 2) / 2                               # few distinct values
+    rows[7] = rng.standard_normal(V); rows[7, 64 * 900 + 3] = 30.0                   # one dominant id
+    rows_d, rows_v = to_dev(rows, "bf16")
+    a = np.zeros((B, K), np.float32); a[np.arange(B), np.arange(B)] = 1.0
+    w = np.zeros((V, K), np.float32); w[:, :B] = rows_v.T
+    ad, _ = to_dev(a, "bf16"); wd, _ = to_dev(w, "bf16")
+    logits, lists = binding.op_lm_head(binding.op_pack_tiled(ad), binding.op_pack_tiled(wd), (B, V, K))
+    lg = logits.cpu().numpy()
+    np.testing.assert_array_equal(lg, rows_v)
+    us = synth.uniforms(273, 1, (B,))
+    ud = torch.from_numpy(us).cuda()
+    for T, k in [(0.7, 50), (1.0, 64), (0.7, 65), (0.3, 2), (1.3, 5), (0.0, 50), (0.7, 1)]:
+        print("case: sample lists", T, k, flush=True)
+        toks, topk = binding.op_sample_lists(logits, lists, T, k, ud, want_topk=True)
+        toks, topk = toks.cpu().numpy(), topk.cpu().numpy()
+        for b in range(B):
+            check_sampler_on_logits(lg[b], T, k, us[b], toks[b], topk[b])
+        # the same ids as the whole-row sampler
+        t2, k2 = binding.op_sample(logits, T, k, ud, want_topk=True)
+        np.testing.assert_array_equal(topk, k2.cpu().numpy())
+        np.testing.assert_array_equal(toks, t2.cpu().numpy())
+    # every candidate reading row 0 of both
+    t3 = binding.op_sample_lists(logits, lists, 0.7, 50, ud, shared_row=True).cpu().numpy()
+    for b in range(B):
+        check_sampler_on_logits(lg[0], 0.7, 50, us[b], t3[b])
+
+
 def test_reward_score_op():
     import torch
     V, B, R = 128256, 64, 8
