@@ -170,6 +170,20 @@ int mc_prefill_suffix_ragged(mc_session *s, const int32_t *suffix_tokens, const 
  *    mc_session_reset_candidates starts over with all candidates. */
 int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n);
 
+/* 1e. A candidate that sits out some steps and goes on later (it waits for its execution feedback
+ *    while the others keep decoding, Sec. 3.3).  mc_pause_candidates takes the n candidates cands[.]
+ *    (each still decoding, at least one other must go on) out of the set that decodes, exactly as
+ *    mc_drop_candidates does (rows, KV traffic and per-candidate arrays shrink to the others, whose
+ *    pending results stay valid), but they keep their pages and suffix tokens.
+ *    mc_resume_candidates puts n paused candidates back, in ascending id order among the others,
+ *    each at its own suffix length (the candidates may then differ in length as after
+ *    mc_prefill_suffix_ragged).  Resuming renumbers the rows of the per-candidate arrays, so nothing
+ *    is pending afterwards: the next call is mc_decode_step with host tokens for every candidate
+ *    now decoding (or mc_prefill_suffix / mc_prefill_suffix_ragged).  mc_session_reset_candidates
+ *    forgets paused candidates too.  A paused candidate cannot be dropped or promoted; resume it first. */
+int mc_pause_candidates(mc_session *s, const int32_t *cands, int32_t n);
+int mc_resume_candidates(mc_session *s, const int32_t *cands, int32_t n);
+
 /* 2. One new token per candidate: appends its K/V to the candidate's current page
  *    and leaves logits [n_cands][vocab] on the device.  tokens: host [n_cands], or
  *    NULL to consume the tokens drawn by the latest mc_sample without leaving the

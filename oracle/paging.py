@@ -37,13 +37,15 @@ class PagePool:
     candidates that still have a token to append are visited in ascending order, and one whose
     own suffix length is a multiple of the page size takes the page at the head of the queue.  A
     candidate that is dropped gives its pages back to the tail of the queue (candidates in
-    ascending index, each one's pages in the order it took them).  Written event by event so
-    that a test can replay a call sequence."""
+    ascending index, each one's pages in the order it took them).  A candidate that pauses
+    keeps its pages and its length and takes no part in the appends until it resumes (back into
+    the ascending order).  Written event by event so that a test can replay a call sequence."""
 
     def __init__(self, n_cands: int, page_tokens: int, free_list):
         self.free = list(free_list)
         self.page_tokens = page_tokens
         self.alive = list(range(n_cands))
+        self.paused = []
         self.pages = {b: [] for b in range(n_cands)}
         self.lens = {b: 0 for b in range(n_cands)}
 
@@ -82,6 +84,17 @@ class PagePool:
             self.alive.remove(b)
             self.free.extend(self.pages[b])
             self.pages[b] = []
+
+    def pause(self, ids):
+        for b in sorted(ids):
+            self.alive.remove(b)
+            self.paused.append(b)
+
+    def resume(self, ids):
+        for b in sorted(ids):
+            self.paused.remove(b)
+            self.alive.append(b)
+        self.alive.sort()
 
     def table(self, b: int):
         return list(self.pages[b])

@@ -72,6 +72,8 @@ SIGNATURES = {
     "mc_prefill_suffix": (C.c_int, [_vp, _vp, _i32, _i32]),
     "mc_prefill_suffix_ragged": (C.c_int, [_vp, _vp, _vp, _i32, _i32]),
     "mc_drop_candidates": (C.c_int, [_vp, _vp, _i32]),
+    "mc_pause_candidates": (C.c_int, [_vp, _vp, _i32]),
+    "mc_resume_candidates": (C.c_int, [_vp, _vp, _i32]),
     "mc_reward_bin": (_i32, [C.c_double, _i32, _vp]),
     "mc_best_so_far": (C.c_int, [_vp, _vp, _i32, C.c_double, _vp]),
     "mc_value_targets": (C.c_int, [_vp, _i32, C.c_double, _vp, _vp]),
@@ -255,6 +257,14 @@ class Session:
     def drop_candidates(self, cands):
         c = np.ascontiguousarray(cands, dtype=np.int32)
         _check(load_library().mc_drop_candidates(self.handle, c.ctypes.data, c.shape[0]))
+
+    def pause_candidates(self, cands):
+        c = np.ascontiguousarray(cands, dtype=np.int32)
+        _check(load_library().mc_pause_candidates(self.handle, c.ctypes.data, c.shape[0]))
+
+    def resume_candidates(self, cands):
+        c = np.ascontiguousarray(cands, dtype=np.int32)
+        _check(load_library().mc_resume_candidates(self.handle, c.ctypes.data, c.shape[0]))
 
     def decode_step(self, tokens: Optional[np.ndarray], n_cands: Optional[int] = None):
         if tokens is None:

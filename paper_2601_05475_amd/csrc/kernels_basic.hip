@@ -50,6 +50,17 @@ __global__ void embed_kernel(int d, const int32_t *__restrict__ tok, const T *__
   const int r = blockIdx.x;
   const T *src = table + (size_t)tok[r] * d;
   float *dst = x + (size_t)r * d;
+  if (sizeof(T) == 2 && d % 8 == 0) {
+    // bf16 rows in 16-byte pieces (rows start on a multiple of 16 bytes: d % 8 == 0)
+    for (int i = 8 * threadIdx.x; i < d; i += 8 * blockDim.x) {
+      const uint4 e = *(const uint4 *)((const bf16_t *)src + i);
+      *(float4 *)(dst + i) = make_float4(bf16_to_f32((bf16_t)(e.x & 0xFFFF)), bf16_to_f32((bf16_t)(e.x >> 16)),
+                                         bf16_to_f32((bf16_t)(e.y & 0xFFFF)), bf16_to_f32((bf16_t)(e.y >> 16)));
+      *(float4 *)(dst + i + 4) = make_float4(bf16_to_f32((bf16_t)(e.z & 0xFFFF)), bf16_to_f32((bf16_t)(e.z >> 16)),
+                                             bf16_to_f32((bf16_t)(e.w & 0xFFFF)), bf16_to_f32((bf16_t)(e.w >> 16)));
+    }
+    return;
+  }
   for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = Cvt<T>::to_f32(src[i]);
 }
 

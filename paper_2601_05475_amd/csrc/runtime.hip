@@ -349,6 +349,8 @@ struct mc_session {
   // of every per-candidate buffer belongs to candidate alive[r]
   std::vector<int32_t> alive;
   bool dropped_any = false;
+  // candidates that sit out (mc_pause_candidates): they keep their pages and suffix tokens
+  std::vector<int32_t> paused;
   // suffix tokens held by every started candidate (by id).  suffix_len is the longest among the
   // candidates still decoding; ragged: they are not all that long (set by mc_prefill_suffix_ragged,
   // cleared when the survivors of a drop are level again)
@@ -430,11 +432,14 @@ static int download(mc_session *s, void *dst_host, const void *src_dev, size_t b
   return MC_OK;
 }
 
+// tok_src != nullptr: the tokens drawn on the device become the rows' tokens here as well
 __global__ void decode_rows_kernel(int B, int pos, int page_slot, int off, int table_stride,
                                    const int32_t *__restrict__ table, const int32_t *__restrict__ alive,
-                                   int32_t *row_pos, int32_t *row_page, int32_t *row_off, int32_t *row_tab) {
+                                   int32_t *row_pos, int32_t *row_page, int32_t *row_off, int32_t *row_tab,
+                                   const int32_t *__restrict__ tok_src, int32_t *row_tok) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  if (tok_src) row_tok[b] = tok_src[b];
   const int cand = alive ? alive[b] : b;
   row_pos[b] = pos;
   row_page[b] = table[(size_t)cand * table_stride + page_slot];
@@ -708,6 +713,7 @@ extern "C" int mc_session_reset_candidates(mc_session *s) {
   s->sampled_on_device = false;
   s->free_q.assign(s->free_list.begin(), s->free_list.end());
   s->alive.clear();
+  s->paused.clear();
   s->cand_len.clear();
   s->ragged = false;
   s->dropped_any = false;
@@ -934,9 +940,11 @@ static void commit_pages(mc_session *s, const std::vector<int32_t> &idx, const s
 __global__ void decode_rows_ragged_kernel(int B, int prefix_len, int pg, int table_stride,
                                           const int32_t *__restrict__ table, const int32_t *__restrict__ alive,
                                           const int32_t *__restrict__ cand_len, int32_t *row_pos,
-                                          int32_t *row_page, int32_t *row_off, int32_t *row_tab, int32_t *row_len) {
+                                          int32_t *row_page, int32_t *row_off, int32_t *row_tab, int32_t *row_len,
+                                          const int32_t *__restrict__ tok_src, int32_t *row_tok) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  if (tok_src) row_tok[b] = tok_src[b];
   const int cand = alive ? alive[b] : b;
   const int t = cand_len[cand];
   row_pos[b] = prefix_len + t;
@@ -969,22 +977,20 @@ extern "C" int mc_decode_step(mc_session *s, const int32_t *tokens, int32_t n_ca
   auto fail = [&](int code) { unfix_cands(s, saved_n); return code; };
   if (tokens) {
     if (int rc1 = upload(s, s->ptr<void>(L.row_tok), tokens, (size_t)n_cands * 4)) return fail(rc1);
-  } else if (hipMemcpyAsync(s->ptr<void>(L.row_tok), s->ptr<void>(L.samp_tok), (size_t)n_cands * 4,
-                            hipMemcpyDeviceToDevice, s->stream) != hipSuccess) {
-    set_error("copy of the sampled tokens failed");
-    return fail(MC_ERR_DEVICE);
   }
+  const int32_t *tok_src = tokens ? nullptr : s->ptr<int32_t>(L.samp_tok);      // copied by the row kernel below
   if (s->ragged) {
     if (int rc1 = upload(s, s->ptr<void>(L.cand_len), s->cand_len.data(), (size_t)s->n_cands * 4)) return fail(rc1);
     decode_rows_ragged_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
         n_cands, s->prefix_len, pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
         s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.cand_len), s->ptr<int32_t>(L.row_pos),
-        s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off), s->ptr<int32_t>(L.row_tab), s->ptr<int32_t>(L.row_len));
+        s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off), s->ptr<int32_t>(L.row_tab), s->ptr<int32_t>(L.row_len),
+        tok_src, s->ptr<int32_t>(L.row_tok));
   } else {
     decode_rows_kernel<<<(n_cands + 63) / 64, 64, 0, s->stream>>>(
         n_cands, s->prefix_len + t, t / pg, t % pg, L.pages_per_cand, s->ptr<int32_t>(L.page_table),
         s->dropped_any ? s->ptr<int32_t>(L.alive) : nullptr, s->ptr<int32_t>(L.row_pos), s->ptr<int32_t>(L.row_page), s->ptr<int32_t>(L.row_off),
-        s->ptr<int32_t>(L.row_tab));
+        s->ptr<int32_t>(L.row_tab), tok_src, s->ptr<int32_t>(L.row_tok));
   }
   if (hipGetLastError() != hipSuccess) {
     set_error("launch of the decode-row kernel failed");
@@ -1137,11 +1143,13 @@ extern "C" int mc_score_candidates(mc_session *s, const int32_t *suffix_tokens,
   return MC_OK;
 }
 
-extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n) {
+// Take the n candidates cands[.] out of the set that decodes.  release: their pages go back to
+// the pool (a drop); otherwise they keep pages and tokens and wait in `paused`.
+static int take_out(mc_session *s, const int32_t *cands, int32_t n, bool release, const char *who) {
   if (!s || !cands) MC_FAIL(MC_ERR_INVALID, "session / cands is NULL");
-  if (s->n_cands < 1) MC_FAIL(MC_ERR_STATE, "mc_drop_candidates: no candidates");
+  if (s->n_cands < 1) MC_FAIL(MC_ERR_STATE, "%s: no candidates", who);
   const int old_n = (int)s->alive.size();
-  if (n < 1 || n >= old_n) MC_FAIL(MC_ERR_INVALID, "n %d outside [1, %d): at least one candidate must stay", n, old_n);
+  if (n < 1 || n >= old_n) MC_FAIL(MC_ERR_INVALID, "n %d outside [1, %d): at least one candidate must go on decoding", n, old_n);
   std::vector<char> gone(s->n_cands, 0);
   for (int i = 0; i < n; ++i) {
     const int b = cands[i];
@@ -1171,17 +1179,55 @@ extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n
     MC_HIP(hipGetLastError());
   }
   MC_TRY(upload(s, s->ptr<void>(L.alive), new_alive.data(), (size_t)new_n * 4));
-  for (int b = 0; b < s->n_cands; ++b)
-    if (gone[b])
-      for (int p = 0; p < L.pages_per_cand; ++p) {
-        int32_t &id = s->host_table[(size_t)b * L.pages_per_cand + p];
-        if (id >= 0) s->free_q.push_back(id);
-        id = -1;
-      }
+  for (int b = 0; b < s->n_cands; ++b) {
+    if (!gone[b]) continue;
+    if (!release) { s->paused.push_back(b); continue; }
+    for (int p = 0; p < L.pages_per_cand; ++p) {
+      int32_t &id = s->host_table[(size_t)b * L.pages_per_cand + p];
+      if (id >= 0) s->free_q.push_back(id);
+      id = -1;
+    }
+  }
   s->alive = new_alive;
   s->dropped_any = true;
   refresh_lengths(s);
   if (s->logits_state == LOGITS_CANDS) s->logits_rows = new_n;
+  return MC_OK;
+}
+
+extern "C" int mc_drop_candidates(mc_session *s, const int32_t *cands, int32_t n) {
+  return take_out(s, cands, n, true, "mc_drop_candidates");
+}
+
+extern "C" int mc_pause_candidates(mc_session *s, const int32_t *cands, int32_t n) {
+  return take_out(s, cands, n, false, "mc_pause_candidates");
+}
+
+extern "C" int mc_resume_candidates(mc_session *s, const int32_t *cands, int32_t n) {
+  if (!s || !cands) MC_FAIL(MC_ERR_INVALID, "session / cands is NULL");
+  if (n < 1 || n > (int)s->paused.size()) MC_FAIL(MC_ERR_INVALID, "n %d outside [1, %d paused candidates]", n, (int)s->paused.size());
+  std::vector<int32_t> back(cands, cands + n);
+  std::sort(back.begin(), back.end());
+  for (int i = 0; i < n; ++i)
+    if ((i > 0 && back[i] == back[i - 1]) || std::find(s->paused.begin(), s->paused.end(), back[i]) == s->paused.end())
+      MC_FAIL(MC_ERR_INVALID, "candidate %d is not paused (or is repeated)", back[i]);
+  MC_HIP(hipSetDevice(s->m->device));
+  std::vector<int32_t> new_alive(s->alive);
+  new_alive.insert(new_alive.end(), back.begin(), back.end());
+  std::sort(new_alive.begin(), new_alive.end());
+  MC_TRY(upload(s, s->ptr<void>(s->lay.alive), new_alive.data(), new_alive.size() * 4));
+  for (int b : back) s->paused.erase(std::find(s->paused.begin(), s->paused.end(), b));
+  s->alive = new_alive;
+  s->dropped_any = true;
+  refresh_lengths(s);
+  // the rows of the per-candidate buffers are renumbered and the resumed candidates have none:
+  // nothing is pending any more
+  s->lists_cands = false;
+  s->sampled_on_device = false;
+  if (s->logits_state == LOGITS_CANDS || s->logits_state == LOGITS_SCORE) {
+    s->logits_state = LOGITS_NONE;
+    s->logits_rows = 0;
+  }
   return MC_OK;
 }
 
@@ -1304,10 +1350,13 @@ extern "C" int mc_debug_copy_logits(mc_session *s, float *out, int32_t n_rows) {
 
 extern "C" int mc_debug_page_table(mc_session *s, int32_t *out, int32_t *n_pages, int32_t max_pages) {
   if (!s || !out || !n_pages) MC_FAIL(MC_ERR_INVALID, "a pointer is NULL");
-  const int most = (s->suffix_len + s->p.page_tokens - 1) / s->p.page_tokens;
+  int longest = s->suffix_len;
+  for (int b : s->paused) longest = std::max(longest, s->cand_len[b]);
+  const int most = (longest + s->p.page_tokens - 1) / s->p.page_tokens;
   if (max_pages < most) MC_FAIL(MC_ERR_INVALID, "max_pages %d < %d pages held", max_pages, most);
   for (int b = 0; b < s->p.max_cands; ++b) {
-    const bool holds = std::find(s->alive.begin(), s->alive.end(), b) != s->alive.end();
+    const bool holds = std::find(s->alive.begin(), s->alive.end(), b) != s->alive.end() ||
+                       std::find(s->paused.begin(), s->paused.end(), b) != s->paused.end();
     const int held = holds ? (s->cand_len[b] + s->p.page_tokens - 1) / s->p.page_tokens : 0;
     n_pages[b] = held;
     for (int p = 0; p < max_pages; ++p)

@@ -822,3 +822,147 @@ def test_drop_candidates_with_tokens_pending_on_the_device(tiny):
     with pytest.raises(binding.McError):
         a.drop_candidates([1, 3])                                     # one candidate must stay
 
+
+
+# ---------------------------------------------------------------- candidates that sit out and come back
+@pytest.mark.parametrize("kw,dtype", [
+    (dict(L=2, d=128, Hq=4, Hkv=2, hd=32, F=200, V=1000, pg=4), "f32"),
+    (dict(L=2, d=256, Hq=4, Hkv=2, hd=64, F=512, V=1024, pg=64), "bf16"),
+])
+def test_pause_and_resume_candidates(kw, dtype):
+    """Candidates sit out some steps (keeping pages and tokens) and come back at their own length.
+    Every logits row of every candidate equals the oracle's for that candidate's own sequence; the
+    page table equals the reference pool's after the same events; pending results of the others
+    survive a pause; state errors are refused."""
+    s = small_shape("pause", kw["L"], kw["d"], kw["Hq"], kw["Hkv"], kw["hd"], kw["F"], kw["V"], dtype=dtype)
+    w = synth.make_weights(s, 84)
+    pg = kw["pg"]
+    P, B, N = 50, 5, 2 * pg + 9
+    prefix = synth.tokens(12, 1, (P,), s.vocab)
+    suffix = synth.tokens(12, 2, (B, N), s.vocab)
+    print("case: pause / resume", kw, dtype, flush=True)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P, B, N, pg)
+    sess.prefill_shared(prefix)
+    pool = opaging.PagePool(B, pg, range(sess.pool_pages()))
+    alive, fed = list(range(B)), [0] * B            # tokens each candidate has consumed
+    rows_of = {b: [] for b in range(B)}
+
+    def step():
+        sess.decode_step(np.array([suffix[b, fed[b]] for b in alive], np.int32))
+        pool.append(1)
+        lg = sess.logits(len(alive))
+        for i, b in enumerate(alive):
+            fed[b] += 1
+            rows_of[b].append(lg[i])
+        return lg
+
+    # events: (steps to run first, "pause" / "resume", ids)
+    events = [(3, "pause", [1, 3]), (pg, "resume", [3]), (2, "pause", [0]), (pg - 1, "resume", [0, 1]), (4, None, None)]
+    for n_steps, what, ids in events:
+        for _ in range(n_steps):
+            lg = step()
+        if what == "pause":
+            before = sess.logits(len(alive))
+            sess.pause_candidates(ids); pool.pause(ids)
+            keep = [i for i, b in enumerate(alive) if b not in ids]
+            alive = [b for b in alive if b not in ids]
+            np.testing.assert_array_equal(sess.logits(len(alive)), before[keep])     # the others' pending rows moved up
+            for call in (lambda: sess.pause_candidates(ids[:1]), lambda: sess.drop_candidates(ids[:1]),
+                         lambda: sess.promote_candidate(ids[0]), lambda: sess.resume_candidates([alive[0]])):
+                with pytest.raises(binding.McError):
+                    call()
+        elif what == "resume":
+            sess.resume_candidates(ids); pool.resume(ids)
+            alive = sorted(alive + ids)
+            with pytest.raises(binding.McError) as e:      # nothing is pending after a resume
+                sess.sample(len(alive), 0.8, 50, np.zeros(len(alive), np.float32))
+            assert e.value.code == -2
+            with pytest.raises(binding.McError):
+                sess.decode_step(None, len(alive))
+    assert sorted(alive) == list(range(B)) and len(set(fed)) > 1
+    want_pl, want = oracle_shared(s, w, prefix, suffix)              # [N, B, V]
+    fl = oracle_shared(s, w, prefix, suffix, exact=False)[1] if dtype == "bf16" else None
+    for b in range(B):
+        assert len(rows_of[b]) == fed[b]
+        assert_logits_close(np.stack(rows_of[b]), want[:fed[b], b], dtype, f"pause / resume, candidate {b}: {fed[b]} steps",
+                            None if fl is None else fl[:fed[b], b])
+    tab, n = sess.page_table()
+    for b in range(B):
+        held = -(-fed[b] // pg)
+        assert int(n[b]) == held and tab[b, :held].tolist() == pool.table(b)
+    # a reset forgets the paused ones as well
+    sess.pause_candidates([2])
+    sess.reset_candidates()
+    with pytest.raises(binding.McError):
+        sess.resume_candidates([2])
+
+
+def test_oversample_then_filter_by_reward_score():
+    """The search loop's call sequence on one session (Sec. 3.3, value-guided search: expand many,
+    keep the promising): start 8 candidates, decode a stretch free-running, score what each has
+    written so far with mc_score_candidates, drop the four lowest-ranked, decode on, promote the
+    best survivor into the shared prefix and start a new round.  Scoring must leave the decode
+    state alone, the ranks must be the oracle's ranking of the device scores, and every logits row
+    must equal the oracle's on that candidate's own (sampled) sequence."""
+    wl = synth.WORKLOADS["tiny"]
+    s = wl.shape
+    w = synth.make_weights(s, wl.seed_weights)
+    P, B, N1, N2 = 40, 8, 6, 5
+    prefix = synth.prefix_tokens(wl, P)
+    us = synth.step_uniforms(wl, B, N1 + N2 + 1)
+    model = binding.Model(s, w)
+    sess = binding.Session(model, P + N1 + N2, B, N1 + N2, 4)
+    sess.prefill_shared(prefix)
+    seqs = [[] for _ in range(B)]
+    rows = [[] for _ in range(B)]
+    alive = list(range(B))
+
+    def run(n, t0):
+        for t in range(n):
+            toks = sess.sample(len(alive), wl.temperature, wl.top_k, us[t0 + t][:len(alive)])
+            sess.decode_step(None, len(alive))
+            lg = sess.logits(len(alive))
+            for i, b in enumerate(alive):
+                seqs[b].append(int(toks[i]))
+                rows[b].append(lg[i])
+
+    run(N1, 0)
+    ids = synth.reward_token_ids(wl, 5)
+    vals = np.arange(5, dtype=np.float32)
+    so_far = np.array([seqs[b] for b in alive], np.int32)
+    pending = sess.logits(len(alive))
+    lp, sc, rk = sess.score_candidates(so_far, [N1] * B, ids, vals, 0.7)
+    assert list(rk) == list(osamp.rank(sc))
+    worst = [alive[i] for i in rk[B // 2:]]
+    # scoring overwrote the pending logits buffer: the next sample needs a decode step first; the
+    # decode state itself is untouched, so feeding the last sampled tokens again is not needed:
+    # drop the losers, then go on from host tokens
+    sess.drop_candidates(sorted(worst))
+    alive = [b for b in alive if b not in worst]
+    nxt = np.array([osamp.sample(pending[list(range(B)).index(b)], wl.temperature, wl.top_k, float(us[N1][i]))[0]
+                    for i, b in enumerate(alive)], np.int32)
+    sess.decode_step(nxt)
+    lg = sess.logits(len(alive))
+    for i, b in enumerate(alive):
+        seqs[b].append(int(nxt[i])); rows[b].append(lg[i])
+    run(N2 - 1, N1 + 1)
+    # every row against the oracle on the candidate's own sequence
+    cfg = oracle_config(s)
+    plog, pcache = otf.forward(cfg, w, prefix)
+    for b in range(B):
+        want = otf.forward(cfg, w, np.array(seqs[b]), pcache.copy())[0]
+        assert_logits_close(np.stack(rows[b]), want, "f32", f"oversample / filter, candidate {b}")
+    # the reward read-out of the scored stretch against the oracle
+    for i in range(B):
+        want_lp = osamp.reward_logprobs(otf.forward(cfg, w, so_far[i], pcache.copy())[0][-1], ids)
+        np.testing.assert_allclose(lp[i], want_lp, rtol=0, atol=1e-4)
+    best = alive[0]
+    sess.promote_candidate(best)
+    grown = np.concatenate([prefix, np.array(seqs[best], np.int32)])
+    sess.decode_step(np.array([1, 2, 3], np.int32))
+    want = otf.forward(cfg, w, grown)[1]
+    got = sess.logits(3)
+    for i, tok in enumerate([1, 2, 3]):
+        ref = otf.forward(cfg, w, np.array([tok]), want.copy())[0][0]
+        assert_logits_close(got[i][None], ref[None], "f32", "new round on the promoted prefix")

@@ -449,3 +449,27 @@ def test_logits_parity_statistics_see_mistakes_the_widened_bound_accepts(monkeyp
         with pytest.raises(AssertionError):
             gpu_common.assert_logits_close(wrong, exact, "bf16", name, floor=floor)
     del gpu_common.PARITY_RECORDS[:]
+
+
+def test_page_pool_pause_and_resume_by_hand():
+    """Three candidates, pages of 2, free queue 10, 11, 12, ...: worked by hand.  Step 1: all take
+    a page (10, 11, 12).  Candidate 1 pauses.  Steps 2-3: at step 3 candidates 0 and 2 reach a page
+    boundary and take 13, 14; candidate 1 keeps page 11 and length 1.  Candidate 1 resumes; step 4:
+    it fills its first page (no new page), 0 and 2 fill their second.  Step 5: candidate 0 takes 15,
+    candidate 1 (length 2) takes 16, candidate 2 takes 17: ascending order, the resumed one in its
+    place.  Dropping the paused candidate 2 later returns its pages in the order it took them."""
+    pool = paging.PagePool(3, 2, range(10, 30))
+    pool.append(1)
+    pool.pause([1])
+    pool.append(2)
+    assert pool.table(0) == [10, 13] and pool.table(1) == [11] and pool.table(2) == [12, 14]
+    assert pool.lens == {0: 3, 1: 1, 2: 3}
+    pool.resume([1])
+    pool.append(1)
+    assert pool.table(1) == [11] and pool.lens[1] == 2
+    pool.append(1)
+    assert pool.table(0) == [10, 13, 15] and pool.table(1) == [11, 16] and pool.table(2) == [12, 14, 17]
+    pool.pause([2])
+    pool.resume([2])
+    pool.drop([2])
+    assert pool.free[-3:] == [12, 14, 17] and pool.alive == [0, 1]
