@@ -33,17 +33,17 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115742.2, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115742.1, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "7cfbe178efc61816ff285b7ce09cd98b0f344b10f3be73ef01922dfcf001c86c"}
+                   "sha256": "e158f6e7bc1096797c8c25612d81c80c027cf6481e1f2a18f62380d9e5e4cffe"}
 
 
-# Decode attention + merge at suffix lengths 255..258 (bench.py --steps 4 --warmup 1 --suffix-start 254
-# under the same two counter runs): the average suffix length of the 512-step workload is 256.5.
-TRAFFIC_ATTN = {"fetch_kib": 27088.4, "merge_fetch_kib": 2614.0, "write_kib": 4680.0, "merge_write_kib": 256.0,
+# Decode attention + merge at suffix lengths 255..258 (the same two counter runs: four timed steps
+# sit at the middle of the 512-step workload, whose average suffix length is 256.5).
+TRAFFIC_ATTN = {"fetch_kib": 26411.0, "merge_fetch_kib": 2913.5, "write_kib": 4680.0, "merge_write_kib": 256.0,
                 "fetch_scale": 2.0, "write_scale": 1.0, "suffix_len": 256.5,
                 "source": "paper_2601_05475_amd/csrc/kernels_attn.hip",
-                "sha256": "9c2a5acbf21e4424cdbe545b0624d41f8f94760575e01330a96f3738dea3a666"}
+                "sha256": "0dcce61a42f42cd933bf3c56bfa23fb8d340520a82f740cee10bc7d0c6f7b480"}
 
 
 def measured_attention_traffic_bytes(workload, mean_suffix_len):
@@ -339,6 +339,9 @@ def main():
                     help="decode workloads: write this many tokens per candidate in one untimed pass before the "
                          "steps (default: (workload steps - timed steps) / 2, which centres the timed steps on "
                          "the workload's mean suffix length)")
+    ap.add_argument("--prefix-splits", type=int, default=0,
+                    help="decode attention: key-axis splits of the shared prefix (0 = the library's plan; "
+                         "diagnosis only, marks the line invalid)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain elementwise copy of 256 MiB (a kernel of known traffic "
                          "that hardware-counter readings are scaled by)")
@@ -378,6 +381,8 @@ def main():
     t0 = time.perf_counter()
     model = binding.Model(s, weights)
     sess = binding.Session(model, P, B, N, wl.page_tokens, chunk_rows=args.chunk_rows or 4096)
+    if args.prefix_splits:
+        sess.set_prefix_splits(args.prefix_splits)
     torch.cuda.synchronize()
     t_upload = time.perf_counter() - t0
 
@@ -482,6 +487,8 @@ def main():
     }
     if args.layers:
         out["invalid"] = "layer count overridden"
+    if args.prefix_splits:
+        out["invalid"] = "prefix splits overridden"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, weights)
     print(json.dumps(out))
