@@ -334,9 +334,12 @@ __global__ __launch_bounds__(HD) void decode_attention_merge_kernel(
     float v[16];
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
-      const int pp = p < n_parts ? p : 0;
-      ml[p] = *(const float2 *)(part_ml + (pp * stride + bh) * 2);
-      v[p] = part_o[(pp * stride + bh) * HD + d];
+      ml[p] = make_float2(-INFINITY, 0.f);
+      v[p] = 0.f;
+      if (p < n_parts) {                           // uniform: the loads of the parts that exist go out back to back
+        ml[p] = *(const float2 *)(part_ml + (p * stride + bh) * 2);
+        v[p] = part_o[(p * stride + bh) * HD + d];
+      }
     }
     float M = -INFINITY;
 #pragma unroll
