@@ -301,6 +301,115 @@ __global__ __launch_bounds__(256) void skinny_linear_kernel(
 }
 
 // =====================================================================================
+// The one-split fused layers (gate/up + SwiGLU, QKV + rotary) in row-range form, for up to 32
+// activation rows.  With one workgroup per 32-row weight tile the 8B gate/up layer has 448
+// workgroups for 256 compute units: 192 units hold two and 64 hold one, and since a unit pulls
+// no more than its share of the HBM rate the layer takes as long as the units with two (measured:
+// the others idle from 22 us on, the layer ends at 40 us); the QKV layer has 192 workgroups and
+// leaves 64 units empty.  Here every one of gridDim.x workgroups takes the same number of weight
+// rows, R = N / gridDim.x (a multiple of 8: an output quad group of the MFMA layout), over the
+// whole K range, wherever they fall in the 32-row tiles.  The MFMA does not care which weight rows
+// sit in its operand (result row i depends on operand row i only), so a workgroup treats its
+// range as NB blocks of 32 consecutive rows: lane (row nl, half h) of block b fetches row
+// r0 + 32 b + nl from whatever tile holds it; lanes past the range read its last row (a valid
+// address, no bytes fetched for a neighbour's rows) and their results are never stored.  The
+// four waves split K and meet in LDS as in the form above.
+// =====================================================================================
+template <int NB, int MODE, bool ROPE>
+__global__ __launch_bounds__(256) void skinny_rows_kernel(
+    int M, int N, int K, int rows_per_wg, const bf16_t *__restrict__ a, const bf16_t *__restrict__ w,
+    const bf16_t *__restrict__ w2, bf16_t *__restrict__ out_t, RopeOut ro) {
+  constexpr bool SWIGLU = MODE == SKINNY_SWIGLU;
+  constexpr int NW = SWIGLU ? 2 : 1;
+  extern __shared__ float4 red_rows[];                        // [4 waves][NB][NW][4 quads][64 lanes]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, nl = lane & 31, h = lane >> 5;
+  const int r0 = blockIdx.x * rows_per_wg, r1 = r0 + rows_per_wg;
+  const int U = K >> 6, units_per_wave = U >> 2, u0 = wave * units_per_wave;
+  const bf16_t *wp[NB], *up[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int row = min(r0 + 32 * b + nl, r1 - 1);
+    const size_t off = ((size_t)(row >> 5) * U + u0) * 2048 + (size_t)(32 * h + (row & 31)) * 8;
+    wp[b] = w + off;
+    up[b] = NW == 2 ? w2 + off : nullptr;
+  }
+  const bf16_t *ap = a + (size_t)u0 * 2048 + lane * 8;
+  f32x16 acc[NB][NW];
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int i = 0; i < NW; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[b][i][r] = 0.f;
+
+  v4u wf[2][NB][4], uf[2][NB][4], af[2][4];
+  auto issue = [&](int slot, int u) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        wf[slot][b][c] = load_stream(wp[b] + (size_t)u * 2048 + c * 512);
+        if (NW == 2) uf[slot][b][c] = load_stream(up[b] + (size_t)u * 2048 + c * 512);
+      }
+      af[slot][c] = *(const v4u *)(ap + (size_t)u * 2048 + c * 512);
+    }
+  };
+  auto compute = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int b = 0; b < NB; ++b) {
+        acc[b][0] = mfma32(wf[slot][b][c], af[slot][c], acc[b][0]);
+        if (NW == 2) acc[b][NW - 1] = mfma32(uf[slot][b][c], af[slot][c], acc[b][NW - 1]);
+      }
+  };
+  issue(0, 0);
+  int u = 0;
+  for (; u + 2 <= units_per_wave; u += 2) {
+    issue(1, u + 1);
+    compute(0);
+    if (u + 2 < units_per_wave) issue(0, u + 2);
+    compute(1);
+  }
+  if (u < units_per_wave) compute(0);
+
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+#pragma unroll
+    for (int i = 0; i < NW; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        red_rows[((((wave * NB + b) * NW + i) * 4 + r4) << 6) + lane] =
+            make_float4(acc[b][i][4 * r4], acc[b][i][4 * r4 + 1], acc[b][i][4 * r4 + 2], acc[b][i][4 * r4 + 3]);
+  __syncthreads();
+  // thread (r4 = wave, lane) adds the four waves' quads of every block in a fixed order and
+  // stores the 4 outputs of activation row m = nl if their weight rows lie in the range
+  const int r4 = wave, m = nl;
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int n = r0 + 32 * b + 8 * r4 + 4 * h;
+    if (n >= r1 || m >= M) continue;
+    float4 s[NW];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+      s[i] = red_rows[((((0 * NB + b) * NW + i) * 4 + r4) << 6) + lane];
+#pragma unroll
+      for (int sw = 1; sw < 4; ++sw) {
+        const float4 t = red_rows[((((sw * NB + b) * NW + i) * 4 + r4) << 6) + lane];
+        s[i].x += t.x; s[i].y += t.y; s[i].z += t.z; s[i].w += t.w;
+      }
+    }
+    if (SWIGLU) {
+      *(uint2 *)(out_t + tiled_offset(m, n, N)) =
+          pack4_bf16(silu_f(s[0].x) * s[NW - 1].x, silu_f(s[0].y) * s[NW - 1].y,
+                     silu_f(s[0].z) * s[NW - 1].z, silu_f(s[0].w) * s[NW - 1].w);
+    } else if (ROPE) {
+      rope_store_quad(ro, m, n, s[0], rope_load_quad(ro, m, n));
+    }
+  }
+}
+
+// =====================================================================================
 // The same layer for 33..64 rows (two 32-row activation tiles).  In the form above every wave
 // fetches its own activation units, and with two tiles per weight tile that is as many bytes
 // from L2 as the weights bring from HBM (twice as many in the plain form), all of them addressed
@@ -454,6 +563,17 @@ static bool skinny_pair_form(int N, int n_splits, bool rope, bool swiglu) {
   return !rope && !swiglu && n_splits == 1 && (N / 32) % 2 == 0 && N / 32 >= 2048;
 }
 
+// Rows per workgroup of the row-range form, or 0 where it does not apply: one of the two fused
+// one-split layers, up to 32 activation rows, a row count that splits into equal multiples of 8
+// over the chip's 256 compute units, and a tile count that does not already do so.
+static int skinny_rows_per_wg(int M, int N, int n_splits, bool rope, bool swiglu) {
+  constexpr int kComputeUnits = 256;
+  if (M > 32 || n_splits != 1 || rope == swiglu) return 0;
+  if (N % (8 * kComputeUnits) || (N / 32) % kComputeUnits == 0) return 0;
+  const int R = N / kComputeUnits;
+  return R <= 64 ? R : 0;                                     // at most two 32-row blocks
+}
+
 bool skinny_top_lists_supported(int M, int N, int K) {
   return skinny_linear_supported(M, N, K) && N % 64 == 0 && skinny_pair_form(N, 1, false, false) &&
          !skinny_shared_form(M, N, 1, false);
@@ -472,6 +592,26 @@ int launch_linear_skinny(hipStream_t st, int M, int N, int K, const void *a, con
   const RopeOut none{};
   if (top_out && !(n_splits == 1 && !rope && !w2 && skinny_top_lists_supported(M, N, K)))
     MC_FAIL(MC_ERR_UNSUPPORTED, "per-group top lists: M=%d N=%d K=%d not covered", M, N, K);
+  if (const int R = skinny_rows_per_wg(M, N, n_splits, rope != nullptr, w2 != nullptr)) {
+    const LaunchEvents ev3 = take_launch_events();
+    auto go3 = [&](auto kernel, int n_blocks, int n_w, const RopeOut &ro) -> int {
+      const int lds = 4 * n_blocks * n_w * 4 * 64 * (int)sizeof(float4);
+      MC_TRY(raise_dynamic_lds_limit((const void *)kernel, lds));
+      if (ev3.start || ev3.stop)
+        hipExtLaunchKernelGGL(kernel, dim3(N / R), dim3(256), lds, st, ev3.start, ev3.stop, 0, M, N, K, R,
+                              (const bf16_t *)a, (const bf16_t *)w, (const bf16_t *)w2, (bf16_t *)out_t, ro);
+      else
+        kernel<<<dim3(N / R), 256, lds, st>>>(M, N, K, R, (const bf16_t *)a, (const bf16_t *)w,
+                                              (const bf16_t *)w2, (bf16_t *)out_t, ro);
+      return MC_OK;
+    };
+    if (w2 && R > 32) MC_TRY(go3(skinny_rows_kernel<2, SKINNY_SWIGLU, false>, 2, 2, none));
+    else if (w2) MC_TRY(go3(skinny_rows_kernel<1, SKINNY_SWIGLU, false>, 1, 2, none));
+    else if (R > 32) MC_TRY(go3(skinny_rows_kernel<2, SKINNY_PLAIN, true>, 2, 1, *rope));
+    else MC_TRY(go3(skinny_rows_kernel<1, SKINNY_PLAIN, true>, 1, 1, *rope));
+    MC_HIP(hipGetLastError());
+    return MC_OK;
+  }
   if (skinny_shared_form(M, N, n_splits, rope != nullptr)) {
     const int groups = (N / 32 + 3) / 4;
     const dim3 grid2((groups + 7) / 8 * 8, n_splits);

@@ -518,6 +518,9 @@ def test_linear_accumulate_tiled(M, N, K):
     (6200, 12, 2, 128, 256),       # N = 2048
     (100, 4, 2, 64, 256),          # one ragged row tile, N = 512
     (300, 5, 1, 128, 512),         # N = 896: an odd number of 128-column workgroups
+    (19, 32, 8, 128, 256),         # few rows, N = 6144: the row-range form, 24 weight rows per workgroup
+    (32, 12, 2, 128, 512),         # N = 2048: 8 rows per workgroup
+    (5, 64, 8, 128, 256),          # N = 10240: 40 rows per workgroup (ranges that end on a tile edge and inside one)
 ])
 def test_linear_qkv_rope_fused(rows, Hq, Hkv, hd, K):
     """QKV projection + rotation + query / key / value stores in one kernel, against the oracle's
@@ -556,7 +559,9 @@ def test_linear_qkv_rope_fused(rows, Hq, Hkv, hd, K):
 
 @pytest.mark.parametrize("M,N,K", [(32, 256, 512), (7, 14336, 4096), (64, 128, 256), (150, 256, 512),
                                    (3000, 2048, 512), (2070, 2944, 256), (65, 384, 256),
-                                   (50, 27648, 512), (64, 20480, 256)])
+                                   (50, 27648, 512), (64, 20480, 256),
+                                   # the row-range form: 56, 24, 8 and 48 weight rows per workgroup
+                                   (32, 14336, 256), (17, 6144, 512), (1, 2048, 256), (30, 12288, 256)])
 def test_linear_swiglu_tiled(M, N, K):
     a = rnd(62, (M, K)); wg = rnd(63, (N, K), 0.05); wu = rnd(64, (N, K), 0.05)
     ad, av = to_dev(a, "bf16"); gd, gv = to_dev(wg, "bf16"); ud, uv = to_dev(wu, "bf16")
