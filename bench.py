@@ -33,17 +33,17 @@ MFMA_PEAK_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # HBM traffic of one gate/up launch from the FETCH_SIZE / WRITE_SIZE counter runs (KiB per
 # dispatch, scaled by what the same counters read for a plain copy of known size; see
 # profiles/decode_8b_traffic_counters.md).  Valid for the kernel source with this hash only.
-TRAFFIC_GATE_UP = {"fetch_kib": 115742.1, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
+TRAFFIC_GATE_UP = {"fetch_kib": 115760.5, "fetch_scale": 2.0, "write_kib": 896.0, "write_scale": 1.0,
                    "source": "paper_2601_05475_amd/csrc/kernels_mfma.hip",
-                   "sha256": "e158f6e7bc1096797c8c25612d81c80c027cf6481e1f2a18f62380d9e5e4cffe"}
+                   "sha256": "195b3cd0cc63be24d006182355f7596e3582871f57e80ab923bcf591f9c5ba36"}
 
 
 # Decode attention + merge at suffix lengths 255..258 (the same two counter runs: four timed steps
 # sit at the middle of the 512-step workload, whose average suffix length is 256.5).
-TRAFFIC_ATTN = {"fetch_kib": 26411.0, "merge_fetch_kib": 2913.5, "write_kib": 4680.0, "merge_write_kib": 256.0,
+TRAFFIC_ATTN = {"fetch_kib": 26415.3, "merge_fetch_kib": 2922.0, "write_kib": 4680.0, "merge_write_kib": 256.0,
                 "fetch_scale": 2.0, "write_scale": 1.0, "suffix_len": 256.5,
                 "source": "paper_2601_05475_amd/csrc/kernels_attn.hip",
-                "sha256": "0dcce61a42f42cd933bf3c56bfa23fb8d340520a82f740cee10bc7d0c6f7b480"}
+                "sha256": "dc1b725c64c5750a4ef5366513ffff40b14a2a21651112351262a079835711f2"}
 
 
 def measured_attention_traffic_bytes(workload, mean_suffix_len):
@@ -463,7 +463,7 @@ def main():
                                f"{S0 + 1}..{S0 + K} (mean {mean_len:g}; the workload's mean is {(N + 1) / 2:g}), "
                                f"T={wl.temperature}, top-k {wl.top_k}",
                    "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens, "suffix_start": S0},
-        "roofline": {"bound": "hbm", "kernel": "skinny_linear_kernel (gate/up + SwiGLU)",
+        "roofline": {"bound": "hbm", "kernel": "skinny_rows_kernel (gate/up + SwiGLU)",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
                      "peak_measured": read_gbs, "frac_of_measured": gu_gbs / read_gbs,
                      "traffic": measured_traffic_bytes(args.workload), "algorithmic_bytes": gate_up_bytes(s, B),
