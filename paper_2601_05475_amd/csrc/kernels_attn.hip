@@ -252,8 +252,8 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
 
   // ---- epilogue: the four waves hold four partial states of the same columns; merge in LDS
   __syncthreads();                                      // the query fragments are no longer read
-  float *sm = (float *)lds_raw;                         // [4][32] m, then [4][32] l
-  float *so = sm + 256;                                 // [4][n_cols][SOLD]
+  float *sm = (float *)lds_raw;                         // [4][32] m, [4][32] l, [32] merged m, [32] merged l
+  float *so = sm + 320;                                 // [4][n_cols][SOLD]
   if (h == 0) {
     sm[wave * 32 + col] = m;
     sm[128 + wave * 32 + col] = l;
@@ -264,6 +264,16 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   for (int w = 1; w < 4; ++w) mm = fmaxf(mm, sm[w * 32 + col]);
   // a wave that saw no key has m = -inf and contributes nothing
   const float f = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mm);
+  if (wave == 0 && h == 0) {                            // the column's merged maximum and sum, once
+    float lg = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = sm[w * 32 + col];
+      lg += (mw == -INFINITY) ? 0.f : sm[128 + w * 32 + col] * __builtin_amdgcn_exp2f(mw - mm);
+    }
+    sm[256 + col] = mm;
+    sm[288 + col] = lg;
+  }
   if (col_valid) {
     float *dst = so + (size_t)(wave * n_cols + col) * SOLD + 4 * h;
 #pragma unroll
@@ -275,7 +285,12 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   }
   __syncthreads();
   const int wstride = n_cols * SOLD;
-  for (int e = tid; e < n_cols * (HD / 4); e += 256) {
+  // 32 columns x HD / 4 quads at most: a fixed number of rounds, so that the LDS reads of all of
+  // them are in flight together
+#pragma unroll
+  for (int i = 0; i < HD / 32; ++i) {
+    const int e = tid + 256 * i;
+    if (e >= n_cols * (HD / 4)) continue;
     const int c = e / (HD / 4), d = (e % (HD / 4)) * 4;
     const float *p0 = so + c * SOLD + d;
     float4 v = *(const float4 *)p0;
@@ -287,18 +302,9 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     const int rc = col0 + c;
     const int bc = (b_item >= 0) ? b_item : rc / G;
     const int hq = kvh * G + rc % G;
-    float mg = sm[c], lg = 0.f;
-    if (d == 0 || n_parts == 1) {
-#pragma unroll
-      for (int w = 1; w < 4; ++w) mg = fmaxf(mg, sm[w * 32 + c]);
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float mw = sm[w * 32 + c];
-        lg += (mw == -INFINITY) ? 0.f : sm[128 + w * 32 + c] * __builtin_amdgcn_exp2f(mw - mg);
-      }
-    }
     if (n_parts == 1) {
       // the only partial state of its (candidate, head): normalise and store the output here
+      const float lg = sm[288 + c];
       const size_t at = a.out_tiled ? tiled_offset(bc, hq * HD + d, Hq * HD) : ((size_t)bc * Hq + hq) * HD + d;
       uint2 pk;
       pk.x = pack2_bf16(v.x / lg, v.y / lg);
@@ -308,10 +314,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     }
     const size_t row = ((size_t)part * B + bc) * Hq + hq;
     *(float4 *)(part_o + row * HD + d) = v;
-    if (d == 0) {
-      part_ml[row * 2] = mg;
-      part_ml[row * 2 + 1] = lg;
-    }
+    if (d == 0) *(float2 *)(part_ml + row * 2) = make_float2(sm[256 + c], sm[288 + c]);
   }
 }
 
@@ -455,7 +458,7 @@ static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, co
   const int G = a.n_q_heads / a.n_kv_heads;
   // query fragments of four waves, later reused by the suffix items' merge
   const int max_cols = (a.prefix_len > 0) ? std::min(32, a.n_cands * G) : G;
-  const size_t lds = std::max((size_t)4 * (HD / 16) * 1024, (size_t)(256 + 4 * max_cols * (HD + 4)) * sizeof(float));
+  const size_t lds = std::max((size_t)4 * (HD / 16) * 1024, (size_t)(320 + 4 * max_cols * (HD + 4)) * sizeof(float));
   const AttnItems &it = it_in;
   MC_TRY(raise_dynamic_lds_limit((const void *)decode_attention_kernel<HD>, 160 * 1024 - 1024));
   // events offered by a profiling scope: begin of the first kernel, end of the last
