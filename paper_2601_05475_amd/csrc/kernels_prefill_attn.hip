@@ -7,8 +7,9 @@
 // with eight waves per CU.
 // Keys are streamed page by page (64 keys) through LDS and shared by the four waves: first the
 // shared-prefix pages that are visible to the block, then (scoring) the sequence's own suffix
-// pages.  Pages are stored in MFMA fragment order, so a page is copied to LDS as it is and an
-// operand is one conflict-free 16-byte read per lane.  Each item sees all keys of its rows, so
+// pages.  Pages are stored in MFMA fragment order, so a page is copied to LDS as it is (by
+// loads that write LDS directly, two pages ahead, three buffers) and an operand is one
+// conflict-free 16-byte read per lane.  Each item sees all keys of its rows, so
 // it normalises and writes bf16 itself.  Operand mapping and the softmax scheme are those of
 // the decode kernel (transposed scores, lazy base-2 reference maximum); the addition is the
 // causal mask, applied only to blocks that reach past the first position of the item.
@@ -38,7 +39,7 @@ constexpr int PPG = 64;                       // keys per page
 template <int HD> struct PTile {
   static constexpr int K_ELEMS = PPG * HD, V_ELEMS = PPG * HD, PAGE_ELEMS = K_ELEMS + V_ELEMS;
   static constexpr int NF = HD / 16;          // 1 KB fragments per 32-key block (K and V alike)
-  static constexpr int LDS_BYTES = 2 * PAGE_ELEMS * 2;
+  static constexpr int LDS_BYTES = 3 * PAGE_ELEMS * 2;      // three page buffers
   static constexpr int CPT = PPG * HD / 8 / 512;
 };
 
@@ -103,9 +104,12 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
   const size_t page_stride = (size_t)Hkv * PPG * HD, head_off = (size_t)kvh * PPG * HD;
   const bf16_t *kA = (const bf16_t *)a.k_prefix, *vA = (const bf16_t *)a.v_prefix;
   const bf16_t *kB = (const bf16_t *)a.k_suffix, *vB = (const bf16_t *)a.v_suffix;
-  v4u sk[3][TL::CPT], sv[3][TL::CPT];
-  // same number of loads whether or not the page exists (see the decode kernel)
-  auto issue = [&](int stage, int pi) __attribute__((always_inline)) {
+  // Pages go from global memory straight into LDS (lane i of a wave-wide 16-byte load lands at
+  // the wave's base + 16 i: the page is copied as it is), two pages ahead of the one in use, into
+  // three buffers.  The same number of loads is issued whether or not the page exists (a page
+  // past the end re-reads 16 bytes of page 0 into a buffer nobody reads), so the wait before the
+  // barrier can count: all but the newest page's loads have landed.
+  auto issue = [&](int pi, int buf) __attribute__((always_inline)) {
     const bool real = pi < n_pages;
     const int p = real ? pi : 0;
     const bool in_a = p < nPA;
@@ -113,19 +117,13 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
     const bf16_t *kp = (in_a ? kA : kB) + (size_t)page * page_stride + head_off;
     const bf16_t *vp = (in_a ? vA : vB) + (size_t)page * page_stride + head_off;
     const size_t lane_off = real ? (size_t)tid * 8 : 0, step = real ? 512 * 8 : 0;
+    bf16_t *kt = lds + buf * TL::PAGE_ELEMS + wave * 512, *vt = kt + TL::K_ELEMS;
 #pragma unroll
     for (int i = 0; i < TL::CPT; ++i) {
-      sk[stage][i] = *(const v4u *)(kp + lane_off + step * i);
-      sv[stage][i] = *(const v4u *)(vp + lane_off + step * i);
-    }
-  };
-  auto commit = [&](int stage, int buf) __attribute__((always_inline)) {
-    bf16_t *kt = lds + buf * TL::PAGE_ELEMS, *vt = kt + TL::K_ELEMS;
-#pragma unroll
-    for (int i = 0; i < TL::CPT; ++i) {
-      const int ci = tid + 512 * i;
-      *(v4u *)(kt + ci * 8) = sk[stage][i];
-      *(v4u *)(vt + ci * 8) = sv[stage][i];
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(kp + lane_off + step * i),
+                                       (__attribute__((address_space(3))) void *)(kt + 4096 * i), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(vp + lane_off + step * i),
+                                       (__attribute__((address_space(3))) void *)(vt + 4096 * i), 16, 0, 0);
     }
   };
   // one 32-key block whose key 0 sits at absolute position abs0; n_valid keys exist
@@ -193,7 +191,7 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
         o[dt] = mfma32p(vf, pb[sl], o[dt]);
       }
   };
-  auto consume = [&](int pi) __attribute__((always_inline)) {
+  auto consume = [&](int pi, int buf) __attribute__((always_inline)) {
     if (!wave_active) return;
     const bool in_a = pi < nPA;
     const int abs_page = in_a ? pi * PPG : a.prefix_len + (pi - nPA) * PPG;
@@ -201,22 +199,23 @@ void prefill_attention_kernel(PrefillAttnArgs a) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int nv = min(32, keys_here - 32 * blk);
-      if (nv > 0 && abs_page + 32 * blk <= my_last) process(pi & 1, blk, nv, abs_page + 32 * blk);   // else all masked
+      if (nv > 0 && abs_page + 32 * blk <= my_last) process(buf, blk, nv, abs_page + 32 * blk);   // else all masked
     }
   };
 
-#pragma unroll
-  for (int st = 0; st < 3; ++st) issue(st, st);
-  for (int i = 0; i < n_pages; i += 3) {
-#pragma unroll
-    for (int st = 0; st < 3; ++st) {
-      const int pi = i + st;
-      commit(st, pi & 1);
-      __syncthreads();
-      issue(st, pi + 3);
-      if (pi < n_pages) consume(pi);
-    }
+  issue(0, 0);
+  issue(1, 1);
+  int buf = 0;
+  for (int pi = 0; pi < n_pages; ++pi) {
+    // page pi has landed once at most the loads of page pi + 1 are outstanding
+    if (TL::CPT == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    __syncthreads();                             // ... for every wave; and page pi - 1 is no longer read
+    issue(pi + 2, buf >= 1 ? buf - 1 : 2);       // into page pi - 1's buffer, (buf + 2) % 3
+    consume(pi, buf);
+    buf = buf == 2 ? 0 : buf + 1;
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no load into LDS outlives the workgroup
 
   if (wave_active && col_valid) {
     const float inv = 1.0f / l;                  // l > 0: every row sees at least its own key
