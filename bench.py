@@ -82,6 +82,17 @@ def measured_traffic_bytes(workload):
     return (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0
 
 
+def gate_up_kernel_name(s, n_cands):
+    """Which form of the weight-streaming layer the library picks for gate/up at this shape (the
+    rules of csrc/kernels_mfma.hip, restated for the record's label only)."""
+    if n_cands > 32:
+        return "skinny_shared_kernel" if (s.d_ffn // 32 + 3) // 4 >= 160 else "skinny_linear_kernel"
+    rows = s.d_ffn // 256
+    if s.d_ffn % 2048 == 0 and (s.d_ffn // 32) % 256 != 0 and rows <= 64:
+        return "skinny_rows_kernel"
+    return "skinny_linear_kernel"
+
+
 def gate_up_bytes(s, n_cands):
     """Algorithmic bytes of one gate/up launch: both weight matrices once, the activations in
     and the SwiGLU product out (bf16)."""
@@ -463,7 +474,7 @@ def main():
                                f"{S0 + 1}..{S0 + K} (mean {mean_len:g}; the workload's mean is {(N + 1) / 2:g}), "
                                f"T={wl.temperature}, top-k {wl.top_k}",
                    "n_cands": B, "prefix_len": P, "page_tokens": wl.page_tokens, "suffix_start": S0},
-        "roofline": {"bound": "hbm", "kernel": "skinny_rows_kernel (gate/up + SwiGLU)",
+        "roofline": {"bound": "hbm", "kernel": gate_up_kernel_name(s, B) + " (gate/up + SwiGLU)",
                      "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS,
                      "peak_measured": read_gbs, "frac_of_measured": gu_gbs / read_gbs,
                      "traffic": measured_traffic_bytes(args.workload), "algorithmic_bytes": gate_up_bytes(s, B),
