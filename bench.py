@@ -428,8 +428,10 @@ def main():
         del src, dst
 
     # timed region; a sample of the gate/up launches carries HIP events of its own (attached to the
-    # launch: begin and end of that dispatch on the session stream), about 256 launches of the run
-    stride = max(1, (s.n_layers * K) // 256)
+    # launch: begin and end of that dispatch on the session stream): about 256 launches of a long
+    # run, and never more than one per step (a bracketed launch costs the stream about 5 us: two
+    # per layer-pair of a 20-step run took 2 % off the rate), in a different layer each time
+    stride = max(s.n_layers + 1, (s.n_layers * K) // 256)
     sess.profile_begin("linear_gate_up", stride)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
