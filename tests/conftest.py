@@ -28,7 +28,8 @@ def pytest_collection_modifyitems(config, items):
 
 
 def pytest_sessionfinish(session, exitstatus):
-    """bf16 parity comparisons of this run as a table (gpurun_out/parity_bf16.md): per comparison
+    """bf16 parity comparisons of this run as a table, parity_bf16.md in the directory that the
+    environment variable MC_TEST_REPORT_DIR names (nothing is written without it): per comparison
     the device's and the noise floor's distance from the exact oracle, the bound that applied and
     the statistics with power."""
     try:
@@ -38,7 +39,9 @@ def pytest_sessionfinish(session, exitstatus):
     recs = gpu_common.PARITY_RECORDS
     if not recs:
         return
-    out_dir = os.path.join(ROOT, "gpurun_out")
+    out_dir = os.environ.get("MC_TEST_REPORT_DIR")
+    if not out_dir:
+        return
     try:
         os.makedirs(out_dir, exist_ok=True)
         with open(os.path.join(out_dir, "parity_bf16.md"), "w") as f:
