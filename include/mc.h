@@ -397,13 +397,13 @@ int mc_op_attention_decode_static(void *stream, int32_t dtype, int32_t n_cands, 
                                   void *out, int32_t out_tiled);
 
 /* Host-only: the work-item plan mc_op_attention_decode would launch for these sizes on the bf16
- * MFMA path (MC_ERR_UNSUPPORTED for shapes that path does not cover).  out8 (host): prefix items
- * incl. padding ids, suffix items, prefix key splits, 32-key blocks per prefix split, suffix key
- * splits, blocks per suffix split, partial states per (candidate, head), id distance between the
- * row blocks of one prefix split. */
+ * MFMA path (MC_ERR_UNSUPPORTED for shapes that path does not cover).  out9 (host, nine values):
+ * prefix items incl. padding ids, suffix items, prefix key splits, 32-key blocks per prefix split,
+ * suffix key splits, blocks per suffix split, partial states per (candidate, head), id distance
+ * between the items of one prefix split, blocks of 32 query rows per prefix item (1 or 4). */
 int mc_op_attention_decode_plan(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
                                 int32_t head_dim, int32_t page_tokens, int32_t prefix_len,
-                                int32_t suffix_len, int32_t prefix_splits, int32_t *out8);
+                                int32_t suffix_len, int32_t prefix_splits, int32_t *out9);
 
 /* Causal attention for many query rows (prefix prefill, candidate scoring); bf16, 64-token
  * pages, head_dim 64 or 128.  items: device int32 [n_items][4] = (first row, rows <= 64,

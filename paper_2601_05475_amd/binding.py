@@ -606,11 +606,11 @@ def op_attention_decode(q, k_prefix, v_prefix, k_suffix, v_suffix, page_table, p
 def op_attention_decode_plan(n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens, prefix_len,
                              suffix_len, prefix_splits=0):
     """Host-only: the decode-attention launch plan as a dict (no GPU work)."""
-    out = np.zeros(8, np.int32)
+    out = np.zeros(9, np.int32)
     _check(load_library().mc_op_attention_decode_plan(n_cands, n_q_heads, n_kv_heads, head_dim, page_tokens,
                                                       prefix_len, suffix_len, prefix_splits, out.ctypes.data))
     keys = ("prefix_items", "suffix_items", "splits", "blocks_per_split", "suffix_splits", "suffix_bps",
-            "n_parts", "prefix_stride")
+            "n_parts", "prefix_stride", "rb_per_item")
     return dict(zip(keys, (int(v) for v in out)))
 
 

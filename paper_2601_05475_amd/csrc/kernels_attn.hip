@@ -57,6 +57,7 @@ struct AttnItems {
   int prefix_groups, prefix_stride;          // (kv head, split) pairs; id distance between row blocks (multiple of 8)
   int suffix_splits, suffix_bps;             // suffix: key splits per (candidate, kv head), blocks per split
   int n_prefix_blocks, n_suffix_blocks, rows;   // rows = B * G
+  int rb_per_item;                           // prefix: row blocks per item, 1 (waves split the keys) or 4 (one per wave)
 };
 
 template <int HD>
@@ -80,8 +81,15 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   int kvh, part, first_blk, blk_end, len, n_cols, col0, b_item;
   const bf16_t *kpool, *vpool;
   const int32_t *table = nullptr;
+  // Many query rows per KV head (more than 7 blocks of 32): a prefix item takes four row blocks,
+  // one per wave, and every wave walks all key blocks of the item's range.  The four waves ask
+  // for the same key and value fragments at about the same time, so the range crosses the L2-to-CU
+  // path about once per item instead of once per row block, which is what bounds the kernel
+  // there; nothing is merged across waves.  With few row blocks (wave_rows false) the waves
+  // split the key blocks of one row block instead, which keeps more items in flight.
+  const bool wave_rows = is_prefix && it.rb_per_item == 4;
   if (is_prefix) {
-    const int rb = blockIdx.x / it.prefix_stride, grp = blockIdx.x % it.prefix_stride;
+    const int rbg = blockIdx.x / it.prefix_stride, grp = blockIdx.x % it.prefix_stride;
     if (grp >= it.prefix_groups) return;                       // padding id
     const int s = grp % it.splits;
     kvh = grp / it.splits;
@@ -90,8 +98,8 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     blk_end = min(first_blk + it.blocks_per_split, it.n_prefix_blocks);
     len = a.prefix_len;
     kpool = (const bf16_t *)a.k_prefix; vpool = (const bf16_t *)a.v_prefix;
-    col0 = rb * 32;
-    n_cols = min(32, it.rows - col0);
+    col0 = (wave_rows ? rbg * 4 + wave : rbg) * 32;
+    n_cols = max(0, min(32, it.rows - col0));                  // 0: a wave past the last row block idles
     b_item = -1;
   } else {
     int id = blockIdx.x - it.n_prefix_items;
@@ -110,11 +118,12 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     n_cols = G;
   }
   const bool col_valid = col < n_cols;
-  const int rho = col0 + (col_valid ? col : 0);
+  const int rho = n_cols > 0 ? col0 + (col_valid ? col : 0) : 0;   // a wave without columns reads row 0 (never stored)
   const int b_of_col = (b_item >= 0) ? b_item : rho / G;
   const int head = kvh * G + rho % G;
-  const int blk_begin = first_blk + wave;
-  const int n_mine = (blk_end - blk_begin + 3) / 4;          // <= 0: idle wave
+  const int bstep = wave_rows ? 1 : 4;                       // distance between this wave's key blocks
+  const int blk_begin = first_blk + (wave_rows ? 0 : wave);
+  const int n_mine = n_cols > 0 ? (blk_end - blk_begin + bstep - 1) / bstep : 0;   // <= 0: idle wave
 
   // ---- query fragments: B operand of S^T = K Q^T, lane (col, h) holds Q[row][16c + 8h .. +7].
   // They are parked in LDS (each lane reads back only what it wrote) to leave the registers to
@@ -140,7 +149,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   // Page ids of the next 64 blocks of this wave, one per lane; block j of the window reads lane j.
   int my_pid = 0;
   auto load_pids = [&](int w0) __attribute__((always_inline)) {
-    int g = blk_begin + (w0 + lane) * 4;
+    int g = blk_begin + (w0 + lane) * bstep;
     if (g >= blk_end) g = first_blk;                            // any valid block of the item
     my_pid = table ? table[g >> 1] : (g >> 1);
   };
@@ -155,7 +164,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   auto block_base = [&](int w0, int j, int wn, uint32_t &voff, int &n_valid) __attribute__((always_inline)) -> size_t {
     const bool real = j < wn;
     const int jj = real ? j : 0;
-    const int g = blk_begin + (w0 + jj) * 4;
+    const int g = blk_begin + (w0 + jj) * bstep;
     const int page = __builtin_amdgcn_readlane(my_pid, jj);
     voff = real ? lane * 16u : 0u;
     n_valid = len - 32 * g;
@@ -187,7 +196,7 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
     issue_k(w0, 0, wn);
     issue_v(w0, 0, wn);
     for (int j = 0; j < wn; ++j) {
-      const int n_valid = min(32, len - 32 * (blk_begin + (w0 + j) * 4));
+      const int n_valid = min(32, len - 32 * (blk_begin + (w0 + j) * bstep));
       // an offset the compiler cannot see through (always 0): the query reads stay inside the
       // loop instead of being hoisted back into 4 * NF registers
       int q_at = 0;
@@ -254,6 +263,47 @@ void decode_attention_kernel(DecodeAttnArgs a, AttnItems it, float *__restrict__
   __syncthreads();                                      // the query fragments are no longer read
   float *sm = (float *)lds_raw;                         // [4][32] m, [4][32] l, [32] merged m, [32] merged l
   float *so = sm + 320;                                 // [4][n_cols][SOLD]
+  if (wave_rows) {
+    // every wave holds the finished partial state of its own 32 columns: through LDS only to
+    // turn lane-per-column registers into row-contiguous stores
+    if (h == 0) {
+      sm[wave * 32 + col] = m;
+      sm[128 + wave * 32 + col] = l;
+    }
+    if (col_valid) {
+      float *dst = so + (size_t)(wave * 32 + col) * SOLD + 4 * h;
+#pragma unroll
+      for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+          *(float4 *)(dst + dt * 32 + 8 * r4) = make_float4(o[dt][4 * r4], o[dt][4 * r4 + 1],
+                                                            o[dt][4 * r4 + 2], o[dt][4 * r4 + 3]);
+    }
+    __syncthreads();
+    const int row0 = (int)(blockIdx.x / it.prefix_stride) * 128;      // first query row of the item
+#pragma unroll 4
+    for (int i = 0; i < HD / 8; ++i) {                  // 128 columns x HD / 4 quads, 256 per round
+      const int e = tid + 256 * i;
+      const int cg = e / (HD / 4), d = (e % (HD / 4)) * 4;
+      const int rc = row0 + cg;
+      if (rc >= it.rows) continue;
+      const float4 v = *(const float4 *)(so + (size_t)cg * SOLD + d);
+      const int bc = rc / G, hq = kvh * G + rc % G;
+      if (n_parts == 1) {
+        const float lg = sm[128 + cg];
+        const size_t at = a.out_tiled ? tiled_offset(bc, hq * HD + d, Hq * HD) : ((size_t)bc * Hq + hq) * HD + d;
+        uint2 pk;
+        pk.x = pack2_bf16(v.x / lg, v.y / lg);
+        pk.y = pack2_bf16(v.z / lg, v.w / lg);
+        *(uint2 *)((bf16_t *)a.out + at) = pk;
+        continue;
+      }
+      const size_t row = ((size_t)part * B + bc) * Hq + hq;
+      *(float4 *)(part_o + row * HD + d) = v;
+      if (d == 0) *(float2 *)(part_ml + row * 2) = make_float2(sm[cg], sm[128 + cg]);
+    }
+    return;
+  }
   if (h == 0) {
     sm[wave * 32 + col] = m;
     sm[128 + wave * 32 + col] = l;
@@ -413,10 +463,20 @@ static AttnItems plan_items(const DecodeAttnArgs &a) {
     it.blocks_per_split = (it.n_prefix_blocks + splits - 1) / splits;
     splits = (it.n_prefix_blocks + it.blocks_per_split - 1) / it.blocks_per_split;   // drop empty splits
   }
+  // many row blocks: four per item (one per wave), and key splits for about 384 items
+  it.rb_per_item = it.row_blocks >= 8 ? 4 : 1;
+  const int rb_groups = (it.row_blocks + it.rb_per_item - 1) / it.rb_per_item;
+  if (it.rb_per_item == 4 && it.n_prefix_blocks > 0) {
+    const int max_splits = (it.n_prefix_blocks + 3) / 4;
+    splits = a.prefix_splits > 0 ? a.prefix_splits : (384 + a.n_kv_heads * rb_groups - 1) / (a.n_kv_heads * rb_groups);
+    splits = std::max(1, std::min(splits, max_splits));
+    it.blocks_per_split = (it.n_prefix_blocks + splits - 1) / splits;
+    splits = (it.n_prefix_blocks + it.blocks_per_split - 1) / it.blocks_per_split;
+  }
   it.splits = splits;
   it.prefix_groups = a.n_kv_heads * splits;
   it.prefix_stride = (it.prefix_groups + 7) / 8 * 8;
-  it.n_prefix_items = (splits > 0) ? it.prefix_stride * it.row_blocks : 0;
+  it.n_prefix_items = (splits > 0) ? it.prefix_stride * rb_groups : 0;
   // suffix: the same share per wave
   int ssplits = 1;
   it.suffix_bps = 0;
@@ -484,14 +544,15 @@ static int launch_decode_attention_t(hipStream_t st, const DecodeAttnArgs &a, co
 
 // The launch plan as numbers, for host-side checks: {prefix items (with padding ids), suffix
 // items, prefix splits, blocks per prefix split, suffix splits, blocks per suffix split, partial
-// states per (candidate, head), prefix id stride}.
-int decode_attention_plan(const DecodeAttnArgs &a, int32_t out[8]) {
+// states per (candidate, head), prefix id stride, row blocks per prefix item}.
+int decode_attention_plan(const DecodeAttnArgs &a, int32_t out[9]) {
   if (!decode_attention_mfma_supported(a)) MC_FAIL(MC_ERR_UNSUPPORTED, "decode attention: shape not covered");
   const AttnItems it = plan_items(a);
   out[0] = it.n_prefix_items; out[1] = it.n_suffix_items; out[2] = it.splits; out[3] = it.blocks_per_split;
   out[4] = it.suffix_splits; out[5] = it.suffix_bps;
   out[6] = (a.prefix_len > 0 ? it.splits : 0) + (a.suffix_len > 0 ? it.suffix_splits : 0);
   out[7] = it.prefix_stride;
+  out[8] = it.rb_per_item;
   return MC_OK;
 }
 

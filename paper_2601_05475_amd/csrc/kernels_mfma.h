@@ -134,6 +134,6 @@ bool decode_attention_mfma_supported(const DecodeAttnArgs &a);
 size_t decode_attention_mfma_ws_bytes(int n_cands, int Hq, int Hkv, int hd, int prefix_len,
                                       int suffix_len, int page_tokens);
 int launch_attention_decode_mfma(hipStream_t st, const DecodeAttnArgs &a);
-int decode_attention_plan(const DecodeAttnArgs &a, int32_t out[8]);
+int decode_attention_plan(const DecodeAttnArgs &a, int32_t out[9]);
 
 }  // namespace mc

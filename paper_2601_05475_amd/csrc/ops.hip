@@ -343,15 +343,15 @@ extern "C" int mc_op_attention_decode_static(void *stream, int32_t dtype, int32_
 
 extern "C" int mc_op_attention_decode_plan(int32_t n_cands, int32_t n_q_heads, int32_t n_kv_heads,
                                            int32_t head_dim, int32_t page_tokens, int32_t prefix_len,
-                                           int32_t suffix_len, int32_t prefix_splits, int32_t *out8) {
-  if (!out8 || n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || prefix_len < 0 ||
+                                           int32_t suffix_len, int32_t prefix_splits, int32_t *out9) {
+  if (!out9 || n_cands < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || prefix_len < 0 ||
       suffix_len < 0 || prefix_len + suffix_len < 1 || prefix_splits < 0)
     MC_FAIL(MC_ERR_INVALID, "bad sizes");
   DecodeAttnArgs a{};
   a.n_cands = n_cands; a.n_q_heads = n_q_heads; a.n_kv_heads = n_kv_heads; a.head_dim = head_dim;
   a.page_tokens = page_tokens; a.prefix_len = prefix_len; a.suffix_len = suffix_len;
   a.prefix_splits = prefix_splits;
-  return decode_attention_plan(a, out8);
+  return decode_attention_plan(a, out9);
 }
 
 extern "C" int mc_op_read_probe(void *stream, const void *buf, size_t bytes, void *out_word) {

@@ -94,7 +94,7 @@ def test_invalid_configs_are_rejected(lib):
     assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 128, 64, 4096, 5e5, 100, *([None] * 9)) == -1
     assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 126, 64, 4096, 5e5, 100, *args) == -1   # head_dim % 4
     assert lib.mc_op_linear_qkv_rope(None, 32, 32, 8, 128, 64, 4096, -1.0, 100, *args) == -1
-    out = (C.c_int32 * 8)()
+    out = (C.c_int32 * 9)()
     assert lib.mc_op_attention_decode_plan(32, 32, 8, 128, 64, 4096, 1, 0, out) == 0 and out[2] >= 1
     assert lib.mc_op_attention_decode_plan(32, 32, 8, 128, 64, 0, 0, 0, out) == -1           # no keys
     assert lib.mc_op_attention_decode_plan(32, 32, 7, 128, 64, 4096, 1, 0, out) == -1        # heads do not divide
@@ -119,8 +119,9 @@ def test_decode_attention_plan_covers_every_block_and_fits_its_workspace(lib):
             assert p["splits"] >= 1 and p["splits"] * p["blocks_per_split"] >= nb_p
             assert (p["splits"] - 1) * p["blocks_per_split"] < nb_p
             row_blocks = -(-B * G // 32)
+            assert p["rb_per_item"] == (4 if row_blocks >= 8 else 1)
             assert p["prefix_stride"] % 8 == 0 and p["prefix_stride"] >= Hkv * p["splits"]
-            assert p["prefix_items"] == p["prefix_stride"] * row_blocks
+            assert p["prefix_items"] == p["prefix_stride"] * -(-row_blocks // p["rb_per_item"])
         else:
             assert p["prefix_items"] == 0
         if t:

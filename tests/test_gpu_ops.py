@@ -225,6 +225,8 @@ def test_attention_decode_candidates_of_different_lengths(dtype, B, Hq, Hkv, hd,
     (50, 32, 8, 128, 1000, 70, 3),       # 7 row blocks (the last of 8 rows), last page of 40 keys
     (64, 32, 2, 64, 200, 33, 17),        # head_dim 64, 32 row blocks, last page of 8 keys
     (48, 16, 4, 128, 130, 5, 1),         # 6 row blocks, 3 pages (the last with 2 keys)
+    (64, 32, 8, 128, 100, 0, 3),         # 8 row blocks, one key split, no suffix: every item writes its outputs itself
+    (72, 32, 8, 128, 700, 40, 5),        # 9 row blocks: three items of 4, 4 and 1 row blocks per KV head and split
 ])
 def test_attention_decode_mfma_shapes(B, Hq, Hkv, hd, P, t, stride):
     worst, _, _ = attention_case("bf16", B, Hq, Hkv, hd, 64, P, t, stride=stride)
