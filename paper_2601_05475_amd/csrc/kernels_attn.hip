@@ -13,6 +13,8 @@
 //     (row = b * G + g, G = query heads per KV head).  The items of one (kv head, split) differ
 //     in rb only and are numbered a multiple of 8 apart: workgroups are dealt round-robin to the
 //     8 XCDs, so they share one L2 and the keys come from HBM once.
+//     With eight or more row blocks per KV head an item takes four of them instead, one per wave:
+//     every wave walks all blocks of the range and nothing is merged across waves.
 //   suffix item (candidate b, kv head, key split): columns are b's G query heads.
 // Every item leaves an un-normalised partial (max m, sum l, weighted values o) per query head;
 // a second small kernel merges the partials of each (candidate, head) and writes bf16.  (An item
