@@ -40,10 +40,10 @@ TRAFFIC_GATE_UP = {"fetch_kib": 115760.5, "fetch_scale": 2.0, "write_kib": 896.0
 
 # Decode attention + merge at suffix lengths 255..258 (the same two counter runs: four timed steps
 # sit at the middle of the 512-step workload, whose average suffix length is 256.5).
-TRAFFIC_ATTN = {"fetch_kib": 26420.7, "merge_fetch_kib": 2922.0, "write_kib": 4680.0, "merge_write_kib": 256.0,
+TRAFFIC_ATTN = {"fetch_kib": 26427.5, "merge_fetch_kib": 2922.0, "write_kib": 4680.0, "merge_write_kib": 256.0,
                 "fetch_scale": 2.0, "write_scale": 1.0, "suffix_len": 256.5,
                 "source": "paper_2601_05475_amd/csrc/kernels_attn.hip",
-                "sha256": "6263e84a74fe8acd744093cd54ad39e9e5c8cfb686b74682ad332d4754d4f328"}
+                "sha256": "0ab99c8fa2d8bfba6214bf19266d40b3861557b3f9ebbff542f3b9bf4a2434f7"}
 
 
 def measured_attention_traffic_bytes(workload, mean_suffix_len):

@@ -471,6 +471,8 @@ static AttnItems plan_items(const DecodeAttnArgs &a) {
   if (it.rb_per_item == 4 && it.n_prefix_blocks > 0) {
     const int max_splits = (it.n_prefix_blocks + 3) / 4;
     splits = a.prefix_splits > 0 ? a.prefix_splits : (384 + a.n_kv_heads * rb_groups - 1) / (a.n_kv_heads * rb_groups);
+    // 16 partial states per row are what the merge kernel fetches in one batch: leave one to the suffix
+    if (a.prefix_splits <= 0 && a.suffix_len > 0 && splits == 16) splits = 15;
     splits = std::max(1, std::min(splits, max_splits));
     it.blocks_per_split = (it.n_prefix_blocks + splits - 1) / splits;
     splits = (it.n_prefix_blocks + it.blocks_per_split - 1) / it.blocks_per_split;
