@@ -75,9 +75,9 @@ def plan(name: str):
     elif name == "8b-twin":
         rows = [(b, t) for b in range(B) for t in (1, 2, pg - 1, pg, pg + 1, 2 * pg, 2 * pg + 1, N // 2, N // 2 + 1, N - 1, N)]
     elif name == "8b-rerank":
-        # four of the 64 suffixes at full depth (each costs the oracle 14 TFLOP and 1.7e10 softmax
+        # eight of the 64 suffixes at full depth (each costs the oracle 14 TFLOP and 1.7e10 softmax
         # elements per precision); the two-layer twin covers all 64
-        rows = [(b, N) for b in (0, 22, 40, 63)]
+        rows = [(b, N) for b in (0, 9, 22, 31, 40, 47, 54, 63)]
     elif name == "8b-rerank-twin":
         rows = [(b, N) for b in range(B)]
     elif name == "32b":

@@ -202,7 +202,7 @@ def run_rerank_workload(variant, s, wl, g, what):
 @pytest.mark.timeout(900)
 def test_8b_rerank_workload_full_depth():
     """Workload 4 as specified: all 64 suffixes of 1024 tokens are scored on the 4096-token
-    prefix at 32 layers; four of them are compared with the oracle (final-position logits, reward
+    prefix at 32 layers; eight of them are compared with the oracle (final-position logits, reward
     log-probs, relative order)."""
     g = load_golden("8b-rerank")
     wl = synth.WORKLOADS["8b-rerank"]
