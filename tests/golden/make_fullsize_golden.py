@@ -52,9 +52,9 @@ VARIANTS = {
     "8b-rerank-twin": ("8b-rerank", 2, None, 2048),
     # full depth costs the float64 oracle 2.4 PFLOP and 1.4e12 softmax elements at the workload's
     # 16384-token prefix (more than a day on the 8-core host that writes these files): the
-    # full-depth file is cut to a 2048-token prefix, 8 candidates at steps 1 and 2 and two that
-    # cross a page; the two-layer twin keeps all 16384 prefix tokens, 64 candidates, 1024 steps
-    "32b": ("32b", None, 2048, 2048),
+    # full-depth file is cut to a 4096-token prefix (2.6 hours), 8 candidates at steps 1 and 2 and
+    # two that cross a page; the two-layer twin keeps all 16384 prefix tokens, 64 candidates, 1024 steps
+    "32b": ("32b", None, 4096, 2048),
     "32b-twin": ("32b", 2, None, 1024),
 }
 

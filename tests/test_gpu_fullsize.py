@@ -220,11 +220,12 @@ def test_8b_rerank_workload_two_layer_twin():
 @pytest.mark.timeout(1500)
 def test_32b_workload_full_depth_on_a_shortened_prefix():
     """Workload 5 at full depth (64 layers, vocabulary 152064, 64 candidates, session sized for the
-    16384-token prefix and 1024 steps) on the first 2048 prefix tokens, the length the oracle
-    could be run at: eight candidates at steps 1 and 2, two across a page boundary."""
+    16384-token prefix and 1024 steps) on the first prefix tokens, as many as the oracle could be
+    run at (the stored file says how many): eight candidates at steps 1 and 2, two across a page
+    boundary."""
     g = load_golden("32b")
     wl = synth.WORKLOADS["32b"]
-    run_decode_workload("32b", wl.shape, wl, g, "32b full depth, prefix 2048")
+    run_decode_workload("32b", wl.shape, wl, g, f"32b full depth, prefix {g['meta']['prefix_len']}")
 
 
 @pytest.mark.timeout(1500)
